@@ -1,0 +1,1 @@
+"""ICaRus shared-KV layer step for MI355X (gfx950): Python binding over the C-ABI library."""
