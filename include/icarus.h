@@ -1,0 +1,177 @@
+/*
+ * icarus.h -- C ABI of the ICaRus shared-KV layer step for MI355X (gfx950).
+ *
+ * One transformer layer of the paper's multi-model decode/prefill path: a frozen
+ * logical encoder (the base weights) is the only writer of a paged KV cache
+ * (Eq. 4); M task-specific logical decoders (the same base weights plus one LoRA
+ * adapter each) only issue queries against that cache (Eq. 5).  At decode the
+ * encoder row and the decoder rows of every sequence run side by side in one
+ * batched pass (Sec. 3.3, Alg. 2 and Alg. 3).
+ *
+ * Conventions
+ *  - Every call returns an icarus_status (0 = OK), never throws, never aborts;
+ *    icarus_last_error() gives the message of the last failure on that context
+ *    (or of the last failed icarus_create when ctx is NULL).
+ *  - The CALLER owns all device memory (weights, KV pool, block tables,
+ *    activations, workspace).  The library allocates no device memory, frees
+ *    nothing of the caller's, and enqueues all work on the caller's stream
+ *    without synchronising it.  It keeps a small ring of pinned HOST staging
+ *    buffers for per-call metadata.
+ *  - "host" / "device" after a pointer says where the memory lives.
+ *  - Small integer metadata (lengths, row lists) is passed as HOST arrays so it
+ *    can be validated; block tables are DEVICE int32 [S, max_blocks].
+ *  - dtype selects the storage type of weights, activations and cache:
+ *    ICARUS_BF16 (2 bytes, arithmetic on bf16 MFMA with fp32 accumulation) or
+ *    ICARUS_F32 (4 bytes, fp32 vector arithmetic).
+ *  - Base weights W_p are [out_p, in_p] row-major.  LoRA A_p is
+ *    [n_models, r, in_p], B_p is [n_models, out_p, r]; the adapter delta is
+ *    lora_scale * B (A x) on the layer INPUT x (Alg. 2, read as standard LoRA).
+ *    Adapters for K and V may be supplied but are never read: K and V come from
+ *    the encoder row with base weights only (Alg. 3; App. C).
+ *  - All pointers must be 16-byte aligned; head_dim must be even.
+ *
+ * KV pool layout (part of the ABI): element type = dtype,
+ *     pool[num_blocks][n_kv_heads][2][block_size * head_dim]
+ *   plane 0 holds K of the block as [block_size][head_dim] (token-major),
+ *   plane 1 holds V of the block TRANSPOSED as [head_dim][block_size],
+ * so that one (block, kv-head) is one contiguous run of 2*block_size*head_dim
+ * elements and both planes load straight into matrix-core operand registers.
+ * K is stored after RoPE (and after QK-RMSNorm when enabled).
+ * Logical position p of sequence s lives in block block_table[s][p / block_size]
+ * at in-block offset p % block_size; its "slot" is block * block_size + offset.
+ */
+#ifndef ICARUS_H
+#define ICARUS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum icarus_status {
+    ICARUS_OK = 0,
+    ICARUS_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad enum */
+    ICARUS_ERR_SHAPE = 2,       /* config fields inconsistent (heads, dims, rank) */
+    ICARUS_ERR_ALIGNMENT = 3,   /* a pointer is not 16-byte aligned */
+    ICARUS_ERR_MODEL_ID = 4,    /* model id out of range or duplicated in a sequence */
+    ICARUS_ERR_ROW_ORDER = 5,   /* rows not grouped by sequence / encoder row missing or not first */
+    ICARUS_ERR_CAPACITY = 6,    /* block table, max_position or workspace too small */
+    ICARUS_ERR_UNSUPPORTED = 7, /* shape outside what the kernels cover */
+    ICARUS_ERR_HIP = 8          /* a HIP runtime call failed (message has the HIP error) */
+} icarus_status;
+
+enum { ICARUS_F32 = 0, ICARUS_BF16 = 1 };
+
+/* Projection indices for the weight arrays and for lora_target_mask bits. */
+enum { ICARUS_PROJ_Q = 0, ICARUS_PROJ_K, ICARUS_PROJ_V, ICARUS_PROJ_O,
+       ICARUS_PROJ_GATE, ICARUS_PROJ_UP, ICARUS_PROJ_DOWN, ICARUS_NPROJ };
+
+typedef struct icarus_layer_config {
+    int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ffn;
+    int32_t block_size;       /* tokens per KV block (16 in every benchmark config) */
+    int32_t num_blocks;       /* blocks in the pool; block ids are 0..num_blocks-1 */
+    int32_t n_models;         /* M: adapters loaded (0 = base model only) */
+    int32_t lora_rank;        /* r */
+    int32_t lora_target_mask; /* bit p set: projection p carries an adapter (K, V bits ignored) */
+    int32_t dtype;            /* ICARUS_F32 or ICARUS_BF16 */
+    int32_t qk_norm;          /* 1: per-head RMSNorm on q and k before RoPE */
+    int32_t max_position;     /* largest position + 1 any call may touch */
+    int32_t reserved;
+    double rope_theta;        /* RoPE base; rotate-half pairing (i, i + head_dim/2) */
+    double rms_eps;
+    double lora_scale;        /* s = alpha / r */
+} icarus_layer_config;
+
+typedef struct icarus_base_weights { /* all DEVICE, dtype elements */
+    const void *w[ICARUS_NPROJ];       /* W_q [Hq*D, d], W_k, W_v [Hkv*D, d], W_o [d, Hq*D],
+                                          W_gate, W_up [F, d], W_down [d, F] */
+    const void *norm_attn, *norm_ffn;  /* [d] RMSNorm weights before attention / before the FFN */
+    const void *q_norm, *k_norm;       /* [D], read only when qk_norm */
+} icarus_base_weights;
+
+typedef struct icarus_lora_weights { /* all DEVICE, dtype elements; NULL where not targeted */
+    const void *A[ICARUS_NPROJ];       /* [n_models, r, in_p]  */
+    const void *B[ICARUS_NPROJ];       /* [n_models, out_p, r] */
+} icarus_lora_weights;
+
+typedef struct icarus_ctx icarus_ctx;
+
+/* Create a layer context: validates the configuration and keeps the (caller-owned)
+ * weight pointers.  Host work only; no device is touched.  lora may be NULL when
+ * n_models == 0.  On failure *out = NULL and icarus_last_error(NULL) has the reason. */
+icarus_status icarus_create(const icarus_layer_config *cfg, const icarus_base_weights *base,
+                            const icarus_lora_weights *lora, icarus_ctx **out);
+void icarus_destroy(icarus_ctx *ctx);
+const char *icarus_last_error(const icarus_ctx *ctx);
+
+/* Device workspace, in bytes, sufficient for any call with at most max_rows rows
+ * (decode: R; prefill: sum of chunk lengths), max_seqs sequences, and contexts of
+ * at most max_ctx tokens (after the call's appends).  0 on invalid arguments. */
+size_t icarus_workspace_bytes(const icarus_ctx *ctx, int32_t max_rows, int32_t max_seqs, int32_t max_ctx);
+
+/* Host-only checks of a decode batch (what icarus_decode_step checks before it
+ * launches anything): rows grouped by sequence in increasing sequence order, exactly
+ * one encoder row (model -1) first in each group, decoder model ids in range and not
+ * repeated within a sequence, every sequence's block table long enough for position
+ * ctx_lens[s], positions below max_position. */
+icarus_status icarus_validate_decode(icarus_ctx *ctx, int32_t max_blocks, int32_t S,
+                                     const int32_t *ctx_lens /*host [S]*/, int32_t R,
+                                     const int32_t *row_seq /*host [R]*/,
+                                     const int32_t *row_model /*host [R]*/);
+
+/* Prefill of the logical encoder (Alg. 1; Sec. 3.3: prefill uses the encoder only).
+ * Sequence s appends chunk_lens[s] new rows at positions ctx_lens[s] .. ctx_lens[s] +
+ * chunk_lens[s] - 1 of its (possibly non-empty) paged prefix.  K (after RoPE) and V
+ * of every new row are written to the pool with base weights only; the row at chunk
+ * offset i attends to positions 0 .. ctx_lens[s] + i; then W_o, the residual and the
+ * SwiGLU FFN give x_out.  Rows of x_in / x_out / slot_out are ordered by sequence,
+ * then by chunk offset.
+ *   kv_pool           device, mutated only at the new slots
+ *   block_tables      device int32 [S, max_blocks]
+ *   x_in              device [sum T, d_model]
+ *   x_out             device [sum T, d_model], or NULL to write the cache only
+ *   slot_out          device int64 [sum T] or NULL: slot written for each row
+ *   workspace         device, >= icarus_workspace_bytes(ctx, sum T, S, max(ctx+chunk)) */
+icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *block_tables,
+                                int32_t max_blocks, int32_t S, const int32_t *ctx_lens /*host*/,
+                                const int32_t *chunk_lens /*host*/, const void *x_in, void *x_out,
+                                int64_t *slot_out, void *workspace, size_t workspace_bytes,
+                                void *stream /* hipStream_t */);
+
+/* One decode step of one layer (Alg. 3 with ICaRusLinear, Alg. 2), one token per row.
+ * Rows are grouped by sequence; the first row of a group is the logical encoder
+ * (row_model -1), followed by that sequence's active decoders (row_model 0..M-1,
+ * distinct; none is legal and gives a plain base-model step).  For sequence s, with
+ * p = ctx_lens[s] tokens already cached: the encoder row's K, V (base weights) are
+ * appended at position p; every row's query (base + its adapter) attends once to
+ * positions 0..p of the shared cache; then W_o, residual, SwiGLU FFN, residual, each an
+ * ICaRusLinear.  x_in is not modified.
+ *   slot_out          device int64 [S] or NULL: slot written for each sequence      */
+icarus_status icarus_decode_step(icarus_ctx *ctx, void *kv_pool, const int32_t *block_tables,
+                                 int32_t max_blocks, int32_t S, const int32_t *ctx_lens /*host*/,
+                                 int32_t R, const int32_t *row_seq /*host*/,
+                                 const int32_t *row_model /*host*/, const void *x_in /*[R,d]*/,
+                                 void *x_out /*[R,d]*/, int64_t *slot_out, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
+/* Shared-KV attention alone (the GQA line of Alg. 3; Sec. 3.3: the streams' queries are
+ * concatenated on the head axis so that the cache is read once).  q [R, Hq, D] is
+ * already normed and rotated; rows are grouped by sequence (any number >= 1 per
+ * sequence, row_seq non-decreasing); kv_lens[s] INCLUDES the current token.  Head h of
+ * every row uses kv-head h / (Hq/Hkv).  out [R, Hq, D] = softmax(q K^T / sqrt(D)) V. */
+icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *kv_pool,
+                                    const int32_t *block_tables, int32_t max_blocks, int32_t S,
+                                    const int32_t *kv_lens /*host*/, int32_t R,
+                                    const int32_t *row_seq /*host*/, void *out, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
+/* Kernel selection for tests and measurements: 0 = automatic (matrix-core kernels
+ * where the shape allows, default), 1 = force the generic vector kernels. */
+icarus_status icarus_set_kernel_mode(icarus_ctx *ctx, int32_t mode);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ICARUS_H */

@@ -1,0 +1,256 @@
+"""Python binding over libicarus.so: argument marshalling only.
+
+Every step of the layer runs in the library's gfx950 kernels; torch is used for device
+memory and streams.  Function names mirror the C ABI (include/icarus.h).  If the library
+is missing this module raises at import time: there is no CPU or eager fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libicarus.so")
+
+PROJ = ("q", "k", "v", "o", "gate", "up", "down")
+NPROJ = 7
+F32, BF16 = 0, 1
+
+STATUS = {0: "OK", 1: "INVALID_ARG", 2: "SHAPE", 3: "ALIGNMENT", 4: "MODEL_ID", 5: "ROW_ORDER",
+          6: "CAPACITY", 7: "UNSUPPORTED", 8: "HIP"}
+
+EXPORTS = ("icarus_create", "icarus_destroy", "icarus_last_error", "icarus_workspace_bytes",
+           "icarus_validate_decode", "icarus_prefill_kv", "icarus_decode_step", "icarus_attn_shared_kv",
+           "icarus_set_kernel_mode")
+
+
+class IcarusError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"icarus status {status} ({STATUS.get(status, '?')}): {message}")
+        self.status = status
+        self.status_name = STATUS.get(status, "?")
+
+
+class _Cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "block_size", "num_blocks", "n_models",
+        "lora_rank", "lora_target_mask", "dtype", "qk_norm", "max_position", "reserved")] + [
+        ("rope_theta", C.c_double), ("rms_eps", C.c_double), ("lora_scale", C.c_double)]
+
+
+class _Base(C.Structure):
+    _fields_ = [("w", C.c_void_p * NPROJ), ("norm_attn", C.c_void_p), ("norm_ffn", C.c_void_p),
+                ("q_norm", C.c_void_p), ("k_norm", C.c_void_p)]
+
+
+class _Lora(C.Structure):
+    _fields_ = [("A", C.c_void_p * NPROJ), ("B", C.c_void_p * NPROJ)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_13281_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    lib.icarus_create.restype = C.c_int
+    lib.icarus_create.argtypes = [C.POINTER(_Cfg), C.POINTER(_Base), C.POINTER(_Lora), C.POINTER(vp)]
+    lib.icarus_destroy.restype = None
+    lib.icarus_destroy.argtypes = [vp]
+    lib.icarus_last_error.restype = C.c_char_p
+    lib.icarus_last_error.argtypes = [vp]
+    lib.icarus_workspace_bytes.restype = sz
+    lib.icarus_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.icarus_validate_decode.restype = C.c_int
+    lib.icarus_validate_decode.argtypes = [vp, i32, i32, vp, i32, vp, vp]
+    lib.icarus_prefill_kv.restype = C.c_int
+    lib.icarus_prefill_kv.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.icarus_decode_step.restype = C.c_int
+    lib.icarus_decode_step.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.icarus_attn_shared_kv.restype = C.c_int
+    lib.icarus_attn_shared_kv.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+    lib.icarus_set_kernel_mode.restype = C.c_int
+    lib.icarus_set_kernel_mode.argtypes = [vp, i32]
+    return lib
+
+
+_lib = _load()
+
+
+def lib():
+    return _lib
+
+
+@dataclass
+class LayerConfig:
+    d_model: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    d_ffn: int
+    block_size: int
+    num_blocks: int
+    n_models: int = 0
+    lora_rank: int = 0
+    lora_target_mask: int = 0
+    bf16: bool = True
+    qk_norm: bool = False
+    max_position: int = 1 << 17
+    rope_theta: float = 5e5
+    rms_eps: float = 1e-5
+    lora_scale: float = 2.0
+
+    def _c(self) -> _Cfg:
+        return _Cfg(self.d_model, self.n_q_heads, self.n_kv_heads, self.head_dim, self.d_ffn, self.block_size,
+                    self.num_blocks, self.n_models, self.lora_rank, self.lora_target_mask,
+                    BF16 if self.bf16 else F32, int(self.qk_norm), self.max_position, 0,
+                    float(self.rope_theta), float(self.rms_eps), float(self.lora_scale))
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.bf16 else torch.float32
+
+    def pool_shape(self):
+        """[num_blocks, n_kv_heads, 2, block_size*head_dim]: plane 0 = K [Bk, D], plane 1 = V^T [D, Bk]."""
+        return (self.num_blocks, self.n_kv_heads, 2, self.block_size * self.head_dim)
+
+
+def _ptr(t) -> C.c_void_p:
+    if t is None:
+        return C.c_void_p(0)
+    if isinstance(t, torch.Tensor):
+        assert t.is_contiguous(), "tensors passed to the library must be contiguous"
+        return C.c_void_p(t.data_ptr())
+    if isinstance(t, np.ndarray):
+        return C.c_void_p(t.ctypes.data)
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    raise TypeError(type(t))
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+class IcarusLayer:
+    """One layer context.  base / lora hold torch tensors (device, storage dtype) the caller owns;
+    this object keeps references so that they outlive the context.
+
+    base: dict "q","k","v","o","gate","up","down" -> [out,in]; "norm_attn","norm_ffn" -> [d];
+          "q_norm","k_norm" -> [D] when qk_norm.
+    lora: dict p -> (A [M,r,in_p], B [M,out_p,r]) or None.
+    """
+
+    def __init__(self, cfg: LayerConfig, base: dict, lora: dict | None = None):
+        self.cfg = cfg
+        self._refs = []
+        cb = _Base()
+        for i, p in enumerate(PROJ):
+            cb.w[i] = self._keep(base[p])
+        for name in ("norm_attn", "norm_ffn", "q_norm", "k_norm"):
+            if base.get(name) is not None:
+                setattr(cb, name, self._keep(base[name]))
+        cl = _Lora()
+        if lora:
+            for i, p in enumerate(PROJ):
+                if lora.get(p) is not None:
+                    cl.A[i] = self._keep(lora[p][0])
+                    cl.B[i] = self._keep(lora[p][1])
+        cc = cfg._c()
+        h = C.c_void_p()
+        rc = _lib.icarus_create(C.byref(cc), C.byref(cb), C.byref(cl), C.byref(h))
+        if rc != 0:
+            raise IcarusError(rc, _lib.icarus_last_error(None).decode())
+        self._h = h
+        self._ws = None
+
+    def _keep(self, t):
+        if isinstance(t, torch.Tensor):
+            assert t.is_contiguous()
+            self._refs.append(t)
+            return t.data_ptr()
+        return int(t)  # raw address (host-only validation tests)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.icarus_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != 0:
+            raise IcarusError(rc, _lib.icarus_last_error(self._h).decode())
+
+    # -- C ABI mirrors ---------------------------------------------------------------
+    def set_kernel_mode(self, mode: int):
+        self._check(_lib.icarus_set_kernel_mode(self._h, mode))
+
+    def workspace_bytes(self, max_rows: int, max_seqs: int, max_ctx: int) -> int:
+        return int(_lib.icarus_workspace_bytes(self._h, max_rows, max_seqs, max_ctx))
+
+    def validate_decode(self, max_blocks, ctx_lens, row_seq, row_model):
+        ctx_lens, row_seq, row_model = _host_i32(ctx_lens), _host_i32(row_seq), _host_i32(row_model)
+        self._check(_lib.icarus_validate_decode(self._h, max_blocks, len(ctx_lens), _ptr(ctx_lens), len(row_seq),
+                                                _ptr(row_seq), _ptr(row_model)))
+
+    def _workspace(self, rows, seqs, max_ctx, device):
+        need = self.workspace_bytes(rows, seqs, max_ctx)
+        if self._ws is None or self._ws.numel() < need or self._ws.device != device:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=device)
+        return self._ws
+
+    @staticmethod
+    def _stream(device):
+        return C.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+    def prefill_kv(self, kv_pool, block_tables, ctx_lens, chunk_lens, x_in, x_out=None, slot_out=None,
+                   workspace=None, want_out=True):
+        ctx_lens, chunk_lens = _host_i32(ctx_lens), _host_i32(chunk_lens)
+        S, max_blocks = block_tables.shape
+        total = int(chunk_lens.sum())
+        if want_out and x_out is None:
+            x_out = torch.empty_like(x_in)
+        if not want_out:
+            x_out = None
+        max_ctx = int((ctx_lens + chunk_lens).max()) if S else 0
+        ws = workspace if workspace is not None else self._workspace(total, S, max_ctx, x_in.device)
+        self._check(_lib.icarus_prefill_kv(self._h, _ptr(kv_pool), _ptr(block_tables), max_blocks, S, _ptr(ctx_lens),
+                                           _ptr(chunk_lens), _ptr(x_in), _ptr(x_out), _ptr(slot_out), _ptr(ws),
+                                           ws.numel(), self._stream(x_in.device)))
+        return x_out
+
+    def decode_step(self, kv_pool, block_tables, ctx_lens, row_seq, row_model, x_in, x_out=None, slot_out=None,
+                    workspace=None):
+        ctx_lens, row_seq, row_model = _host_i32(ctx_lens), _host_i32(row_seq), _host_i32(row_model)
+        S, max_blocks = block_tables.shape
+        R = len(row_seq)
+        if x_out is None:
+            x_out = torch.empty_like(x_in)
+        max_ctx = int(ctx_lens.max()) + 1 if S else 0
+        ws = workspace if workspace is not None else self._workspace(R, S, max_ctx, x_in.device)
+        self._check(_lib.icarus_decode_step(self._h, _ptr(kv_pool), _ptr(block_tables), max_blocks, S, _ptr(ctx_lens),
+                                            R, _ptr(row_seq), _ptr(row_model), _ptr(x_in), _ptr(x_out), _ptr(slot_out),
+                                            _ptr(ws), ws.numel(), self._stream(x_in.device)))
+        return x_out
+
+    def attn_shared_kv(self, q, kv_pool, block_tables, kv_lens, row_seq, out=None, workspace=None):
+        kv_lens, row_seq = _host_i32(kv_lens), _host_i32(row_seq)
+        S, max_blocks = block_tables.shape
+        R = len(row_seq)
+        if out is None:
+            out = torch.empty_like(q)
+        max_ctx = int(kv_lens.max()) if S else 0
+        ws = workspace if workspace is not None else self._workspace(R, S, max_ctx, q.device)
+        self._check(_lib.icarus_attn_shared_kv(self._h, _ptr(q), _ptr(kv_pool), _ptr(block_tables), max_blocks, S,
+                                               _ptr(kv_lens), R, _ptr(row_seq), _ptr(out), _ptr(ws), ws.numel(),
+                                               self._stream(q.device)))
+        return out

@@ -1,0 +1,312 @@
+// Generic vector kernels for the ICaRus layer step: any shape, storage type float32 or
+// bfloat16, fp32 accumulation.  They serve the fp32 configuration and every shape the
+// matrix-core kernels do not cover.
+#include "device_util.h"
+#include "kernels.h"
+
+namespace icarus {
+
+#define DISPATCH_T(bf16, ...)                         \
+    do {                                              \
+        if (bf16) { typedef bf16_t T; __VA_ARGS__; }  \
+        else      { typedef float T;  __VA_ARGS__; }  \
+    } while (0)
+
+// ------------------------------------------------------------------ RMSNorm
+template <typename T>
+__global__ void __launch_bounds__(256) k_rmsnorm(const T *__restrict__ x, const T *__restrict__ w, T *__restrict__ y,
+                                                 int n, float eps) {
+    __shared__ float red[16];
+    const T *xr = x + (size_t)blockIdx.x * n;
+    T *yr = y + (size_t)blockIdx.x * n;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) { float v = Elem<T>::ld(xr + i); ss += v * v; }
+    ss = block_sum(ss, red);
+    float inv = rsqrtf(ss / (float)n + eps);
+    for (int i = threadIdx.x; i < n; i += blockDim.x)
+        Elem<T>::st(yr + i, Elem<T>::ld(xr + i) * inv * Elem<T>::ld(w + i));
+}
+
+hipError_t launch_rmsnorm(const Dims &dm, const void *x, const void *w, void *y, int R, int n, hipStream_t st) {
+    if (R <= 0) return hipSuccess;
+    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_rmsnorm<T>, dim3(R), dim3(256), 0, st, (const T *)x, (const T *)w, (T *)y, n, dm.eps));
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ GEMM  Y = X W^T  (fp32 out)
+// 64x64 output tile per 256-thread block, 4x4 outputs per thread, K staged 16 at a time in LDS.
+template <typename T>
+__global__ void __launch_bounds__(256) k_gemm_generic(const T *__restrict__ X, int ldx, const T *__restrict__ W,
+                                                      int M, int N, int K, float *__restrict__ Y, int ldy) {
+    __shared__ float Xs[16][65];
+    __shared__ float Ws[16][65];
+    int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        for (int e = threadIdx.x; e < 64 * 16; e += 256) {
+            int rr = e >> 4, kk = e & 15;
+            int m = m0 + rr, n = n0 + rr, k = k0 + kk;
+            Xs[kk][rr] = (m < M && k < K) ? Elem<T>::ld(X + (size_t)m * ldx + k) : 0.f;
+            Ws[kk][rr] = (n < N && k < K) ? Elem<T>::ld(W + (size_t)n * K + k) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = Xs[kk][ty * 4 + i]; b[i] = Ws[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (m < M && n < N) Y[(size_t)m * ldy + n] = acc[i][j];
+        }
+}
+
+hipError_t launch_gemm_generic(const Dims &dm, const void *X, int ldx, const void *W, int M, int N, int K,
+                               float *Y, int ldy, hipStream_t st) {
+    if (M <= 0 || N <= 0) return hipSuccess;
+    dim3 grid((N + 63) / 64, (M + 63) / 64);
+    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_gemm_generic<T>, grid, dim3(256), 0, st, (const T *)X, ldx, (const T *)W, M, N, K, Y, ldy));
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ LoRA shrink / expand
+// One block per row; wave w computes t[rr] for rr = w, w+4, ...
+template <typename T>
+__global__ void __launch_bounds__(256) k_lora_shrink(const T *__restrict__ X, int ldx, const T *__restrict__ A, int K, int r,
+                                                     const int32_t *__restrict__ row_model, float *__restrict__ t, float scale) {
+    int row = blockIdx.x;
+    int j = row_model[row];
+    if (j < 0) return;
+    const T *xr = X + (size_t)row * ldx;
+    const T *Aj = A + (size_t)j * r * K;
+    int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    for (int rr = w; rr < r; rr += 4) {
+        float acc = 0.f;
+        for (int k = lane; k < K; k += 64) acc += Elem<T>::ld(Aj + (size_t)rr * K + k) * Elem<T>::ld(xr + k);
+        acc = wave_sum(acc);
+        if (lane == 0) t[(size_t)row * r + rr] = acc * scale;
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) k_lora_expand(const float *__restrict__ t, const T *__restrict__ B, int N, int r,
+                                                     const int32_t *__restrict__ row_model, float *__restrict__ Y, int ldy) {
+    int row = blockIdx.y;
+    int j = row_model[row];
+    if (j < 0) return;
+    int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const T *Bn = B + ((size_t)j * N + n) * r;
+    float acc = 0.f;
+    for (int k = 0; k < r; ++k) acc += Elem<T>::ld(Bn + k) * t[(size_t)row * r + k];
+    Y[(size_t)row * ldy + n] += acc;
+}
+
+hipError_t launch_lora_shrink_generic(const Dims &dm, const void *X, int ldx, const void *A, int K,
+                                      const int32_t *row_model, float *t, int R, hipStream_t st) {
+    if (R <= 0 || dm.r <= 0) return hipSuccess;
+    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_lora_shrink<T>, dim3(R), dim3(256), 0, st, (const T *)X, ldx, (const T *)A, K, dm.r, row_model, t, dm.lora_scale));
+    return hipGetLastError();
+}
+hipError_t launch_lora_expand_generic(const Dims &dm, const float *t, const void *B, int N,
+                                      const int32_t *row_model, float *Y, int ldy, int R, hipStream_t st) {
+    if (R <= 0 || dm.r <= 0) return hipSuccess;
+    dim3 grid((N + 255) / 256, R);
+    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_lora_expand<T>, grid, dim3(256), 0, st, t, (const T *)B, N, dm.r, row_model, Y, ldy));
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ elementwise epilogues
+template <typename T>
+__global__ void __launch_bounds__(256) k_resid_store(const T *__restrict__ resid, const float *__restrict__ acc, T *__restrict__ out, size_t total) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < total) Elem<T>::st(out + i, Elem<T>::ld(resid + i) + acc[i]);
+}
+template <typename T>
+__global__ void __launch_bounds__(256) k_silu_mul(const float *__restrict__ g, const float *__restrict__ u, T *__restrict__ h, size_t total) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < total) {
+        float a = g[i];
+        Elem<T>::st(h + i, a / (1.f + __expf(-a)) * u[i]);
+    }
+}
+hipError_t launch_resid_store(const Dims &dm, const void *resid, const float *acc, void *out, int R, int n, hipStream_t st) {
+    size_t total = (size_t)R * n;
+    if (!total) return hipSuccess;
+    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_resid_store<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const T *)resid, acc, (T *)out, total));
+    return hipGetLastError();
+}
+hipError_t launch_silu_mul(const Dims &dm, const float *gate, const float *up, void *h, int R, int n, hipStream_t st) {
+    size_t total = (size_t)R * n;
+    if (!total) return hipSuccess;
+    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_silu_mul<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, gate, up, (T *)h, total));
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ QK-norm + RoPE + paged append
+// One block per row.  Heads 0..Hq-1 are q; for encoder rows heads Hq..Hq+Hkv-1 are k and the
+// next Hkv are v.  Angles are computed in double: pos * theta^(-2i/D).
+template <typename T>
+__global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ qkv, int ldq, const int32_t *__restrict__ row_seq,
+                                                     const int32_t *__restrict__ row_model, const int32_t *__restrict__ row_pos,
+                                                     const int32_t *__restrict__ bt, int max_blocks, T *__restrict__ pool,
+                                                     T *__restrict__ q_out, int64_t *__restrict__ slot_out, int slot_by_row,
+                                                     const T *__restrict__ q_norm, const T *__restrict__ k_norm,
+                                                     int Hq, int Hkv, int D, int Bk, double log2_theta, float eps, int qk_norm) {
+    extern __shared__ float sm[];  // inv_rms per head [Hq + Hkv]
+    int row = blockIdx.x;
+    int s = row_seq[row], pos = row_pos[row];
+    bool enc = row_model[row] < 0;
+    const float *src = qkv + (size_t)row * ldq;
+    int half = D >> 1;
+    int n_rot = Hq + (enc ? Hkv : 0);
+    int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (qk_norm) {
+        for (int h = w; h < n_rot; h += 4) {
+            float ss = 0.f;
+            for (int i = lane; i < D; i += 64) { float v = src[(size_t)h * D + i]; ss += v * v; }
+            ss = wave_sum(ss);
+            if (lane == 0) sm[h] = rsqrtf(ss / (float)D + eps);
+        }
+        __syncthreads();
+    }
+    int64_t slot = 0;
+    T *kdst = nullptr, *vdst = nullptr;
+    int off = 0;
+    if (enc) {
+        int blk = bt[(size_t)s * max_blocks + pos / Bk];
+        off = pos % Bk;
+        slot = (int64_t)blk * Bk + off;
+        kdst = pool + (size_t)blk * Hkv * 2 * Bk * D;
+        vdst = kdst;
+        if (threadIdx.x == 0 && slot_out) slot_out[slot_by_row ? row : s] = slot;
+    }
+    for (int idx = threadIdx.x; idx < n_rot * half; idx += 256) {
+        int h = idx / half, i = idx % half;
+        double ang = (double)pos * exp2(-(2.0 * (double)i / (double)D) * log2_theta);
+        double sn_d, cs_d;
+        sincos(ang, &sn_d, &cs_d);
+        float cs = (float)cs_d, sn = (float)sn_d;
+        float a = src[(size_t)h * D + i], b = src[(size_t)h * D + i + half];
+        if (qk_norm) {
+            const T *nw = h < Hq ? q_norm : k_norm;
+            a = a * sm[h] * Elem<T>::ld(nw + i);
+            b = b * sm[h] * Elem<T>::ld(nw + i + half);
+        }
+        float ra = a * cs - b * sn, rb = b * cs + a * sn;
+        if (h < Hq) {
+            T *dst = q_out + ((size_t)row * Hq + h) * D;
+            Elem<T>::st(dst + i, ra);
+            Elem<T>::st(dst + i + half, rb);
+        } else {
+            T *dst = kdst + ((size_t)(h - Hq) * 2 + 0) * Bk * D + (size_t)off * D;  // K plane [Bk][D]
+            Elem<T>::st(dst + i, ra);
+            Elem<T>::st(dst + i + half, rb);
+        }
+    }
+    if (enc) {
+        const float *vsrc = src + (size_t)(Hq + Hkv) * D;
+        for (int idx = threadIdx.x; idx < Hkv * D; idx += 256) {
+            int h = idx / D, i = idx % D;
+            T *dst = vdst + ((size_t)h * 2 + 1) * Bk * D;  // V plane [D][Bk]
+            Elem<T>::st(dst + (size_t)i * Bk + off, vsrc[idx]);
+        }
+    }
+}
+
+hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, const RowMeta &rm, const int32_t *bt,
+                              int max_blocks, void *pool, void *q_out, int64_t *slot_out, int slot_by_row,
+                              const void *q_norm, const void *k_norm, int R, hipStream_t st) {
+    if (R <= 0) return hipSuccess;
+    size_t shm = sizeof(float) * (size_t)(dm.Hq + dm.Hkv);
+    double l2t = log2(dm.theta);
+    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_rope_append<T>, dim3(R), dim3(256), shm, st, qkv, ldq, rm.row_seq, rm.row_model,
+                                           rm.row_pos, bt, max_blocks, (T *)pool, (T *)q_out, slot_out, slot_by_row,
+                                           (const T *)q_norm, (const T *)k_norm, dm.Hq, dm.Hkv, dm.D, dm.Bk, l2t, dm.eps, dm.qk_norm));
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ attention (one block per row and query head)
+// Online softmax over chunks of 1024 cached positions; thread d < D owns output element d.
+template <typename T>
+__global__ void __launch_bounds__(256) k_attn_generic(const T *__restrict__ q, const T *__restrict__ pool,
+                                                      const int32_t *__restrict__ bt, int max_blocks,
+                                                      const int32_t *__restrict__ row_seq, const int32_t *__restrict__ row_kvlen,
+                                                      T *__restrict__ out, int Hq, int Hkv, int D, int Bk, float scale) {
+    __shared__ float sc[1024];
+    __shared__ float red[16];
+    extern __shared__ float qs[];  // [D]
+    int row = blockIdx.y, h = blockIdx.x;
+    int c = h / (Hq / Hkv);
+    int s = row_seq[row], n = row_kvlen[row];
+    const int32_t *btr = bt + (size_t)s * max_blocks;
+    for (int i = threadIdx.x; i < D; i += 256) qs[i] = Elem<T>::ld(q + ((size_t)row * Hq + h) * D + i);
+    __syncthreads();
+    size_t head_stride = (size_t)2 * Bk * D, blk_stride = (size_t)Hkv * head_stride;
+    float m = -INFINITY, l = 0.f, acc = 0.f;
+    for (int c0 = 0; c0 < n; c0 += 1024) {
+        int cnt = min(1024, n - c0);
+        float lmax = -INFINITY;
+        for (int t = threadIdx.x; t < cnt; t += 256) {
+            int tok = c0 + t;
+            const T *kr = pool + (size_t)btr[tok / Bk] * blk_stride + (size_t)c * head_stride + (size_t)(tok % Bk) * D;
+            float dot = 0.f;
+            for (int i = 0; i < D; ++i) dot += qs[i] * Elem<T>::ld(kr + i);
+            dot *= scale;
+            sc[t] = dot;
+            lmax = fmaxf(lmax, dot);
+        }
+        float cmax = block_max(lmax, red);
+        float m_new = fmaxf(m, cmax);
+        float lsum = 0.f;
+        for (int t = threadIdx.x; t < cnt; t += 256) {
+            float p = __expf(sc[t] - m_new);
+            sc[t] = p;
+            lsum += p;
+        }
+        float csum = block_sum(lsum, red);  // barriers inside also publish sc[]
+        float alpha = (m == -INFINITY) ? 0.f : __expf(m - m_new);
+        l = l * alpha + csum;
+        if (threadIdx.x < D) {
+            float a = acc * alpha;
+            int d = threadIdx.x;
+            for (int t = 0; t < cnt; ++t) {
+                int tok = c0 + t;
+                const T *vr = pool + (size_t)btr[tok / Bk] * blk_stride + (size_t)c * head_stride + (size_t)Bk * D;
+                a += sc[t] * Elem<T>::ld(vr + (size_t)d * Bk + (tok % Bk));
+            }
+            acc = a;
+        }
+        m = m_new;
+        __syncthreads();
+    }
+    if (threadIdx.x < D)
+        Elem<T>::st(out + ((size_t)row * Hq + h) * D + threadIdx.x, l > 0.f ? acc / l : 0.f);
+}
+
+hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
+                               const RowMeta &rm, void *out, int R, hipStream_t st) {
+    if (R <= 0) return hipSuccess;
+    float scale = 1.0f / sqrtf((float)dm.D);
+    dim3 grid(dm.Hq, R);
+    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_attn_generic<T>, grid, dim3(256), sizeof(float) * dm.D, st, (const T *)q, (const T *)pool, bt,
+                                           max_blocks, rm.row_seq, rm.row_kvlen, (T *)out, dm.Hq, dm.Hkv, dm.D, dm.Bk, scale));
+    return hipGetLastError();
+}
+
+}  // namespace icarus

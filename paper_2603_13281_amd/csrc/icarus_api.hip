@@ -1,0 +1,462 @@
+// Host side of the C ABI: context, validation, per-call metadata staging, workspace
+// layout and the launch sequence of one layer step.  No arithmetic of the method
+// happens here; every step runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "../../include/icarus.h"
+#include "kernels.h"
+
+using namespace icarus;
+
+namespace {
+
+constexpr int kSlots = 16;  // pinned staging ring depth
+
+struct StageSlot {
+    void *host = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool in_flight = false;
+};
+
+char g_create_err[512] = "";
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+struct icarus_ctx {
+    icarus_layer_config cfg;
+    icarus_base_weights base;
+    icarus_lora_weights lora;
+    Dims dm;
+    int mode = 0;
+    char err[512];
+    StageSlot slots[kSlots];
+    int next_slot = 0;
+    std::mutex mu;
+};
+
+namespace {
+
+icarus_status fail(icarus_ctx *ctx, icarus_status st, const char *fmt, ...) {
+    char *dst = ctx ? ctx->err : g_create_err;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 512, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int proj_in(const icarus_layer_config &c, int p) {
+    switch (p) {
+    case ICARUS_PROJ_O: return c.n_q_heads * c.head_dim;
+    case ICARUS_PROJ_DOWN: return c.d_ffn;
+    default: return c.d_model;
+    }
+}
+int proj_out(const icarus_layer_config &c, int p) {
+    switch (p) {
+    case ICARUS_PROJ_Q: return c.n_q_heads * c.head_dim;
+    case ICARUS_PROJ_K: case ICARUS_PROJ_V: return c.n_kv_heads * c.head_dim;
+    case ICARUS_PROJ_GATE: case ICARUS_PROJ_UP: return c.d_ffn;
+    default: return c.d_model;
+    }
+}
+
+bool has_lora(const icarus_ctx *ctx, int p) {
+    if (p == ICARUS_PROJ_K || p == ICARUS_PROJ_V) return false;  // the decoder writes no KV: never read
+    return ctx->cfg.n_models > 0 && ctx->cfg.lora_rank > 0 && ((ctx->cfg.lora_target_mask >> p) & 1);
+}
+
+// ---- workspace layout ---------------------------------------------------------------
+struct WsLayout {
+    size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, total;
+    size_t meta_ints;
+};
+
+WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t /*max_ctx*/) {
+    const icarus_layer_config &c = ctx->cfg;
+    size_t es = c.dtype == ICARUS_BF16 ? 2 : 4;
+    size_t qd = (size_t)c.n_q_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim;
+    WsLayout w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    w.meta_ints = 4 * rows + 4 * seqs + 64;
+    w.meta = take(w.meta_ints * 4);
+    w.xn = take(rows * c.d_model * es);
+    w.qkv = take(rows * (qd + 2 * kvd) * 4);
+    w.q = take(rows * qd * es);
+    w.attn = take(rows * qd * es);
+    w.z = take(rows * c.d_model * es);
+    w.h = take(rows * c.d_ffn * es);
+    w.f32a = take(rows * std::max<size_t>(c.d_ffn, c.d_model) * 4);
+    w.f32b = take(rows * c.d_ffn * 4);
+    w.t = take(rows * std::max(1, c.lora_rank) * 4 * 2);
+    w.total = off;
+    return w;
+}
+
+// ---- pinned staging of per-call metadata -----------------------------------------------
+// Returns a host buffer of at least `bytes`; the caller fills it, then calls stage_commit to
+// enqueue the copy to the device and mark the slot busy until that copy has run.
+icarus_status stage_acquire(icarus_ctx *ctx, size_t bytes, StageSlot **out) {
+    StageSlot &s = ctx->slots[ctx->next_slot];
+    ctx->next_slot = (ctx->next_slot + 1) % kSlots;
+    hipError_t e;
+    if (s.in_flight) {
+        e = hipEventSynchronize(s.ev);
+        if (e != hipSuccess) return fail(ctx, ICARUS_ERR_HIP, "hipEventSynchronize: %s", hipGetErrorString(e));
+        s.in_flight = false;
+    }
+    if (!s.ev) {
+        e = hipEventCreateWithFlags(&s.ev, hipEventDisableTiming);
+        if (e != hipSuccess) return fail(ctx, ICARUS_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+    }
+    if (s.cap < bytes) {
+        if (s.host) (void)hipHostFree(s.host);
+        s.host = nullptr;
+        s.cap = 0;
+        size_t cap = align_up(std::max<size_t>(bytes, 1 << 16), 4096);
+        e = hipHostMalloc(&s.host, cap, hipHostMallocDefault);
+        if (e != hipSuccess) return fail(ctx, ICARUS_ERR_HIP, "hipHostMalloc(%zu): %s", cap, hipGetErrorString(e));
+        s.cap = cap;
+    }
+    *out = &s;
+    return ICARUS_OK;
+}
+
+icarus_status stage_commit(icarus_ctx *ctx, StageSlot *s, void *dev, size_t bytes, hipStream_t st) {
+    hipError_t e = hipMemcpyAsync(dev, s->host, bytes, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return fail(ctx, ICARUS_ERR_HIP, "hipMemcpyAsync(meta): %s", hipGetErrorString(e));
+    e = hipEventRecord(s->ev, st);
+    if (e != hipSuccess) return fail(ctx, ICARUS_ERR_HIP, "hipEventRecord: %s", hipGetErrorString(e));
+    s->in_flight = true;
+    return ICARUS_OK;
+}
+
+#define HIP_TRY(ctx, expr)                                                                         \
+    do {                                                                                           \
+        hipError_t e__ = (expr);                                                                   \
+        if (e__ != hipSuccess) return fail(ctx, ICARUS_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+
+// ---- validation ----------------------------------------------------------------------
+icarus_status check_decode_rows(icarus_ctx *ctx, int32_t max_blocks, int32_t S, const int32_t *ctx_lens, int32_t R,
+                                const int32_t *row_seq, const int32_t *row_model) {
+    const icarus_layer_config &c = ctx->cfg;
+    if (S < 0 || R < 0 || max_blocks < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "negative size");
+    if (S == 0 && R == 0) return ICARUS_OK;
+    if (!ctx_lens || !row_seq || !row_model) return fail(ctx, ICARUS_ERR_INVALID_ARG, "null metadata array");
+    if (R > 65535) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "at most 65535 rows per call (got %d)", R);
+    int r = 0;
+    std::vector<char> seen((size_t)std::max(1, c.n_models));
+    for (int s = 0; s < S; ++s) {
+        if (ctx_lens[s] < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "ctx_lens[%d] = %d is negative", s, ctx_lens[s]);
+        if (ctx_lens[s] + 1 > c.max_position)
+            return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: position %d >= max_position %d", s, ctx_lens[s], c.max_position);
+        if ((int64_t)ctx_lens[s] / c.block_size + 1 > max_blocks)
+            return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: position %d needs %d blocks, table has %d", s, ctx_lens[s],
+                        ctx_lens[s] / c.block_size + 1, max_blocks);
+        if (r >= R || row_seq[r] != s)
+            return fail(ctx, ICARUS_ERR_ROW_ORDER, "sequence %d has no rows at row %d (rows must be grouped by sequence, in order)", s, r);
+        if (row_model[r] != -1)
+            return fail(ctx, ICARUS_ERR_ROW_ORDER, "row %d: the first row of sequence %d must be the encoder row (model -1)", r, s);
+        ++r;
+        std::fill(seen.begin(), seen.end(), 0);
+        while (r < R && row_seq[r] == s) {
+            int j = row_model[r];
+            if (j == -1) return fail(ctx, ICARUS_ERR_ROW_ORDER, "row %d: second encoder row in sequence %d", r, s);
+            if (j < 0 || j >= c.n_models) return fail(ctx, ICARUS_ERR_MODEL_ID, "row %d: model id %d outside 0..%d", r, j, c.n_models - 1);
+            if (seen[j]) return fail(ctx, ICARUS_ERR_MODEL_ID, "row %d: model id %d repeated in sequence %d", r, j, s);
+            seen[j] = 1;
+            ++r;
+        }
+    }
+    if (r != R) {
+        if (row_seq[r] < 0 || row_seq[r] >= S) return fail(ctx, ICARUS_ERR_INVALID_ARG, "row %d: sequence id %d outside 0..%d", r, row_seq[r], S - 1);
+        return fail(ctx, ICARUS_ERR_ROW_ORDER, "row %d: sequence %d appears out of order", r, row_seq[r]);
+    }
+    return ICARUS_OK;
+}
+
+icarus_status check_common_ptrs(icarus_ctx *ctx, const void *pool, const void *bt, const void *ws, size_t ws_bytes, size_t need) {
+    if (!pool || !bt) return fail(ctx, ICARUS_ERR_INVALID_ARG, "kv_pool / block_tables is null");
+    if (!ws) return fail(ctx, ICARUS_ERR_INVALID_ARG, "workspace is null");
+    if (!aligned16(pool) || !aligned16(bt) || !aligned16(ws)) return fail(ctx, ICARUS_ERR_ALIGNMENT, "kv_pool, block_tables and workspace must be 16-byte aligned");
+    if (ws_bytes < need) return fail(ctx, ICARUS_ERR_CAPACITY, "workspace has %zu bytes, this call needs %zu", ws_bytes, need);
+    return ICARUS_OK;
+}
+
+// ---- the layer, after metadata is on the device ---------------------------------------
+// rows: x_in [R, d].  use_lora: decoder rows get adapter deltas.  kv_only: stop after the append.
+icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, int R, bool use_lora, bool kv_only,
+                        int slot_by_row, void *pool, const int32_t *bt, int max_blocks, const void *x_in, void *x_out,
+                        int64_t *slot_out, hipStream_t st) {
+    const icarus_layer_config &c = ctx->cfg;
+    const Dims &dm = ctx->dm;
+    int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, F = c.d_ffn;
+    int ldq = qd + 2 * kvd;
+    void *xn = ws + L.xn, *q = ws + L.q, *attn = ws + L.attn, *z = ws + L.z, *h = ws + L.h;
+    float *qkv = (float *)(ws + L.qkv), *fa = (float *)(ws + L.f32a), *fb = (float *)(ws + L.f32b), *t = (float *)(ws + L.t);
+    auto lora = [&](int p, const void *X, int ldx, float *Y, int ldy) -> hipError_t {
+        if (!use_lora || !has_lora(ctx, p)) return hipSuccess;
+        hipError_t e = launch_lora_shrink_generic(dm, X, ldx, ctx->lora.A[p], proj_in(c, p), rm.row_model, t, R, st);
+        if (e != hipSuccess) return e;
+        return launch_lora_expand_generic(dm, t, ctx->lora.B[p], proj_out(c, p), rm.row_model, Y, ldy, R, st);
+    };
+    HIP_TRY(ctx, launch_rmsnorm(dm, x_in, ctx->base.norm_attn, xn, R, d, st));
+    if (!kv_only) {
+        HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_Q], R, qd, d, qkv, ldq, st));
+        HIP_TRY(ctx, lora(ICARUS_PROJ_Q, xn, d, qkv, ldq));
+    }
+    HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_K], R, kvd, d, qkv + qd, ldq, st));
+    HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_V], R, kvd, d, qkv + qd + kvd, ldq, st));
+    HIP_TRY(ctx, launch_rope_append(dm, qkv, ldq, rm, bt, max_blocks, pool, q, slot_out, slot_by_row, ctx->base.q_norm,
+                                    ctx->base.k_norm, R, st));
+    if (kv_only) return ICARUS_OK;
+    HIP_TRY(ctx, launch_attn_generic(dm, q, pool, bt, max_blocks, rm, attn, R, st));
+    HIP_TRY(ctx, launch_gemm_generic(dm, attn, qd, ctx->base.w[ICARUS_PROJ_O], R, d, qd, fa, d, st));
+    HIP_TRY(ctx, lora(ICARUS_PROJ_O, attn, qd, fa, d));
+    HIP_TRY(ctx, launch_resid_store(dm, x_in, fa, z, R, d, st));
+    HIP_TRY(ctx, launch_rmsnorm(dm, z, ctx->base.norm_ffn, xn, R, d, st));
+    HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_GATE], R, F, d, fa, F, st));
+    HIP_TRY(ctx, lora(ICARUS_PROJ_GATE, xn, d, fa, F));
+    HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_UP], R, F, d, fb, F, st));
+    HIP_TRY(ctx, lora(ICARUS_PROJ_UP, xn, d, fb, F));
+    HIP_TRY(ctx, launch_silu_mul(dm, fa, fb, h, R, F, st));
+    HIP_TRY(ctx, launch_gemm_generic(dm, h, F, ctx->base.w[ICARUS_PROJ_DOWN], R, d, F, fa, d, st));
+    HIP_TRY(ctx, lora(ICARUS_PROJ_DOWN, h, F, fa, d));
+    HIP_TRY(ctx, launch_resid_store(dm, z, fa, x_out, R, d, st));
+    return ICARUS_OK;
+}
+
+}  // namespace
+
+// =====================================================================================
+extern "C" {
+
+const char *icarus_last_error(const icarus_ctx *ctx) { return ctx ? ctx->err : g_create_err; }
+
+icarus_status icarus_create(const icarus_layer_config *cfg, const icarus_base_weights *base,
+                            const icarus_lora_weights *lora, icarus_ctx **out) {
+    if (out) *out = nullptr;
+    if (!cfg || !base || !out) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "cfg, base and out must not be null");
+    const icarus_layer_config &c = *cfg;
+    if (c.dtype != ICARUS_F32 && c.dtype != ICARUS_BF16) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "dtype %d is neither ICARUS_F32 nor ICARUS_BF16", c.dtype);
+    if (c.d_model <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.d_ffn <= 0 || c.block_size <= 0 ||
+        c.num_blocks <= 0 || c.max_position <= 0 || c.n_models < 0 || c.lora_rank < 0)
+        return fail(nullptr, ICARUS_ERR_SHAPE, "all sizes must be positive (n_models, lora_rank non-negative)");
+    if (c.n_q_heads % c.n_kv_heads) return fail(nullptr, ICARUS_ERR_SHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", c.n_q_heads, c.n_kv_heads);
+    if (c.head_dim % 2 || c.head_dim > 256) return fail(nullptr, ICARUS_ERR_SHAPE, "head_dim %d must be even and at most 256", c.head_dim);
+    if (!(c.rope_theta > 1.0) || !(c.rms_eps >= 0.0)) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "rope_theta must exceed 1 and rms_eps be non-negative");
+    if ((int64_t)c.num_blocks * c.block_size > (int64_t)1 << 40) return fail(nullptr, ICARUS_ERR_SHAPE, "pool too large");
+    for (int p = 0; p < ICARUS_NPROJ; ++p) {
+        if (!base->w[p]) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "base weight %d is null", p);
+        if (!aligned16(base->w[p])) return fail(nullptr, ICARUS_ERR_ALIGNMENT, "base weight %d is not 16-byte aligned", p);
+    }
+    if (!base->norm_attn || !base->norm_ffn) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "norm weights are null");
+    if (c.qk_norm && (!base->q_norm || !base->k_norm)) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "qk_norm set but q_norm / k_norm is null");
+    if (!aligned16(base->norm_attn) || !aligned16(base->norm_ffn) || !aligned16(base->q_norm) || !aligned16(base->k_norm))
+        return fail(nullptr, ICARUS_ERR_ALIGNMENT, "norm weights must be 16-byte aligned");
+    icarus_ctx *ctx = new (std::nothrow) icarus_ctx();
+    if (!ctx) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "out of host memory");
+    ctx->cfg = c;
+    ctx->base = *base;
+    memset(&ctx->lora, 0, sizeof(ctx->lora));
+    ctx->err[0] = 0;
+    if (lora) ctx->lora = *lora;
+    for (int p = 0; p < ICARUS_NPROJ; ++p) {
+        if (!has_lora(ctx, p)) continue;
+        if (!ctx->lora.A[p] || !ctx->lora.B[p]) {
+            delete ctx;
+            return fail(nullptr, ICARUS_ERR_INVALID_ARG, "projection %d is a LoRA target but its A or B is null", p);
+        }
+        if (!aligned16(ctx->lora.A[p]) || !aligned16(ctx->lora.B[p])) {
+            delete ctx;
+            return fail(nullptr, ICARUS_ERR_ALIGNMENT, "LoRA weights of projection %d are not 16-byte aligned", p);
+        }
+    }
+    Dims &dm = ctx->dm;
+    dm.d = c.d_model; dm.Hq = c.n_q_heads; dm.Hkv = c.n_kv_heads; dm.D = c.head_dim; dm.F = c.d_ffn; dm.Bk = c.block_size;
+    dm.M = c.n_models; dm.r = c.lora_rank; dm.bf16 = c.dtype == ICARUS_BF16; dm.qk_norm = c.qk_norm != 0;
+    dm.theta = c.rope_theta; dm.eps = (float)c.rms_eps; dm.lora_scale = (float)c.lora_scale;
+    *out = ctx;
+    return ICARUS_OK;
+}
+
+void icarus_destroy(icarus_ctx *ctx) {
+    if (!ctx) return;
+    for (auto &s : ctx->slots) {
+        if (s.in_flight && s.ev) (void)hipEventSynchronize(s.ev);
+        if (s.ev) (void)hipEventDestroy(s.ev);
+        if (s.host) (void)hipHostFree(s.host);
+    }
+    delete ctx;
+}
+
+icarus_status icarus_set_kernel_mode(icarus_ctx *ctx, int32_t mode) {
+    if (!ctx) return ICARUS_ERR_INVALID_ARG;
+    if (mode != 0 && mode != 1) return fail(ctx, ICARUS_ERR_INVALID_ARG, "kernel mode %d unknown", mode);
+    ctx->mode = mode;
+    return ICARUS_OK;
+}
+
+size_t icarus_workspace_bytes(const icarus_ctx *ctx, int32_t max_rows, int32_t max_seqs, int32_t max_ctx) {
+    if (!ctx || max_rows < 0 || max_seqs < 0 || max_ctx < 0) return 0;
+    return ws_layout(ctx, (size_t)std::max(1, max_rows), (size_t)std::max(1, max_seqs), (size_t)max_ctx).total;
+}
+
+icarus_status icarus_validate_decode(icarus_ctx *ctx, int32_t max_blocks, int32_t S, const int32_t *ctx_lens, int32_t R,
+                                     const int32_t *row_seq, const int32_t *row_model) {
+    if (!ctx) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    return check_decode_rows(ctx, max_blocks, S, ctx_lens, R, row_seq, row_model);
+}
+
+icarus_status icarus_decode_step(icarus_ctx *ctx, void *kv_pool, const int32_t *block_tables, int32_t max_blocks, int32_t S,
+                                 const int32_t *ctx_lens, int32_t R, const int32_t *row_seq, const int32_t *row_model,
+                                 const void *x_in, void *x_out, int64_t *slot_out, void *workspace, size_t workspace_bytes,
+                                 void *stream) {
+    if (!ctx) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    icarus_status rc = check_decode_rows(ctx, max_blocks, S, ctx_lens, R, row_seq, row_model);
+    if (rc) return rc;
+    if (R == 0) return ICARUS_OK;
+    if (!x_in || !x_out) return fail(ctx, ICARUS_ERR_INVALID_ARG, "x_in / x_out is null");
+    if (!aligned16(x_in) || !aligned16(x_out) || (slot_out && !aligned16(slot_out))) return fail(ctx, ICARUS_ERR_ALIGNMENT, "x_in, x_out and slot_out must be 16-byte aligned");
+    int max_ctx = 0;
+    for (int s = 0; s < S; ++s) max_ctx = std::max(max_ctx, ctx_lens[s] + 1);
+    WsLayout L = ws_layout(ctx, (size_t)R, (size_t)S, (size_t)max_ctx);
+    rc = check_common_ptrs(ctx, kv_pool, block_tables, workspace, workspace_bytes, L.total);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    StageSlot *slot;
+    size_t meta_bytes = (size_t)4 * R * 4;
+    rc = stage_acquire(ctx, meta_bytes, &slot);
+    if (rc) return rc;
+    int32_t *m = (int32_t *)slot->host;
+    for (int r = 0; r < R; ++r) {
+        m[r] = row_seq[r];
+        m[R + r] = row_model[r];
+        m[2 * R + r] = ctx_lens[row_seq[r]];
+        m[3 * R + r] = ctx_lens[row_seq[r]] + 1;
+    }
+    char *ws = (char *)workspace;
+    rc = stage_commit(ctx, slot, ws + L.meta, meta_bytes, st);
+    if (rc) return rc;
+    const int32_t *dmeta = (const int32_t *)(ws + L.meta);
+    RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
+    return run_layer(ctx, ws, L, rm, R, true, false, 0, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
+}
+
+icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *block_tables, int32_t max_blocks, int32_t S,
+                                const int32_t *ctx_lens, const int32_t *chunk_lens, const void *x_in, void *x_out,
+                                int64_t *slot_out, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!ctx) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    const icarus_layer_config &c = ctx->cfg;
+    if (S < 0 || max_blocks < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "negative size");
+    if (S == 0) return ICARUS_OK;
+    if (!ctx_lens || !chunk_lens) return fail(ctx, ICARUS_ERR_INVALID_ARG, "null metadata array");
+    int64_t total = 0;
+    int max_ctx = 0;
+    for (int s = 0; s < S; ++s) {
+        if (ctx_lens[s] < 0 || chunk_lens[s] < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "sequence %d: negative length", s);
+        int64_t end = (int64_t)ctx_lens[s] + chunk_lens[s];
+        if (end > c.max_position) return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: %lld tokens exceed max_position %d", s, (long long)end, c.max_position);
+        if ((end + c.block_size - 1) / c.block_size > max_blocks)
+            return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: %lld tokens need %lld blocks, table has %d", s, (long long)end,
+                        (long long)((end + c.block_size - 1) / c.block_size), max_blocks);
+        total += chunk_lens[s];
+        max_ctx = std::max<int>(max_ctx, (int)end);
+    }
+    if (total == 0) return ICARUS_OK;
+    if (total > 65535) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "at most 65535 rows per call (got %lld)", (long long)total);
+    if (!x_in) return fail(ctx, ICARUS_ERR_INVALID_ARG, "x_in is null");
+    if (!aligned16(x_in) || (x_out && !aligned16(x_out)) || (slot_out && !aligned16(slot_out))) return fail(ctx, ICARUS_ERR_ALIGNMENT, "x_in, x_out and slot_out must be 16-byte aligned");
+    int R = (int)total;
+    WsLayout L = ws_layout(ctx, (size_t)R, (size_t)S, (size_t)max_ctx);
+    icarus_status rc = check_common_ptrs(ctx, kv_pool, block_tables, workspace, workspace_bytes, L.total);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    StageSlot *slot;
+    size_t meta_bytes = (size_t)4 * R * 4;
+    rc = stage_acquire(ctx, meta_bytes, &slot);
+    if (rc) return rc;
+    int32_t *m = (int32_t *)slot->host;
+    int r = 0;
+    for (int s = 0; s < S; ++s)
+        for (int i = 0; i < chunk_lens[s]; ++i, ++r) {
+            m[r] = s;
+            m[R + r] = -1;
+            m[2 * R + r] = ctx_lens[s] + i;
+            m[3 * R + r] = ctx_lens[s] + i + 1;
+        }
+    char *ws = (char *)workspace;
+    rc = stage_commit(ctx, slot, ws + L.meta, meta_bytes, st);
+    if (rc) return rc;
+    const int32_t *dmeta = (const int32_t *)(ws + L.meta);
+    RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
+    return run_layer(ctx, ws, L, rm, R, false, x_out == nullptr, 1, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
+}
+
+icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *kv_pool, const int32_t *block_tables,
+                                    int32_t max_blocks, int32_t S, const int32_t *kv_lens, int32_t R, const int32_t *row_seq,
+                                    void *out, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!ctx) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    const icarus_layer_config &c = ctx->cfg;
+    if (S < 0 || R < 0 || max_blocks < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "negative size");
+    if (R == 0) return ICARUS_OK;
+    if (!kv_lens || !row_seq) return fail(ctx, ICARUS_ERR_INVALID_ARG, "null metadata array");
+    if (R > 65535) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "at most 65535 rows per call (got %d)", R);
+    int max_ctx = 0;
+    for (int s = 0; s < S; ++s) {
+        if (kv_lens[s] < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "kv_lens[%d] is negative", s);
+        if (kv_lens[s] > c.max_position) return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: %d tokens exceed max_position %d", s, kv_lens[s], c.max_position);
+        if (((int64_t)kv_lens[s] + c.block_size - 1) / c.block_size > max_blocks)
+            return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: %d tokens need more than %d blocks", s, kv_lens[s], max_blocks);
+        max_ctx = std::max(max_ctx, kv_lens[s]);
+    }
+    for (int r = 0; r < R; ++r) {
+        if (row_seq[r] < 0 || row_seq[r] >= S) return fail(ctx, ICARUS_ERR_INVALID_ARG, "row %d: sequence id %d outside 0..%d", r, row_seq[r], S - 1);
+        if (r && row_seq[r] < row_seq[r - 1]) return fail(ctx, ICARUS_ERR_ROW_ORDER, "row %d: rows must be grouped by sequence in non-decreasing order", r);
+    }
+    if (!q || !out) return fail(ctx, ICARUS_ERR_INVALID_ARG, "q / out is null");
+    if (!aligned16(q) || !aligned16(out)) return fail(ctx, ICARUS_ERR_ALIGNMENT, "q and out must be 16-byte aligned");
+    WsLayout L = ws_layout(ctx, (size_t)R, (size_t)S, (size_t)max_ctx);
+    icarus_status rc = check_common_ptrs(ctx, kv_pool, block_tables, workspace, workspace_bytes, L.total);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    StageSlot *slot;
+    size_t meta_bytes = (size_t)4 * R * 4;
+    rc = stage_acquire(ctx, meta_bytes, &slot);
+    if (rc) return rc;
+    int32_t *m = (int32_t *)slot->host;
+    for (int r = 0; r < R; ++r) {
+        m[r] = row_seq[r];
+        m[R + r] = 0;
+        m[2 * R + r] = kv_lens[row_seq[r]] - 1;
+        m[3 * R + r] = kv_lens[row_seq[r]];
+    }
+    char *ws = (char *)workspace;
+    rc = stage_commit(ctx, slot, ws + L.meta, meta_bytes, st);
+    if (rc) return rc;
+    const int32_t *dmeta = (const int32_t *)(ws + L.meta);
+    RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
+    HIP_TRY(ctx, launch_attn_generic(ctx->dm, q, kv_pool, block_tables, max_blocks, rm, out, R, st));
+    return ICARUS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,51 @@
+// Internal launch interface between the C-ABI host layer and the gfx950 kernels.
+// Every launcher enqueues on `st` and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace icarus {
+
+struct Dims {
+    int d, Hq, Hkv, D, F, Bk, M, r;
+    int bf16;      // storage type: 1 = bfloat16, 0 = float32
+    int qk_norm;
+    double theta;
+    float eps, lora_scale;
+};
+
+// Per-call row metadata, device int32 arrays.
+struct RowMeta {
+    const int32_t *row_seq;    // [R] sequence of each row
+    const int32_t *row_model;  // [R] -1 = logical encoder row, else adapter id
+    const int32_t *row_pos;    // [R] position of the row's token
+    const int32_t *row_kvlen;  // [R] cache positions the row attends to (0..kvlen-1)
+};
+
+// ---- generic vector kernels (any shape; fp32 accumulation) -------------------------------
+// y[r,:] = x[r,:] * rsqrt(mean(x^2)+eps) * w        (storage type in and out)
+hipError_t launch_rmsnorm(const Dims &dm, const void *x, const void *w, void *y, int R, int n, hipStream_t st);
+// Y[m, n] (fp32, ld = ldy) = sum_k X[m,k] W[n,k];  X, W storage type
+hipError_t launch_gemm_generic(const Dims &dm, const void *X, int ldx, const void *W, int M, int N, int K,
+                               float *Y, int ldy, hipStream_t st);
+// t[row, 0..r) (fp32) = lora_scale * A[model(row)] x[row]   for decoder rows (model >= 0)
+hipError_t launch_lora_shrink_generic(const Dims &dm, const void *X, int ldx, const void *A, int K,
+                                      const int32_t *row_model, float *t, int R, hipStream_t st);
+// Y[row, n] += sum_k B[model(row)][n,k] t[row,k]           for decoder rows
+hipError_t launch_lora_expand_generic(const Dims &dm, const float *t, const void *B, int N,
+                                      const int32_t *row_model, float *Y, int ldy, int R, hipStream_t st);
+// out[r, n] (storage) = resid[r, n] (storage) + acc[r, n] (fp32)
+hipError_t launch_resid_store(const Dims &dm, const void *resid, const float *acc, void *out, int R, int n, hipStream_t st);
+// h[r, n] (storage) = silu(gate[r,n]) * up[r,n]     (fp32 in)
+hipError_t launch_silu_mul(const Dims &dm, const float *gate, const float *up, void *h, int R, int n, hipStream_t st);
+// QK-RMSNorm (optional) + RoPE on q (all rows) and k (encoder rows), q -> q_out (storage, [R,Hq,D]),
+// k, v of encoder rows -> paged cache; slot_out[slot_by_row ? row : seq] = slot.
+// qkv: fp32 [R, ldq] with q at column 0, k at Hq*D, v at (Hq+Hkv)*D.
+hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, const RowMeta &rm, const int32_t *bt,
+                              int max_blocks, void *pool, void *q_out, int64_t *slot_out, int slot_by_row,
+                              const void *q_norm, const void *k_norm, int R, hipStream_t st);
+// out[row, h, :] = softmax(q[row,h,:] K^T / sqrt(D)) V over positions 0..row_kvlen[row]-1 of row_seq[row]
+hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
+                               const RowMeta &rm, void *out, int R, hipStream_t st);
+
+}  // namespace icarus

@@ -1,0 +1,110 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared
+symbol, and rejects malformed configurations and batches before touching a device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2603_13281_amd import binding
+from paper_2603_13281_amd.binding import IcarusError, IcarusLayer, LayerConfig
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a 16-byte aligned non-null address; never dereferenced on the host
+
+
+def _cfg(**kw):
+    base = dict(d_model=256, n_q_heads=8, n_kv_heads=2, head_dim=64, d_ffn=512, block_size=16, num_blocks=64,
+                n_models=4, lora_rank=8, lora_target_mask=0x7F, bf16=True, max_position=4096)
+    base.update(kw)
+    return LayerConfig(**base)
+
+
+def _weights(addr=FAKE):
+    base = {p: addr for p in binding.PROJ}
+    base.update(norm_attn=addr, norm_ffn=addr, q_norm=addr, k_norm=addr)
+    lora = {p: (addr, addr) for p in binding.PROJ}
+    return base, lora
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "icarus.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(icarus_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
+    lib = C.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_create_and_workspace_are_host_only():
+    base, lora = _weights()
+    layer = IcarusLayer(_cfg(), base, lora)
+    small = layer.workspace_bytes(9, 1, 4097)
+    big = layer.workspace_bytes(576, 64, 16484)
+    assert 0 < small < big
+    assert layer.workspace_bytes(-1, 1, 1) == 0
+    layer.close()
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_q_heads=6, n_kv_heads=4), "SHAPE"),
+    (dict(head_dim=63), "SHAPE"),
+    (dict(head_dim=512), "SHAPE"),
+    (dict(d_model=0), "SHAPE"),
+    (dict(num_blocks=0), "SHAPE"),
+    (dict(max_position=0), "SHAPE"),
+    (dict(rope_theta=0.5), "INVALID_ARG"),
+])
+def test_create_rejects_bad_config(kw, status):
+    base, lora = _weights()
+    with pytest.raises(IcarusError) as e:
+        IcarusLayer(_cfg(**kw), base, lora)
+    assert e.value.status_name == status
+
+
+def test_create_rejects_bad_pointers():
+    base, lora = _weights()
+    b2 = dict(base, q=0)
+    with pytest.raises(IcarusError) as e:
+        IcarusLayer(_cfg(), b2, lora)
+    assert e.value.status_name == "INVALID_ARG"
+    b3 = dict(base, down=FAKE + 8)
+    with pytest.raises(IcarusError) as e:
+        IcarusLayer(_cfg(), b3, lora)
+    assert e.value.status_name == "ALIGNMENT"
+    l2 = dict(lora, o=None)
+    with pytest.raises(IcarusError) as e:
+        IcarusLayer(_cfg(), base, l2)
+    assert e.value.status_name == "INVALID_ARG"
+    # adapters for K and V are never read: they may be absent
+    l3 = dict(lora, k=None, v=None)
+    IcarusLayer(_cfg(), base, l3).close()
+    # and no adapters at all is a plain base model
+    IcarusLayer(_cfg(n_models=0, lora_rank=0), base, None).close()
+
+
+def test_validate_decode_row_rules():
+    base, lora = _weights()
+    layer = IcarusLayer(_cfg(), base, lora)
+    ok = lambda ctx, rs, rm, mb=8: layer.validate_decode(mb, ctx, rs, rm)
+    ok([5, 100], [0, 0, 0, 1], [-1, 2, 0, -1])          # m = 2 and m = 0
+    ok([0], [0], [-1])
+
+    def bad(status, *a, **k):
+        with pytest.raises(IcarusError) as e:
+            ok(*a, **k)
+        assert e.value.status_name == status, str(e.value)
+    bad("ROW_ORDER", [5, 7], [0, 1, 0], [-1, -1, 1])     # rows of sequence 0 not contiguous
+    bad("ROW_ORDER", [5], [0, 0], [1, -1])               # encoder row not first
+    bad("ROW_ORDER", [5], [0, 0], [-1, -1])              # two encoder rows
+    bad("ROW_ORDER", [5, 7], [0, 0], [-1, 1])            # sequence 1 has no rows
+    bad("MODEL_ID", [5], [0, 0], [-1, 4])                # id out of range
+    bad("MODEL_ID", [5], [0, 0], [-1, -2])
+    bad("MODEL_ID", [5], [0, 0, 0], [-1, 3, 3])          # repeated
+    bad("CAPACITY", [128], [0], [-1], mb=8)              # position 128 needs 9 blocks
+    bad("CAPACITY", [4096], [0], [-1], mb=1000)          # beyond max_position
+    bad("INVALID_ARG", [-1], [0], [-1])
+    ok([127], [0], [-1], mb=8)
+    layer.close()
