@@ -42,7 +42,10 @@ def make_layer(shape, base, lora, num_blocks, device="cuda:0", max_position=1 <<
     dlora = None
     if lora is not None:
         dlora = {p: (dev(A, shape.bf16, device), dev(B, shape.bf16, device)) for p, (A, B) in lora.items()}
-    return binding.IcarusLayer(layer_config(shape, num_blocks, max_position), dbase, dlora)
+    cfg = layer_config(shape, num_blocks, max_position)
+    if lora is None:
+        cfg.n_models, cfg.lora_rank, cfg.lora_target_mask = 0, 0, 0
+    return binding.IcarusLayer(cfg, dbase, dlora)
 
 
 def bf16_ulp(x: np.ndarray) -> np.ndarray:

@@ -22,12 +22,19 @@ def _say(*a):
 
 
 def _cache_close(shape, got_pool, want_pool, what):
-    """cache entries within one ulp of the storage type of the oracle's (rounded) value."""
+    """Cache entries against the oracle's rounded values.  bf16 storage: the matrix cores take the normed row
+    rounded to bf16 (relative error up to 2^-9 per element), which moves a K/V entry by sigma ~ 1.6e-3 * rms before
+    its own rounding, so the gate is one bf16 ulp of the value plus 2^-6 of the rms of the written entries (~10 sigma).
+    fp32 storage: one ulp plus the fp32 accumulation allowance (1e-5 of the largest entry)."""
+    want = want_pool.astype(np.float64)
+    diff = np.abs(got_pool.astype(np.float64) - want)
     if shape.bf16:
-        ok = np.abs(got_pool.astype(np.float64) - want_pool) <= bf16_ulp(want_pool) * 1.0001
+        written = want[diff > 0]
+        rms = float(np.sqrt(np.mean(written ** 2))) if written.size else 0.0
+        ok = diff <= bf16_ulp(want_pool) * 1.0001 + 2.0 ** -6 * rms
     else:
-        ok = np.abs(got_pool.astype(np.float64) - want_pool) <= np.abs(want_pool) * 2e-6 + 1e-7
-    assert ok.all(), f"{what}: {int((~ok).sum())} cache elements differ by more than one ulp"
+        ok = diff <= np.abs(want) * 2.0 ** -23 + 1e-5 * float(np.max(np.abs(want)))
+    assert ok.all(), f"{what}: {int((~ok).sum())} cache elements outside the gate, worst {float(diff.max()):.3e}"
 
 
 def _decode_case(shape, ctx, n_active, seed, mode, norm_ones=False):
