@@ -171,6 +171,17 @@ icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *
  * where the shape allows, default), 1 = force the generic vector kernels. */
 icarus_status icarus_set_kernel_mode(icarus_ctx *ctx, int32_t mode);
 
+/* Per-phase kernel timing for measurements.  While enabled, every kernel launch of the entry
+ * points above is bracketed by HIP events recorded on the caller's stream (this costs a few
+ * microseconds per launch: leave it off when timing whole steps).  icarus_timing_read waits
+ * for the recorded events, returns the accumulated milliseconds and launch counts per phase
+ * (host arrays of ICARUS_NPHASE entries) and resets the accumulators. */
+enum { ICARUS_PH_NORM = 0, ICARUS_PH_LORA, ICARUS_PH_GEMM_QKV, ICARUS_PH_ROPE_APPEND, ICARUS_PH_ATTN,
+       ICARUS_PH_ATTN_MERGE, ICARUS_PH_GEMM_O, ICARUS_PH_GEMM_GATEUP, ICARUS_PH_GEMM_DOWN,
+       ICARUS_PH_ELEMWISE, ICARUS_NPHASE };
+icarus_status icarus_timing_enable(icarus_ctx *ctx, int32_t on);
+icarus_status icarus_timing_read(icarus_ctx *ctx, double *ms /*host*/, int32_t *launches /*host*/);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,10 @@ STATUS = {0: "OK", 1: "INVALID_ARG", 2: "SHAPE", 3: "ALIGNMENT", 4: "MODEL_ID", 
 
 EXPORTS = ("icarus_create", "icarus_destroy", "icarus_last_error", "icarus_workspace_bytes",
            "icarus_validate_decode", "icarus_prefill_kv", "icarus_decode_step", "icarus_attn_shared_kv",
-           "icarus_set_kernel_mode")
+           "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read")
+
+PHASES = ("norm", "lora", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gateup", "gemm_down",
+          "elementwise")
 
 
 class IcarusError(RuntimeError):
@@ -75,6 +78,10 @@ def _load():
     lib.icarus_attn_shared_kv.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
     lib.icarus_set_kernel_mode.restype = C.c_int
     lib.icarus_set_kernel_mode.argtypes = [vp, i32]
+    lib.icarus_timing_enable.restype = C.c_int
+    lib.icarus_timing_enable.argtypes = [vp, i32]
+    lib.icarus_timing_read.restype = C.c_int
+    lib.icarus_timing_read.argtypes = [vp, vp, vp]
     return lib
 
 
@@ -193,6 +200,16 @@ class IcarusLayer:
     # -- C ABI mirrors ---------------------------------------------------------------
     def set_kernel_mode(self, mode: int):
         self._check(_lib.icarus_set_kernel_mode(self._h, mode))
+
+    def timing_enable(self, on: bool):
+        self._check(_lib.icarus_timing_enable(self._h, int(on)))
+
+    def timing_read(self) -> dict:
+        """{phase: (milliseconds, launches)} accumulated since the last read."""
+        ms = np.zeros(len(PHASES), dtype=np.float64)
+        n = np.zeros(len(PHASES), dtype=np.int32)
+        self._check(_lib.icarus_timing_read(self._h, _ptr(ms), _ptr(n)))
+        return {p: (float(ms[i]), int(n[i])) for i, p in enumerate(PHASES)}
 
     def workspace_bytes(self, max_rows: int, max_seqs: int, max_ctx: int) -> int:
         return int(_lib.icarus_workspace_bytes(self._h, max_rows, max_seqs, max_ctx))

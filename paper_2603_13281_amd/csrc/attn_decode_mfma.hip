@@ -1,0 +1,350 @@
+// Shared-KV paged GQA decode attention on gfx950 matrix cores (bf16 storage, head_dim 128,
+// block_size 16).
+//
+// All stacked queries of one sequence that share a kv-head -- (1 + m_s) streams x g heads --
+// form the N dimension of the MFMA tiles, so each KV block is fetched from HBM once for all
+// of the sequence's models.  A workgroup (4 waves) owns one (sequence, kv-head, token chunk);
+// wave w walks the chunk's 32-token groups w, w+4, ...  Per group a wave computes
+//     S^T[32 tok x G]  = K[32 tok x 128] . Q^T          (A = K straight from global memory)
+//     O^T[128 x G]    += V^T[128 x 32 tok] . P^T         (A = V^T straight from global memory)
+// with an online softmax on the S^T accumulators.  The cache layout (K token-major, V
+// transposed inside the block) makes every global load a 128-bit load that lands directly in
+// MFMA operand registers: no LDS staging and no register shuffles for P.
+//
+// MFMA 16x16x32 bf16 operand layout (lane l, q = l / 16):
+//   A[row l%16][k 8q..8q+7], B[k 8q..8q+7][col l%16], C[row 4q+i][col l%16] (i = 0..3).
+// Token <-> tile-row mapping inside a 32-token group (two KV blocks), chosen so that the 8
+// P values a lane owns after the two S^T tiles are 8 consecutive tokens of one block:
+//   S^T tile t, row 4q'+i'  <->  block q'/2, token-in-block 8(q'%2) + 4t + i'
+//   PV contraction index k = 8q + 4t + i  <->  block q/2, token-in-block 8(q%2) + 4t + i.
+#include "device_util.h"
+#include "kernels.h"
+
+namespace icarus {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+namespace {
+
+constexpr int kD = 128;       // head_dim
+constexpr int kBk = 16;       // tokens per block
+constexpr int kGrp = 32;      // tokens per wave iteration (two blocks)
+constexpr int kKS = kD / 32;  // k-steps of the QK^T contraction
+constexpr int kDT = kD / 16;  // d tiles of the PV product
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct KVFrag {
+    bf16x8 k[2][kKS];  // k[t][ks]: A operand of S^T tile t, k-step ks
+    bf16x8 v[kDT];     // v[dt]:    A operand of O^T tile dt
+};
+
+__device__ __forceinline__ bf16x8 zero8() {
+    bf16x8 z;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.f;
+    return z;
+}
+
+// Issue the 16 loads of one 32-token group.  blk0/blk1: physical block ids (wave-uniform).
+__device__ __forceinline__ void load_group(KVFrag &f, const bf16_t *__restrict__ pool, int blk0, int blk1, int c, int Hkv,
+                                           int lane) {
+    const int m = lane & 15, q = lane >> 4;
+    const size_t head_stride = (size_t)2 * kBk * kD;
+    // K rows: lane m reads block m/8, token-in-block 8((m/4)%2) + 4t + m%4, d = 32ks + 8q
+    const bf16_t *kb = pool + ((size_t)((m >> 3) ? blk1 : blk0) * Hkv + c) * head_stride;
+    const int tok0 = 8 * ((m >> 2) & 1) + (m & 3);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks)
+            f.k[t][ks] = *(const bf16x8 *)(kb + (size_t)(tok0 + 4 * t) * kD + 32 * ks + 8 * q);
+    // V^T rows: lane reads block q/2, d = 16dt + m, tokens 8(q%2) .. +7
+    const bf16_t *vb = pool + ((size_t)((q >> 1) ? blk1 : blk0) * Hkv + c) * head_stride + (size_t)kBk * kD;
+#pragma unroll
+    for (int dt = 0; dt < kDT; ++dt) f.v[dt] = *(const bf16x8 *)(vb + (size_t)(16 * dt + m) * kBk + 8 * (q & 1));
+}
+
+template <int NQT>
+struct State {
+    f32x4 o[kDT][NQT];  // O^T accumulators: [d 16dt + 4q + i][query 16qt + l%16]
+    float m[NQT];       // running max (log2 domain), uniform over the 4 lanes sharing a query
+    float l[NQT];       // running sum, per-lane partial (reduced over q at the end)
+};
+
+// One 32-token group: S^T, online softmax, PV, one 16-query tile at a time so that only one
+// tile's scores are live.  qlds: Q fragments in LDS as [qt][ks][lane] (B operands).
+// n_valid: valid tokens in this group (1..32).
+template <int NQT, bool tail>
+__device__ __forceinline__ void compute_group(State<NQT> &st, KVFrag &f, const bf16x8 *__restrict__ qlds, int n_valid,
+                                              float scale_log2, int lane) {
+    const int q = lane >> 4;
+    // token index inside the group of S^T element (tile t, register i) on this lane: tbase + 4t + i
+    const int tbase = 16 * (q >> 1) + 8 * (q & 1);
+    if (tail) {
+        // stale cache bytes past the end may hold anything: zero those V columns (scores are masked below)
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (tbase + e >= n_valid) f.v[dt][e] = (__bf16)0.f;
+    }
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) {
+            bf16x8 qv = qlds[(qt * kKS + ks) * 64 + lane];
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k[0][ks], qv, s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k[1][ks], qv, s1, 0, 0, 0);
+        }
+        float sv[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sv[i] = s0[i] * scale_log2;
+            sv[4 + i] = s1[i] * scale_log2;
+        }
+        if (tail) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (tbase + e >= n_valid) sv[e] = -INFINITY;
+        }
+        float mx = sv[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_old = st.m[qt];
+        const float m_new = fmaxf(m_old, mx);  // finite: every group has at least one valid token
+        st.m[qt] = m_new;
+        float rs = 0.f;
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float p = __builtin_amdgcn_exp2f(sv[e] - m_new);
+            rs += p;
+            pb[e] = (__bf16)p;
+        }
+        if (__any(m_new != m_old)) {  // the running max moved for some query of this tile: rescale
+            float alpha = __builtin_amdgcn_exp2f(m_old - m_new);
+            st.l[qt] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) {
+                st.o[dt][qt][0] *= alpha; st.o[dt][qt][1] *= alpha; st.o[dt][qt][2] *= alpha; st.o[dt][qt][3] *= alpha;
+            }
+        }
+        st.l[qt] += rs;
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt) st.o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v[dt], pb, st.o[dt][qt], 0, 0, 0);
+    }
+}
+
+// Merge another wave's state (read from LDS) into st.
+template <int NQT>
+__device__ __forceinline__ void merge_from_lds(State<NQT> &st, const float *__restrict__ lds, int lane) {
+    // LDS image of a state: o as [dt][qt][i][lane], then m[qt][lane], l[qt][lane]
+    const float *lo = lds;
+    const float *lm = lds + kDT * NQT * 4 * 64;
+    const float *ll = lm + NQT * 64;
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        float m2 = lm[qt * 64 + lane], l2 = ll[qt * 64 + lane];
+        float mn = fmaxf(st.m[qt], m2);
+        float a1 = st.m[qt] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(st.m[qt] - mn);
+        float a2 = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - mn);
+        st.m[qt] = mn;
+        st.l[qt] = st.l[qt] * a1 + l2 * a2;
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) st.o[dt][qt][i] = st.o[dt][qt][i] * a1 + lo[((dt * NQT + qt) * 4 + i) * 64 + lane] * a2;
+    }
+}
+template <int NQT>
+__device__ __forceinline__ void store_to_lds(const State<NQT> &st, float *__restrict__ lds, int lane) {
+    float *lo = lds;
+    float *lm = lds + kDT * NQT * 4 * 64;
+    float *ll = lm + NQT * 64;
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        lm[qt * 64 + lane] = st.m[qt];
+        ll[qt * 64 + lane] = st.l[qt];
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) lo[((dt * NQT + qt) * 4 + i) * 64 + lane] = st.o[dt][qt][i];
+    }
+}
+
+template <int NQT>
+__global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ qg, const bf16_t *__restrict__ pool,
+                                                     const int32_t *__restrict__ bt, int max_blocks, AttnPlan pl,
+                                                     bf16_t *__restrict__ out, float *__restrict__ part_o,
+                                                     float *__restrict__ part_ml, int Hq, int Hkv, float scale_log2) {
+    extern __shared__ float lds[];
+    const int item = blockIdx.x / Hkv, c = blockIdx.x % Hkv;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int s = pl.item_seq[item];
+    const int tok_begin = pl.item_begin[item];
+    const int kvlen = pl.seq_kvlen[s];
+    const int tok_end = min(tok_begin + pl.chunk, kvlen);
+    const int row0 = pl.seq_row0[s], T = pl.seq_rows[s];
+    const int g = Hq / Hkv, G = T * g;
+    const int m = lane & 15, q = lane >> 4;
+    const int32_t *btr = bt + (size_t)s * max_blocks;
+    const int last_blk = (kvlen - 1) / kBk;
+
+    // Q fragments (B operands) go to LDS once, as [qt][ks][lane]; wave w stages k-step w.
+    // query j = 16qt + m  ->  row row0 + j / g, head c*g + j % g; rows past G are zero.
+    constexpr int kImg = kDT * NQT * 4 * 64 + 2 * NQT * 64;  // floats per wave image of the merge
+    bf16x8 *qlds = (bf16x8 *)(lds + 2 * kImg);
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        int j = 16 * qt + m;
+        const bf16_t *qp = qg + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD + 8 * q + 32 * w;
+        qlds[(qt * kKS + w) * 64 + lane] = j < G ? *(const bf16x8 *)qp : zero8();
+    }
+    __syncthreads();
+    State<NQT> st;
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        st.m[qt] = -INFINITY;
+        st.l[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt) st.o[dt][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // wave w takes groups w, w+4, ... of the chunk.  Full groups run in a loop with two register
+    // buffers, loads issued one group ahead; the chunk's one partial group (if any) is done last.
+    const int n_tok = tok_end - tok_begin;
+    const int n_full = n_tok / kGrp, rem = n_tok % kGrp;
+    auto blk_of = [&](int grp, int which) {
+        int b = (tok_begin + grp * kGrp) / kBk + which;
+        return __builtin_amdgcn_readfirstlane(btr[min(b, last_blk)]);
+    };
+    KVFrag f0, f1;
+    if (w < n_full) load_group(f0, pool, blk_of(w, 0), blk_of(w, 1), c, Hkv, lane);
+#pragma nounroll
+    for (int grp = w; grp < n_full; grp += 8) {
+        if (grp + 4 < n_full) load_group(f1, pool, blk_of(grp + 4, 0), blk_of(grp + 4, 1), c, Hkv, lane);
+        compute_group<NQT, false>(st, f0, qlds, kGrp, scale_log2, lane);
+        if (grp + 8 < n_full) load_group(f0, pool, blk_of(grp + 8, 0), blk_of(grp + 8, 1), c, Hkv, lane);
+        if (grp + 4 < n_full) compute_group<NQT, false>(st, f1, qlds, kGrp, scale_log2, lane);
+    }
+    if (rem && (n_full & 3) == w) {
+        load_group(f0, pool, blk_of(n_full, 0), blk_of(n_full, 1), c, Hkv, lane);
+        compute_group<NQT, true>(st, f0, qlds, rem, scale_log2, lane);
+    }
+
+    // tree merge of the four waves through LDS: (2,3) -> (0,1), then 1 -> 0
+    if (w >= 2) store_to_lds<NQT>(st, lds + (w - 2) * kImg, lane);
+    __syncthreads();
+    if (w < 2) merge_from_lds<NQT>(st, lds + w * kImg, lane);
+    __syncthreads();
+    if (w == 1) store_to_lds<NQT>(st, lds, lane);
+    __syncthreads();
+    if (w != 0) return;
+    merge_from_lds<NQT>(st, lds, lane);
+
+    // finish: reduce l over the 4 lanes of a query, then write the final output or a partial
+    const int direct = pl.item_direct[item];
+    const int slot = pl.item_part[item];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        float l = st.l[qt];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        int j = 16 * qt + m;
+        if (j >= G) continue;
+        if (direct) {
+            float inv = 1.f / l;
+            bf16_t *op = out + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD;
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) {
+                uint2 pk;
+                pk.x = (uint32_t)f32_to_bf16(st.o[dt][qt][0] * inv) | ((uint32_t)f32_to_bf16(st.o[dt][qt][1] * inv) << 16);
+                pk.y = (uint32_t)f32_to_bf16(st.o[dt][qt][2] * inv) | ((uint32_t)f32_to_bf16(st.o[dt][qt][3] * inv) << 16);
+                *(uint2 *)(op + 16 * dt + 4 * q) = pk;
+            }
+        } else {
+            size_t pj = ((size_t)slot * Hkv + c) * pl.g_max + j;
+            float *po = part_o + pj * kD;
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) *(f32x4 *)(po + 16 * dt + 4 * q) = st.o[dt][qt];
+            if (q == 0) {
+                part_ml[pj * 2] = st.m[qt];
+                part_ml[pj * 2 + 1] = l;
+            }
+        }
+    }
+}
+
+// Combine the partial results of sequences that were split into several chunks.
+// One block of 128 threads per (row, query head); thread d owns output element d.
+__global__ void __launch_bounds__(128) k_attn_merge(const float *__restrict__ part_o, const float *__restrict__ part_ml,
+                                                    AttnPlan pl, const int32_t *__restrict__ row_seq,
+                                                    bf16_t *__restrict__ out, int Hq, int Hkv) {
+    const int row = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
+    const int s = row_seq[row];
+    const int np = pl.seq_nparts[s];
+    if (np <= 1) return;  // written directly by the attention kernel
+    const int g = Hq / Hkv, c = h / g;
+    const int j = (row - pl.seq_row0[s]) * g + h % g;
+    const int p0 = pl.seq_part0[s];
+    float M = -INFINITY;
+    for (int p = 0; p < np; ++p) M = fmaxf(M, part_ml[(((size_t)(p0 + p) * Hkv + c) * pl.g_max + j) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int p = 0; p < np; ++p) {
+        size_t pj = ((size_t)(p0 + p) * Hkv + c) * pl.g_max + j;
+        float wgt = __builtin_amdgcn_exp2f(part_ml[pj * 2] - M);
+        den += wgt * part_ml[pj * 2 + 1];
+        num += wgt * part_o[pj * kD + d];
+    }
+    out[((size_t)row * Hq + h) * kD + d] = f32_to_bf16(num / den);
+}
+
+template <int NQT>
+hipError_t launch_one(const void *q, const void *pool, const int32_t *bt, int max_blocks, const AttnPlan &pl, void *out,
+                      float *part_o, float *part_ml, int Hq, int Hkv, float scale_log2, hipStream_t st) {
+    constexpr int kImg = kDT * NQT * 4 * 64 + 2 * NQT * 64;
+    size_t shm = (size_t)2 * kImg * sizeof(float) + (size_t)NQT * kKS * 64 * 16;  // merge images + Q fragments
+    static bool attr_set = false;  // per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_attn_decode<NQT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_attn_decode<NQT>, dim3(pl.n_items * Hkv), dim3(256), shm, st, (const bf16_t *)q, (const bf16_t *)pool, bt,
+                       max_blocks, pl, (bf16_t *)out, part_o, part_ml, Hq, Hkv, scale_log2);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool attn_decode_mfma_supported(const Dims &dm, int g_max) {
+    return dm.bf16 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= 80;
+}
+
+hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
+                                   const AttnPlan &pl, void *out, float *part_o, float *part_ml, hipStream_t st) {
+    if (pl.n_items <= 0) return hipSuccess;
+    float scale_log2 = kLog2e / sqrtf((float)dm.D);
+    int nqt = (pl.g_max + 15) / 16;
+    switch (nqt) {
+    case 1: return launch_one<1>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 2: return launch_one<2>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 3: return launch_one<3>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 4: return launch_one<4>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 5: return launch_one<5>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_attn_merge(const Dims &dm, const float *part_o, const float *part_ml, const AttnPlan &pl,
+                             const int32_t *row_seq, void *out, int R, hipStream_t st) {
+    if (R <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_attn_merge, dim3(dm.Hq, R), dim3(128), 0, st, part_o, part_ml, pl, row_seq, (bf16_t *)out, dm.Hq, dm.Hkv);
+    return hipGetLastError();
+}
+
+}  // namespace icarus

@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -33,15 +34,32 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace
 
+struct PhaseTimer {
+    bool on = false;
+    struct Span { int phase; hipEvent_t a, b; };
+    std::vector<Span> pending;
+    std::vector<hipEvent_t> pool;
+    double ms[ICARUS_NPHASE] = {0};
+    int32_t launches[ICARUS_NPHASE] = {0};
+    hipEvent_t get() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        (void)hipEventCreate(&e);
+        return e;
+    }
+};
+
 struct icarus_ctx {
     icarus_layer_config cfg;
     icarus_base_weights base;
     icarus_lora_weights lora;
     Dims dm;
     int mode = 0;
+    int attn_chunk_override = 0;  // tokens per attention chunk; 0 = automatic (ICARUS_ATTN_CHUNK, for experiments)
     char err[512];
     StageSlot slots[kSlots];
     int next_slot = 0;
+    PhaseTimer timer;
     std::mutex mu;
 };
 
@@ -81,9 +99,15 @@ bool has_lora(const icarus_ctx *ctx, int p) {
 
 // ---- workspace layout ---------------------------------------------------------------
 struct WsLayout {
-    size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, total;
-    size_t meta_ints;
+    size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, part_o, part_ml, total;
+    size_t meta_ints, max_items;
 };
+
+constexpr int kAttnTargetWgs = 2048;  // decode attention: aim for about this many workgroups
+constexpr int kAttnGMax = 80;         // largest stacked query group the MFMA attention covers
+
+// Upper bounds used for sizing: chunks (= partial slots) of a call and its largest stacked group.
+size_t attn_max_items(const icarus_ctx *ctx, size_t seqs) { return (size_t)kAttnTargetWgs / ctx->cfg.n_kv_heads + seqs + 1; }
 
 WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t /*max_ctx*/) {
     const icarus_layer_config &c = ctx->cfg;
@@ -92,8 +116,16 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t /*max
     WsLayout w{};
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    w.meta_ints = 4 * rows + 4 * seqs + 64;
+    w.max_items = attn_max_items(ctx, seqs);
+    w.meta_ints = 4 * rows + 5 * seqs + 4 * w.max_items + 64;
     w.meta = take(w.meta_ints * 4);
+    {
+        size_t g = (size_t)c.n_q_heads / c.n_kv_heads;
+        size_t g_bound = std::min<size_t>(kAttnGMax, rows * g);
+        size_t pj = w.max_items * c.n_kv_heads * g_bound;
+        w.part_o = take(pj * c.head_dim * 4);
+        w.part_ml = take(pj * 2 * 4);
+    }
     w.xn = take(rows * c.d_model * es);
     w.qkv = take(rows * (qd + 2 * kvd) * 4);
     w.q = take(rows * qd * es);
@@ -151,6 +183,16 @@ icarus_status stage_commit(icarus_ctx *ctx, StageSlot *s, void *dev, size_t byte
         if (e__ != hipSuccess) return fail(ctx, ICARUS_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e__)); \
     } while (0)
 
+// Run one launch; with phase timing on, bracket it with events on the launch stream.
+#define PHASE(ctx, st, phase, expr)                                                 \
+    do {                                                                            \
+        PhaseTimer &tm__ = (ctx)->timer;                                            \
+        hipEvent_t a__ = nullptr, b__ = nullptr;                                    \
+        if (tm__.on) { a__ = tm__.get(); b__ = tm__.get(); (void)hipEventRecord(a__, st); } \
+        HIP_TRY(ctx, expr);                                                         \
+        if (tm__.on) { (void)hipEventRecord(b__, st); tm__.pending.push_back({phase, a__, b__}); } \
+    } while (0)
+
 // ---- validation ----------------------------------------------------------------------
 icarus_status check_decode_rows(icarus_ctx *ctx, int32_t max_blocks, int32_t S, const int32_t *ctx_lens, int32_t R,
                                 const int32_t *row_seq, const int32_t *row_model) {
@@ -198,9 +240,94 @@ icarus_status check_common_ptrs(icarus_ctx *ctx, const void *pool, const void *b
     return ICARUS_OK;
 }
 
+// ---- decode-attention split plan --------------------------------------------------------
+// Cuts every sequence's kv_len tokens into chunks of `chunk` tokens (a multiple of 128 chosen so
+// that chunks x kv-heads is about kAttnTargetWgs) and writes the plan's int32 arrays into the
+// host staging buffer `m` starting at int offset `at`; `dmeta` is the device address the buffer
+// will be copied to.  seq_row0 / seq_rows: rows of each sequence.  Returns ints used, 0 if the
+// matrix-core attention does not cover this call (then the generic kernel runs).
+struct HostPlan {
+    AttnPlan pl;
+    bool valid = false, has_split = false;
+    size_t ints = 0;
+};
+
+void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t *dmeta, int S, const int32_t *kv_lens,
+                     const int32_t *seq_row0, const int32_t *seq_rows, size_t max_items, HostPlan *hp) {
+    AttnPlan *pl = &hp->pl;
+    hp->valid = false;
+    hp->has_split = false;
+    hp->ints = 0;
+    const icarus_layer_config &c = ctx->cfg;
+    if (ctx->mode != 0) return;
+    int g = c.n_q_heads / c.n_kv_heads, g_max = 0;
+    int64_t total = 0;
+    for (int s = 0; s < S; ++s) {
+        if (seq_rows[s] > 0 && kv_lens[s] <= 0) return;  // empty context: generic kernel writes zeros
+        g_max = std::max(g_max, seq_rows[s] * g);
+        if (seq_rows[s] > 0) total += kv_lens[s];
+    }
+    if (!attn_decode_mfma_supported(ctx->dm, g_max) || g_max > kAttnGMax) return;
+    int64_t chunk = (total * c.n_kv_heads + kAttnTargetWgs - 1) / kAttnTargetWgs;
+    if (ctx->attn_chunk_override > 0) chunk = ctx->attn_chunk_override;
+    chunk = std::max<int64_t>(128, (chunk + 127) / 128 * 128);
+    size_t n_items = 0;
+    for (int s = 0; s < S; ++s)
+        if (seq_rows[s] > 0) n_items += (size_t)((kv_lens[s] + chunk - 1) / chunk);
+    if (n_items > max_items) return;
+    int32_t *item_seq = m + at, *item_begin = item_seq + n_items, *item_part = item_begin + n_items,
+            *item_direct = item_part + n_items, *seq_kvlen = item_direct + n_items, *row0 = seq_kvlen + S,
+            *rows = row0 + S, *part0 = rows + S, *nparts = part0 + S;
+    size_t it = 0;
+    for (int s = 0; s < S; ++s) {
+        int np = seq_rows[s] > 0 ? (int)((kv_lens[s] + chunk - 1) / chunk) : 0;
+        seq_kvlen[s] = kv_lens[s];
+        row0[s] = seq_row0[s];
+        rows[s] = seq_rows[s];
+        part0[s] = (int32_t)it;
+        nparts[s] = np;
+        for (int p = 0; p < np; ++p, ++it) {
+            item_seq[it] = s;
+            item_begin[it] = (int32_t)(p * chunk);
+            item_part[it] = (int32_t)it;
+            item_direct[it] = np == 1;
+            if (np > 1) hp->has_split = true;
+        }
+    }
+    const int32_t *d = dmeta + at;
+    pl->item_seq = d;
+    pl->item_begin = d + n_items;
+    pl->item_part = d + 2 * n_items;
+    pl->item_direct = d + 3 * n_items;
+    pl->seq_kvlen = d + 4 * n_items;
+    pl->seq_row0 = pl->seq_kvlen + S;
+    pl->seq_rows = pl->seq_row0 + S;
+    pl->seq_part0 = pl->seq_rows + S;
+    pl->seq_nparts = pl->seq_part0 + S;
+    pl->n_items = (int)n_items;
+    pl->chunk = (int)chunk;
+    pl->g_max = g_max;
+    hp->ints = 4 * n_items + 5 * (size_t)S;
+    hp->valid = n_items > 0;
+}
+
+// Attention of decode rows: matrix-core kernel + merge when a plan exists, else the generic kernel.
+icarus_status run_decode_attention(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp,
+                                   const void *q, const void *pool, const int32_t *bt, int max_blocks, void *out, int R,
+                                   hipStream_t st) {
+    if (!hp || !hp->valid) {
+        PHASE(ctx, st, ICARUS_PH_ATTN, launch_attn_generic(ctx->dm, q, pool, bt, max_blocks, rm, out, R, st));
+        return ICARUS_OK;
+    }
+    float *part_o = (float *)(ws + L.part_o), *part_ml = (float *)(ws + L.part_ml);
+    PHASE(ctx, st, ICARUS_PH_ATTN, launch_attn_decode_mfma(ctx->dm, q, pool, bt, max_blocks, hp->pl, out, part_o, part_ml, st));
+    if (hp->has_split) PHASE(ctx, st, ICARUS_PH_ATTN_MERGE, launch_attn_merge(ctx->dm, part_o, part_ml, hp->pl, rm.row_seq, out, R, st));
+    return ICARUS_OK;
+}
+
 // ---- the layer, after metadata is on the device ---------------------------------------
 // rows: x_in [R, d].  use_lora: decoder rows get adapter deltas.  kv_only: stop after the append.
-icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, int R, bool use_lora, bool kv_only,
+icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp, int R, bool use_lora, bool kv_only,
                         int slot_by_row, void *pool, const int32_t *bt, int max_blocks, const void *x_in, void *x_out,
                         int64_t *slot_out, hipStream_t st) {
     const icarus_layer_config &c = ctx->cfg;
@@ -209,35 +336,36 @@ icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowM
     int ldq = qd + 2 * kvd;
     void *xn = ws + L.xn, *q = ws + L.q, *attn = ws + L.attn, *z = ws + L.z, *h = ws + L.h;
     float *qkv = (float *)(ws + L.qkv), *fa = (float *)(ws + L.f32a), *fb = (float *)(ws + L.f32b), *t = (float *)(ws + L.t);
-    auto lora = [&](int p, const void *X, int ldx, float *Y, int ldy) -> hipError_t {
-        if (!use_lora || !has_lora(ctx, p)) return hipSuccess;
-        hipError_t e = launch_lora_shrink_generic(dm, X, ldx, ctx->lora.A[p], proj_in(c, p), rm.row_model, t, R, st);
-        if (e != hipSuccess) return e;
-        return launch_lora_expand_generic(dm, t, ctx->lora.B[p], proj_out(c, p), rm.row_model, Y, ldy, R, st);
+    auto lora = [&](int p, const void *X, int ldx, float *Y, int ldy) -> icarus_status {
+        if (!use_lora || !has_lora(ctx, p)) return ICARUS_OK;
+        PHASE(ctx, st, ICARUS_PH_LORA, launch_lora_shrink_generic(dm, X, ldx, ctx->lora.A[p], proj_in(c, p), rm.row_model, t, R, st));
+        PHASE(ctx, st, ICARUS_PH_LORA, launch_lora_expand_generic(dm, t, ctx->lora.B[p], proj_out(c, p), rm.row_model, Y, ldy, R, st));
+        return ICARUS_OK;
     };
-    HIP_TRY(ctx, launch_rmsnorm(dm, x_in, ctx->base.norm_attn, xn, R, d, st));
+#define LORA_TRY(call) do { icarus_status rc__ = (call); if (rc__) return rc__; } while (0)
+    PHASE(ctx, st, ICARUS_PH_NORM, launch_rmsnorm(dm, x_in, ctx->base.norm_attn, xn, R, d, st));
     if (!kv_only) {
-        HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_Q], R, qd, d, qkv, ldq, st));
-        HIP_TRY(ctx, lora(ICARUS_PROJ_Q, xn, d, qkv, ldq));
+        PHASE(ctx, st, ICARUS_PH_GEMM_QKV, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_Q], R, qd, d, qkv, ldq, st));
+        LORA_TRY(lora(ICARUS_PROJ_Q, xn, d, qkv, ldq));
     }
-    HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_K], R, kvd, d, qkv + qd, ldq, st));
-    HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_V], R, kvd, d, qkv + qd + kvd, ldq, st));
-    HIP_TRY(ctx, launch_rope_append(dm, qkv, ldq, rm, bt, max_blocks, pool, q, slot_out, slot_by_row, ctx->base.q_norm,
-                                    ctx->base.k_norm, R, st));
+    PHASE(ctx, st, ICARUS_PH_GEMM_QKV, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_K], R, kvd, d, qkv + qd, ldq, st));
+    PHASE(ctx, st, ICARUS_PH_GEMM_QKV, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_V], R, kvd, d, qkv + qd + kvd, ldq, st));
+    PHASE(ctx, st, ICARUS_PH_ROPE_APPEND, launch_rope_append(dm, qkv, ldq, rm, bt, max_blocks, pool, q, slot_out, slot_by_row,
+                                                             ctx->base.q_norm, ctx->base.k_norm, R, st));
     if (kv_only) return ICARUS_OK;
-    HIP_TRY(ctx, launch_attn_generic(dm, q, pool, bt, max_blocks, rm, attn, R, st));
-    HIP_TRY(ctx, launch_gemm_generic(dm, attn, qd, ctx->base.w[ICARUS_PROJ_O], R, d, qd, fa, d, st));
-    HIP_TRY(ctx, lora(ICARUS_PROJ_O, attn, qd, fa, d));
-    HIP_TRY(ctx, launch_resid_store(dm, x_in, fa, z, R, d, st));
-    HIP_TRY(ctx, launch_rmsnorm(dm, z, ctx->base.norm_ffn, xn, R, d, st));
-    HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_GATE], R, F, d, fa, F, st));
-    HIP_TRY(ctx, lora(ICARUS_PROJ_GATE, xn, d, fa, F));
-    HIP_TRY(ctx, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_UP], R, F, d, fb, F, st));
-    HIP_TRY(ctx, lora(ICARUS_PROJ_UP, xn, d, fb, F));
-    HIP_TRY(ctx, launch_silu_mul(dm, fa, fb, h, R, F, st));
-    HIP_TRY(ctx, launch_gemm_generic(dm, h, F, ctx->base.w[ICARUS_PROJ_DOWN], R, d, F, fa, d, st));
-    HIP_TRY(ctx, lora(ICARUS_PROJ_DOWN, h, F, fa, d));
-    HIP_TRY(ctx, launch_resid_store(dm, z, fa, x_out, R, d, st));
+    LORA_TRY(run_decode_attention(ctx, ws, L, rm, hp, q, pool, bt, max_blocks, attn, R, st));
+    PHASE(ctx, st, ICARUS_PH_GEMM_O, launch_gemm_generic(dm, attn, qd, ctx->base.w[ICARUS_PROJ_O], R, d, qd, fa, d, st));
+    LORA_TRY(lora(ICARUS_PROJ_O, attn, qd, fa, d));
+    PHASE(ctx, st, ICARUS_PH_ELEMWISE, launch_resid_store(dm, x_in, fa, z, R, d, st));
+    PHASE(ctx, st, ICARUS_PH_NORM, launch_rmsnorm(dm, z, ctx->base.norm_ffn, xn, R, d, st));
+    PHASE(ctx, st, ICARUS_PH_GEMM_GATEUP, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_GATE], R, F, d, fa, F, st));
+    LORA_TRY(lora(ICARUS_PROJ_GATE, xn, d, fa, F));
+    PHASE(ctx, st, ICARUS_PH_GEMM_GATEUP, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_UP], R, F, d, fb, F, st));
+    LORA_TRY(lora(ICARUS_PROJ_UP, xn, d, fb, F));
+    PHASE(ctx, st, ICARUS_PH_ELEMWISE, launch_silu_mul(dm, fa, fb, h, R, F, st));
+    PHASE(ctx, st, ICARUS_PH_GEMM_DOWN, launch_gemm_generic(dm, h, F, ctx->base.w[ICARUS_PROJ_DOWN], R, d, F, fa, d, st));
+    LORA_TRY(lora(ICARUS_PROJ_DOWN, h, F, fa, d));
+    PHASE(ctx, st, ICARUS_PH_ELEMWISE, launch_resid_store(dm, z, fa, x_out, R, d, st));
     return ICARUS_OK;
 }
 
@@ -291,12 +419,15 @@ icarus_status icarus_create(const icarus_layer_config *cfg, const icarus_base_we
     dm.d = c.d_model; dm.Hq = c.n_q_heads; dm.Hkv = c.n_kv_heads; dm.D = c.head_dim; dm.F = c.d_ffn; dm.Bk = c.block_size;
     dm.M = c.n_models; dm.r = c.lora_rank; dm.bf16 = c.dtype == ICARUS_BF16; dm.qk_norm = c.qk_norm != 0;
     dm.theta = c.rope_theta; dm.eps = (float)c.rms_eps; dm.lora_scale = (float)c.lora_scale;
+    if (const char *e = getenv("ICARUS_ATTN_CHUNK")) ctx->attn_chunk_override = atoi(e);
     *out = ctx;
     return ICARUS_OK;
 }
 
 void icarus_destroy(icarus_ctx *ctx) {
     if (!ctx) return;
+    for (auto &sp : ctx->timer.pending) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+    for (auto e : ctx->timer.pool) (void)hipEventDestroy(e);
     for (auto &s : ctx->slots) {
         if (s.in_flight && s.ev) (void)hipEventSynchronize(s.ev);
         if (s.ev) (void)hipEventDestroy(s.ev);
@@ -309,6 +440,36 @@ icarus_status icarus_set_kernel_mode(icarus_ctx *ctx, int32_t mode) {
     if (!ctx) return ICARUS_ERR_INVALID_ARG;
     if (mode != 0 && mode != 1) return fail(ctx, ICARUS_ERR_INVALID_ARG, "kernel mode %d unknown", mode);
     ctx->mode = mode;
+    return ICARUS_OK;
+}
+
+icarus_status icarus_timing_enable(icarus_ctx *ctx, int32_t on) {
+    if (!ctx) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    ctx->timer.on = on != 0;
+    return ICARUS_OK;
+}
+
+icarus_status icarus_timing_read(icarus_ctx *ctx, double *ms, int32_t *launches) {
+    if (!ctx || !ms || !launches) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    PhaseTimer &tm = ctx->timer;
+    for (auto &sp : tm.pending) {
+        HIP_TRY(ctx, hipEventSynchronize(sp.b));
+        float t = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&t, sp.a, sp.b));
+        tm.ms[sp.phase] += t;
+        tm.launches[sp.phase] += 1;
+        tm.pool.push_back(sp.a);
+        tm.pool.push_back(sp.b);
+    }
+    tm.pending.clear();
+    for (int i = 0; i < ICARUS_NPHASE; ++i) {
+        ms[i] = tm.ms[i];
+        launches[i] = tm.launches[i];
+        tm.ms[i] = 0;
+        tm.launches[i] = 0;
+    }
     return ICARUS_OK;
 }
 
@@ -342,22 +503,27 @@ icarus_status icarus_decode_step(icarus_ctx *ctx, void *kv_pool, const int32_t *
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     StageSlot *slot;
-    size_t meta_bytes = (size_t)4 * R * 4;
-    rc = stage_acquire(ctx, meta_bytes, &slot);
+    rc = stage_acquire(ctx, L.meta_ints * 4, &slot);
     if (rc) return rc;
     int32_t *m = (int32_t *)slot->host;
+    std::vector<int32_t> kvl((size_t)S), row0((size_t)S, 0), rows((size_t)S, 0);
     for (int r = 0; r < R; ++r) {
-        m[r] = row_seq[r];
+        int s = row_seq[r];
+        m[r] = s;
         m[R + r] = row_model[r];
-        m[2 * R + r] = ctx_lens[row_seq[r]];
-        m[3 * R + r] = ctx_lens[row_seq[r]] + 1;
+        m[2 * R + r] = ctx_lens[s];
+        m[3 * R + r] = ctx_lens[s] + 1;
+        if (rows[s]++ == 0) row0[s] = r;
     }
+    for (int s = 0; s < S; ++s) kvl[s] = ctx_lens[s] + 1;
     char *ws = (char *)workspace;
-    rc = stage_commit(ctx, slot, ws + L.meta, meta_bytes, st);
-    if (rc) return rc;
     const int32_t *dmeta = (const int32_t *)(ws + L.meta);
+    HostPlan hp;
+    build_attn_plan(ctx, m, (size_t)4 * R, dmeta, S, kvl.data(), row0.data(), rows.data(), L.max_items, &hp);
+    rc = stage_commit(ctx, slot, ws + L.meta, ((size_t)4 * R + hp.ints) * 4, st);
+    if (rc) return rc;
     RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
-    return run_layer(ctx, ws, L, rm, R, true, false, 0, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
+    return run_layer(ctx, ws, L, rm, &hp, R, true, false, 0, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
 }
 
 icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *block_tables, int32_t max_blocks, int32_t S,
@@ -408,7 +574,7 @@ icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *b
     if (rc) return rc;
     const int32_t *dmeta = (const int32_t *)(ws + L.meta);
     RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
-    return run_layer(ctx, ws, L, rm, R, false, x_out == nullptr, 1, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
+    return run_layer(ctx, ws, L, rm, nullptr, R, false, x_out == nullptr, 1, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
 }
 
 icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *kv_pool, const int32_t *block_tables,
@@ -440,23 +606,26 @@ icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     StageSlot *slot;
-    size_t meta_bytes = (size_t)4 * R * 4;
-    rc = stage_acquire(ctx, meta_bytes, &slot);
+    rc = stage_acquire(ctx, L.meta_ints * 4, &slot);
     if (rc) return rc;
     int32_t *m = (int32_t *)slot->host;
+    std::vector<int32_t> row0((size_t)S, 0), rows((size_t)S, 0);
     for (int r = 0; r < R; ++r) {
-        m[r] = row_seq[r];
+        int s = row_seq[r];
+        m[r] = s;
         m[R + r] = 0;
-        m[2 * R + r] = kv_lens[row_seq[r]] - 1;
-        m[3 * R + r] = kv_lens[row_seq[r]];
+        m[2 * R + r] = kv_lens[s] - 1;
+        m[3 * R + r] = kv_lens[s];
+        if (rows[s]++ == 0) row0[s] = r;
     }
     char *ws = (char *)workspace;
-    rc = stage_commit(ctx, slot, ws + L.meta, meta_bytes, st);
-    if (rc) return rc;
     const int32_t *dmeta = (const int32_t *)(ws + L.meta);
+    HostPlan hp;
+    build_attn_plan(ctx, m, (size_t)4 * R, dmeta, S, kv_lens, row0.data(), rows.data(), L.max_items, &hp);
+    rc = stage_commit(ctx, slot, ws + L.meta, ((size_t)4 * R + hp.ints) * 4, st);
+    if (rc) return rc;
     RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
-    HIP_TRY(ctx, launch_attn_generic(ctx->dm, q, kv_pool, block_tables, max_blocks, rm, out, R, st));
-    return ICARUS_OK;
+    return run_decode_attention(ctx, ws, L, rm, &hp, q, kv_pool, block_tables, max_blocks, out, R, st);
 }
 
 }  // extern "C"

@@ -48,4 +48,26 @@ hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, const R
 hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
                                const RowMeta &rm, void *out, int R, hipStream_t st);
 
+// ---- matrix-core kernels (bf16 storage) ------------------------------------------------------
+// Host-built split plan of the decode attention: a sequence's cached tokens are cut into chunks
+// of `chunk` tokens; one workgroup per (chunk, kv-head).  All arrays are device int32.
+struct AttnPlan {
+    const int32_t *item_seq;     // [n_items] sequence of the chunk
+    const int32_t *item_begin;   // [n_items] first token of the chunk
+    const int32_t *item_part;    // [n_items] partial-result slot of the chunk
+    const int32_t *item_direct;  // [n_items] 1: the sequence has a single chunk, write the final output
+    const int32_t *seq_kvlen;    // [S] tokens to attend to
+    const int32_t *seq_row0;     // [S] first row of the sequence
+    const int32_t *seq_rows;     // [S] rows (stacked streams) of the sequence
+    const int32_t *seq_part0;    // [S] first partial slot
+    const int32_t *seq_nparts;   // [S] number of chunks
+    int n_items, chunk, g_max;   // g_max: largest stacked group (rows * Hq/Hkv) in the call
+};
+bool attn_decode_mfma_supported(const Dims &dm, int g_max);
+// part_o: fp32 [slots, Hkv, g_max, D]; part_ml: fp32 [slots, Hkv, g_max, 2] (max in log2 units, sum)
+hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
+                                   const AttnPlan &pl, void *out, float *part_o, float *part_ml, hipStream_t st);
+hipError_t launch_attn_merge(const Dims &dm, const float *part_o, const float *part_ml, const AttnPlan &pl,
+                             const int32_t *row_seq, void *out, int R, hipStream_t st);
+
 }  // namespace icarus

@@ -272,3 +272,30 @@ def test_errors_surface_through_the_binding():
     with pytest.raises(IcarusError) as e:
         layer.decode_step(dpool, bt, [10_000], [0, 0], [-1, 0], x)
     assert e.value.status_name == "CAPACITY"
+
+
+@pytest.mark.parametrize("chunk", [0, 128, 256])
+@pytest.mark.parametrize("g,rows", [(4, 1), (4, 4), (4, 9), (8, 2), (8, 7), (8, 9), (1, 3)])
+def test_attn_mfma_tiles_splits_and_tails(g, rows, chunk, monkeypatch):
+    # matrix-core attention: every query-tile count (1..5 tiles of 16 stacked queries), single-chunk and
+    # split sequences, lengths around the 16-token block, 32-token group and 128-token chunk boundaries
+    _say("case: mfma attention g", g, "rows", rows, "chunk", chunk)
+    if chunk:
+        monkeypatch.setenv("ICARUS_ATTN_CHUNK", str(chunk))
+    shape = synth.LLAMA_SMALL.replace(n_q_heads=2 * g, n_kv_heads=2, d_model=256, n_models=8)
+    lens = [1, 15, 16, 17, 31, 32, 33, 127, 128, 129, 255, 257, 1000, 3001]
+    rows_per_seq = [rows if i % 3 else max(1, rows - 1) for i in range(len(lens))]
+    batch = synth.make_batch(shape, lens, [0] * len(lens), seed=8, headroom=0)
+    pool = filled_batch(shape, batch, seed=8)
+    pool[pool == 0] = np.nan          # unwritten slots hold NaN: masked positions must not leak
+    row_seq = np.repeat(np.arange(len(lens)), rows_per_seq).astype(np.int32)
+    R = len(row_seq)
+    rng = np.random.default_rng(9)
+    q = synth.to_storage(rng.standard_normal((R, shape.n_q_heads, shape.head_dim)).astype(np.float32) * 2, True)
+    orc = oracle.Oracle(oracle_config(shape, batch.num_blocks), synth.make_base(shape), None)
+    want = orc.attn_shared_kv(q, pool, batch.block_tables, lens, row_seq)
+    layer = make_layer(shape, synth.make_base(shape), None, batch.num_blocks)
+    dpool = dev(pool_to_device_layout(pool), True)
+    got = layer.attn_shared_kv(dev(q, True), dpool, torch.from_numpy(batch.block_tables).cuda(), lens, row_seq)
+    torch.cuda.synchronize()
+    assert_close(host(got), want, 2e-2, "attention out")
