@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the ICaRus shared-KV layer step on one MI355X.
+
+A "step" is one pass of the whole hot path -- icarus_decode_step: norms, stacked base GEMMs with the
+per-model LoRA deltas, RoPE + paged append of the encoder K/V, shared-KV attention of every stream,
+O projection and SwiGLU FFN -- over one batch of seeded synthetic input already resident in HBM.
+
+Prints ONE JSON line: decoder tokens/s per layer step (all M models), the roofline of the dominant
+kernel measured live with HIP events on the launch stream, and the CPU oracle timed on a bounded
+sample of the same workload (which also serves as a parity check of that sample).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+METRIC = "decode tokens/s (all M models) per layer step; shared-KV attn HBM GB/s"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def phase_model(wl, step):
+    """Algorithmic bytes and flops of one launch group per phase (weights and caches read once,
+    activations in and out once)."""
+    s, b = wl.shape, wl.batch
+    es = 2
+    R, Rd, S = b.R, b.n_decoder_rows, b.S
+    d, F, qd, kvd, r, M = s.d_model, s.d_ffn, s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim, s.lora_rank, s.n_models
+    lora_b = lambda n_out: M * n_out * r * es
+    kv_tokens = int((wl.ctx_lens(step).astype("int64") + 1).sum())
+    att_flops = 4 * s.head_dim * s.n_q_heads * sum(int(wl.ctx_lens(step)[q] + 1) for q in b.row_seq)
+    return {
+        "attn": dict(bytes=wl.kv_bytes(step) + wl.qo_bytes(), flops=att_flops),
+        "gemm_qkv": dict(bytes=(qd + 2 * kvd) * d * es + lora_b(qd) + R * d * es + R * (qd + 2 * kvd) * 4,
+                         flops=2 * R * d * (qd + 2 * kvd) + 2 * R * M * r * qd),
+        "gemm_o": dict(bytes=d * qd * es + lora_b(d) + R * qd * es + 2 * R * d * es, flops=2 * R * d * qd + 2 * R * M * r * d),
+        "gemm_gateup": dict(bytes=2 * F * d * es + 2 * lora_b(F) + R * d * es + R * F * es,
+                            flops=4 * R * d * F + 4 * R * M * r * F),
+        "gemm_down": dict(bytes=d * F * es + lora_b(d) + R * F * es + 2 * R * d * es, flops=2 * R * d * F + 2 * R * M * r * d),
+        "kv_tokens": kv_tokens,
+    }
+
+
+def run_steps(wl, n, first_step, x_out):
+    for i in range(n):
+        st = first_step + i
+        wl.layer.decode_step(wl.pool, wl.block_tables, wl.ctx_lens(st), wl.batch.row_seq, wl.batch.row_model,
+                             wl.x[st % len(wl.x)], x_out=x_out)
+
+
+def cpu_baseline(wl, step, x_dev_out, budget_seqs=2):
+    """Oracle on a seeded sample of sequences (all their rows) of the same step: time + parity."""
+    import numpy as np
+    import torch
+    import oracle
+    from helpers import assert_close, fill_pool
+    from paper_2603_13281_amd import workloads
+
+    sh, b = wl.shape, wl.batch
+    rng = np.random.default_rng(12345)
+    order = rng.permutation(b.S)
+    # prefer a sample of moderate cost: sequences in seeded random order until ~budget reached
+    sample = [int(s) for s in order[:budget_seqs]]
+    ctx = wl.ctx_lens(step)
+    rows = np.flatnonzero(np.isin(b.row_seq, sample))
+    # compact pool for the sampled sequences
+    Bk = sh.block_size
+    need = [(int(ctx[s]) + 1 + Bk - 1) // Bk for s in sample]
+    nb = sum(need)
+    cfg = oracle.LayerConfig(d_model=sh.d_model, n_q_heads=sh.n_q_heads, n_kv_heads=sh.n_kv_heads, head_dim=sh.head_dim,
+                             d_ffn=sh.d_ffn, block_size=Bk, num_blocks=nb, n_models=sh.n_models, lora_rank=sh.lora_rank,
+                             lora_target_mask=sh.lora_target_mask, qk_norm=sh.qk_norm, bf16=sh.bf16,
+                             rope_theta=sh.rope_theta, rms_eps=sh.rms_eps, lora_scale=sh.lora_scale)
+    orc = oracle.Oracle(cfg, wl.base, wl.lora)
+    pool = orc.new_pool()
+    bt = np.zeros((len(sample), max(need)), dtype=np.int32)
+    k = 0
+    row_seq, row_model, xs = [], [], []
+    x_host = wl.x_host[step % len(wl.x_host)]
+    for i, s in enumerate(sample):
+        bt[i, :need[i]] = np.arange(k, k + need[i])
+        k += need[i]
+        K, V = workloads.sequence_kv_to_host(wl, s, int(ctx[s]))
+        fill_pool(pool, bt[i], K, V)
+        for r in np.flatnonzero(b.row_seq == s):
+            row_seq.append(i)
+            row_model.append(int(b.row_model[r]))
+            xs.append(x_host[r])
+    xs = np.stack(xs)
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    t0 = time.perf_counter()
+    want, _ = orc.decode_step(pool, bt, ctx[sample], np.int32(row_seq), np.int32(row_model), xs)
+    dt = time.perf_counter() - t0
+    got = x_dev_out[torch.from_numpy(np.concatenate([np.flatnonzero(b.row_seq == s) for s in sample])).to(x_dev_out.device)]
+    got = got.to(torch.float32).cpu().numpy()
+    assert_close(got, want, 2e-2 if sh.bf16 else 1e-4, "bench sample vs oracle")
+    n_dec = int(sum(1 for m in row_model if m >= 0))
+    return {"value": n_dec / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"sequences {sample} of the workload at step {step}: {len(row_seq)} rows ({n_dec} decoder rows), "
+                      f"{int(sum(ctx[s] + 1 for s in sample))} cached tokens, {dt:.2f} s; GPU output of these rows "
+                      f"matches the oracle within 2e-2",
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-mode", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2603_13281_amd import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    K, W = args.steps, args.warmup
+    t_build = time.perf_counter()
+    wl = workloads.build_decode_workload(args.workload, dev, headroom=2 * (K + W) + 16, verbose=True)
+    wl.layer.set_kernel_mode(args.kernel_mode)
+    log(f"[bench] workload built in {time.perf_counter() - t_build:.1f} s: R={wl.batch.R} rows "
+        f"({wl.batch.n_decoder_rows} decoder), S={wl.batch.S}, pool {wl.pool.numel() * 2 / 2**30:.2f} GiB")
+    x_out = torch.empty_like(wl.x[0])
+
+    # parity sample + CPU baseline at step 0 (before the timed steps append to the cache)
+    base = None
+    run_steps(wl, 1, 0, x_out)
+    torch.cuda.synchronize()
+    if not args.no_cpu_baseline:
+        nseq = {"c2": 1, "c3": 2, "c5": 1, "c3-small": 4}[args.workload]
+        base = cpu_baseline(wl, 0, x_out, nseq)
+        log(f"[bench] cpu baseline: {base['value']:.2f} tok/s on {base['cores']} threads; sample parity ok")
+
+    # warmup, then EXACTLY K timed steps
+    run_steps(wl, W, 1, x_out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(wl, K, 1 + W, x_out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / K * 1e3
+    tok_s = wl.batch.n_decoder_rows / (dt / K)
+
+    # per-kernel durations: same steps again with HIP events around every launch (on the launch stream)
+    wl.layer.timing_enable(True)
+    run_steps(wl, K, 1 + W, x_out)
+    torch.cuda.synchronize()
+    ph = wl.layer.timing_read()
+    wl.layer.timing_enable(False)
+    per_step_ms = {k: v[0] / K for k, v in ph.items() if v[1]}
+    launches = {k: v[1] // K for k, v in ph.items() if v[1]}
+    model = phase_model(wl, 1 + W + K // 2)
+    dominant = max(per_step_ms, key=per_step_ms.get)
+    phases = {}
+    for k, ms in per_step_ms.items():
+        e = {"ms": round(ms, 4), "launches": launches[k]}
+        if k in model:
+            e["GBps"] = round(model[k]["bytes"] / (ms * 1e-3) / 1e9, 1)
+            e["TFLOPs"] = round(model[k]["flops"] / (ms * 1e-3) / 1e12, 2)
+        phases[k] = e
+    if dominant in model:
+        byts, flops = model[dominant]["bytes"], model[dominant]["flops"]
+        t = per_step_ms[dominant] * 1e-3
+        intensity = flops / byts
+        if intensity < MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+            roof = {"bound": "hbm", "achieved": byts / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+        else:
+            roof = {"bound": "mfma", "achieved": flops / t / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+        roof["frac"] = roof["achieved"] / roof["peak"]
+        roof["traffic"] = None
+        roof["kernel"] = dominant
+        roof["avg_launch_ms"] = per_step_ms[dominant]
+        roof["algorithmic_bytes"] = byts
+    else:
+        roof = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": None,
+                "kernel": dominant}
+    attn_gbps = model["attn"]["bytes"] / (per_step_ms["attn"] * 1e-3) / 1e9 if "attn" in per_step_ms else None
+
+    out = {
+        "metric": METRIC, "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.shape.bf16 else "f32", "data": "synthetic",
+        "config": {"workload": wl.description, "rows": wl.batch.R, "decoder_rows": wl.batch.n_decoder_rows,
+                   "sequences": wl.batch.S, "kv_tokens": model["kv_tokens"], "kernel_mode": args.kernel_mode},
+        "attn_hbm_GBps": attn_gbps,
+        "roofline": roof,
+        "cpu_baseline": base,
+        "phases": phases,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,111 @@
+"""The benchmark configurations as device-resident workloads (seeded, synthetic).
+
+Builds what bench.py times and what the full-size parity tests sample: layer weights, adapters,
+a paged KV pool filled directly with N(0,1) keys and values, permuted block tables, row lists and
+hidden rows.  Bookkeeping and uploads only: the layer itself runs in the library.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+from . import binding, synth
+
+
+@dataclass
+class DecodeWorkload:
+    name: str
+    description: str
+    shape: synth.LayerShape
+    batch: synth.Batch
+    base: dict            # host float32 (storage-representable) -- the oracle reads these
+    lora: dict
+    layer: binding.IcarusLayer
+    pool: torch.Tensor    # device, library layout
+    block_tables: torch.Tensor
+    x: list               # rotating device inputs [R, d]
+    x_host: list
+    headroom: int
+
+    def ctx_lens(self, step: int) -> np.ndarray:
+        return (self.batch.ctx_lens + step).astype(np.int32)
+
+    def kv_bytes(self, step: int) -> int:
+        """Algorithmic KV bytes one attention launch reads: each cached token once per sequence."""
+        s = self.shape
+        es = 2 if s.bf16 else 4
+        return int((self.ctx_lens(step).astype(np.int64) + 1).sum()) * s.n_kv_heads * s.head_dim * 2 * es
+
+    def qo_bytes(self) -> int:
+        s = self.shape
+        return 2 * self.batch.R * s.n_q_heads * s.head_dim * (2 if s.bf16 else 4)
+
+
+SPECS = {
+    # name: (shape, S, (len_lo, len_hi), (act_lo, act_hi), description)
+    "c2": (synth.LLAMA8B, 1, (4096, 4096), (8, 8),
+           "config 2: Llama-3-8B-shaped layer, M=8 rank-16 adapters, 1 sequence, 4096-token shared prefix"),
+    "c3": (synth.LLAMA8B, 64, (1024, 16384), (1, 8),
+           "config 3: multi-agent decode batch, Llama-3-8B-shaped layer, M=8, 64 sequences, shared contexts "
+           "U[1024,16384], 1-8 models active per sequence, permuted block tables"),
+    "c5": (synth.QWEN32B, 16, (32768, 32768), (8, 8),
+           "config 5: Qwen3-32B-shaped layer (QK-RMSNorm), M=8 rank-32 adapters, 16 sequences, 32768-token "
+           "shared contexts, all models active"),
+    # reduced stand-ins for quick runs and tests
+    "c3-small": (synth.LLAMA_SMALL.replace(n_models=8), 16, (100, 3000), (1, 8), "reduced config 3"),
+}
+
+
+def upload(a: np.ndarray, bf16: bool, device) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    return t.to(device=device, dtype=torch.bfloat16 if bf16 else torch.float32).contiguous()
+
+
+def layer_config(shape: synth.LayerShape, num_blocks: int, max_position: int) -> binding.LayerConfig:
+    return binding.LayerConfig(
+        d_model=shape.d_model, n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
+        d_ffn=shape.d_ffn, block_size=shape.block_size, num_blocks=num_blocks, n_models=shape.n_models,
+        lora_rank=shape.lora_rank, lora_target_mask=shape.lora_target_mask, bf16=shape.bf16, qk_norm=shape.qk_norm,
+        max_position=max_position, rope_theta=shape.rope_theta, rms_eps=shape.rms_eps, lora_scale=shape.lora_scale)
+
+
+def build_decode_workload(name: str, device="cuda:0", headroom: int = 128, seed: int = 0, n_x: int = 4,
+                          verbose: bool = False) -> DecodeWorkload:
+    shape, S, (lo, hi), (alo, ahi), desc = SPECS[name]
+    say = (lambda *a: print(*a, flush=True)) if verbose else (lambda *a: None)
+    say(f"[workload {name}] weights")
+    base = synth.make_base(shape, seed=seed)
+    lora = synth.make_lora(shape, seed=seed)
+    lens = synth.draw_lens(seed, S, lo, hi) if lo != hi else np.full(S, lo, dtype=np.int32)
+    nact = synth.draw_active_counts(seed, S, alo, ahi) if alo != ahi else np.full(S, alo, dtype=np.int32)
+    batch = synth.make_batch(shape, lens, nact, seed=seed, headroom=headroom)
+    cfg = layer_config(shape, batch.num_blocks, int(lens.max()) + headroom + 1)
+    dbase = {k: upload(v, shape.bf16, device) for k, v in base.items()}
+    dlora = {p: (upload(A, shape.bf16, device), upload(B, shape.bf16, device)) for p, (A, B) in lora.items()}
+    layer = binding.IcarusLayer(cfg, dbase, dlora)
+    say(f"[workload {name}] pool: {batch.num_blocks} blocks")
+    gen = torch.Generator(device=device)
+    gen.manual_seed(1000 + seed)
+    pool = torch.empty(cfg.pool_shape(), dtype=cfg.torch_dtype, device=device)
+    step_blocks = max(1, (1 << 28) // (pool[0].numel()))
+    for b0 in range(0, batch.num_blocks, step_blocks):        # fill in slabs: bounded temporaries
+        sl = pool[b0:b0 + step_blocks]
+        sl.copy_(torch.randn(sl.shape, generator=gen, device=device, dtype=torch.float32))
+    bt = torch.from_numpy(batch.block_tables).to(device)
+    xs_host = [synth.make_hidden(shape, batch.R, seed=seed, tag=10 + i) for i in range(n_x)]
+    xs = [upload(x, shape.bf16, device) for x in xs_host]
+    return DecodeWorkload(name, desc, shape, batch, base, lora, layer, pool, bt, xs, xs_host, headroom)
+
+
+def sequence_kv_to_host(wl: DecodeWorkload, s: int, n_tokens: int):
+    """Copy sequence s's first n_tokens cached K, V from the device pool: float32 [n, Hkv, D] each."""
+    sh = wl.shape
+    Bk, D = sh.block_size, sh.head_dim
+    nb = (n_tokens + Bk - 1) // Bk
+    ids = torch.from_numpy(wl.batch.block_tables[s, :nb].astype(np.int64)).to(wl.pool.device)
+    blk = wl.pool.index_select(0, ids).to(torch.float32).cpu().numpy()      # [nb, Hkv, 2, Bk*D]
+    K = blk[:, :, 0].reshape(nb, sh.n_kv_heads, Bk, D).transpose(0, 2, 1, 3).reshape(nb * Bk, sh.n_kv_heads, D)
+    V = blk[:, :, 1].reshape(nb, sh.n_kv_heads, D, Bk).transpose(0, 3, 1, 2).reshape(nb * Bk, sh.n_kv_heads, D)
+    return np.ascontiguousarray(K[:n_tokens]), np.ascontiguousarray(V[:n_tokens])
