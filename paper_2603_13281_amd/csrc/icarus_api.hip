@@ -99,12 +99,13 @@ bool has_lora(const icarus_ctx *ctx, int p) {
 
 // ---- workspace layout ---------------------------------------------------------------
 struct WsLayout {
-    size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, part_o, part_ml, total;
+    size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, part_o, part_ml, lora_part, lora_t, total;
     size_t meta_ints, max_items;
 };
 
 constexpr int kAttnTargetWgs = 2048;  // decode attention: aim for about this many workgroups
 constexpr int kAttnGMax = 80;         // largest stacked query group the MFMA attention covers
+constexpr int kShrinkMaxSplits = 16;  // split-K slices of the LoRA shrink GEMM
 
 // Upper bounds used for sizing: chunks (= partial slots) of a call and its largest stacked group.
 size_t attn_max_items(const icarus_ctx *ctx, size_t seqs) { return (size_t)kAttnTargetWgs / ctx->cfg.n_kv_heads + seqs + 1; }
@@ -135,6 +136,11 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t /*max
     w.f32a = take(rows * std::max<size_t>(c.d_ffn, c.d_model) * 4);
     w.f32b = take(rows * c.d_ffn * 4);
     w.t = take(rows * std::max(1, c.lora_rank) * 4 * 2);
+    {
+        size_t cols = (size_t)2 * std::max(1, c.n_models) * std::max(1, c.lora_rank);  // gate + up share a shrink
+        w.lora_part = take((size_t)kShrinkMaxSplits * rows * cols * 4);
+        w.lora_t = take(rows * cols * 2);
+    }
     w.total = off;
     return w;
 }
@@ -325,11 +331,125 @@ icarus_status run_decode_attention(icarus_ctx *ctx, char *ws, const WsLayout &L,
     return ICARUS_OK;
 }
 
+#define LORA_TRY(call) do { icarus_status rc__ = (call); if (rc__) return rc__; } while (0)
+
+// ---- the layer on matrix cores (bf16 storage) -----------------------------------------
+bool layer_mfma_supported(const icarus_ctx *ctx) {
+    const icarus_layer_config &c = ctx->cfg;
+    return ctx->mode == 0 && gemm_mfma_supported(ctx->dm, c.d_model) && gemm_mfma_supported(ctx->dm, c.n_q_heads * c.head_dim) &&
+           gemm_mfma_supported(ctx->dm, c.d_ffn);
+}
+
+// Masked shrink T = s * mask(X A^T) for the adapters of projections p0 (and p1) that share the
+// input X [R, K]: a split-K GEMM into fp32 partials, then reduce + mask + scale to bf16.
+icarus_status run_shrink(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, int R, const void *X, int K, int p0,
+                         int p1, hipStream_t st) {
+    const icarus_layer_config &c = ctx->cfg;
+    int mr = c.n_models * c.lora_rank, nt = p1 >= 0 ? 2 : 1, C = nt * mr;
+    GemmArgs g{};
+    g.X = (const bf16_raw *)X; g.ldx = K; g.R = R; g.K = K;
+    g.W[0] = (const bf16_raw *)ctx->lora.A[p0]; g.n_seg[0] = mr; g.nseg = nt;
+    if (p1 >= 0) { g.W[1] = (const bf16_raw *)ctx->lora.A[p1]; g.n_seg[1] = mr; }
+    g.mode = GEMM_PLAIN; g.epi = EPI_F32;
+    g.Y = ws + L.lora_part; g.ldy = C;
+    int m_tiles = (R + 127) / 128, n_tiles = nt * ((mr + 127) / 128);
+    g.splits = std::max(1, std::min({kShrinkMaxSplits, K / 64, 256 / (m_tiles * n_tiles)}));
+    PHASE(ctx, st, ICARUS_PH_LORA, launch_gemm_mfma(g, st));
+    PHASE(ctx, st, ICARUS_PH_LORA, launch_lora_mask((const float *)(ws + L.lora_part), g.splits, R, C, c.lora_rank, rm.row_model,
+                                                    ctx->dm.lora_scale, ws + L.lora_t, nt, st));
+    return ICARUS_OK;
+}
+
+icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp, int R,
+                             bool use_lora, bool kv_only, int slot_by_row, void *pool, const int32_t *bt, int max_blocks,
+                             const void *x_in, void *x_out, int64_t *slot_out, hipStream_t st) {
+    const icarus_layer_config &c = ctx->cfg;
+    const Dims &dm = ctx->dm;
+    int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, F = c.d_ffn;
+    int ldq = qd + 2 * kvd, mr = c.n_models * c.lora_rank;
+    bf16_raw *xn = (bf16_raw *)(ws + L.xn), *q = (bf16_raw *)(ws + L.q), *attn = (bf16_raw *)(ws + L.attn),
+             *z = (bf16_raw *)(ws + L.z), *h = (bf16_raw *)(ws + L.h), *T = (bf16_raw *)(ws + L.lora_t);
+    float *qkv = (float *)(ws + L.qkv);
+    auto W = [&](int p) { return (const bf16_raw *)ctx->base.w[p]; };
+    auto lo = [&](int p) { return use_lora && has_lora(ctx, p); };
+    auto Bw = [&](int p) { return (const bf16_raw *)ctx->lora.B[p]; };
+
+    PHASE(ctx, st, ICARUS_PH_NORM, launch_rmsnorm(dm, x_in, ctx->base.norm_attn, xn, R, d, st));
+    {   // Q (ICaRusLinear) and the encoder's K, V in one GEMM over [W_q; W_k; W_v]
+        GemmArgs g{};
+        g.X = xn; g.ldx = d; g.R = R; g.K = d;
+        g.mode = GEMM_PLAIN; g.epi = EPI_F32; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
+        if (kv_only) {
+            g.W[0] = W(ICARUS_PROJ_K); g.n_seg[0] = kvd; g.W[1] = W(ICARUS_PROJ_V); g.n_seg[1] = kvd; g.nseg = 2;
+            g.Y = qkv + qd; g.ldy = ldq;
+        } else {
+            if (lo(ICARUS_PROJ_Q)) {
+                LORA_TRY(run_shrink(ctx, ws, L, rm, R, xn, d, ICARUS_PROJ_Q, -1, st));
+                g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_Q);
+            }
+            g.W[0] = W(ICARUS_PROJ_Q); g.n_seg[0] = qd; g.W[1] = W(ICARUS_PROJ_K); g.n_seg[1] = kvd;
+            g.W[2] = W(ICARUS_PROJ_V); g.n_seg[2] = kvd; g.nseg = 3;
+            g.Y = qkv; g.ldy = ldq;
+        }
+        PHASE(ctx, st, ICARUS_PH_GEMM_QKV, launch_gemm_mfma(g, st));
+    }
+    PHASE(ctx, st, ICARUS_PH_ROPE_APPEND, launch_rope_append(dm, qkv, ldq, rm, bt, max_blocks, pool, q, slot_out, slot_by_row,
+                                                             ctx->base.q_norm, ctx->base.k_norm, R, st));
+    if (kv_only) return ICARUS_OK;
+    LORA_TRY(run_decode_attention(ctx, ws, L, rm, hp, q, pool, bt, max_blocks, attn, R, st));
+    {   // O projection (ICaRusLinear) + residual
+        GemmArgs g{};
+        g.X = attn; g.ldx = qd; g.R = R; g.K = qd;
+        g.W[0] = W(ICARUS_PROJ_O); g.n_seg[0] = d; g.nseg = 1;
+        g.mode = GEMM_PLAIN; g.epi = EPI_BF16_RESID; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
+        if (lo(ICARUS_PROJ_O)) {
+            LORA_TRY(run_shrink(ctx, ws, L, rm, R, attn, qd, ICARUS_PROJ_O, -1, st));
+            g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_O);
+        }
+        g.Y = z; g.ldy = d; g.resid = (const bf16_raw *)x_in; g.ldr = d;
+        PHASE(ctx, st, ICARUS_PH_GEMM_O, launch_gemm_mfma(g, st));
+    }
+    PHASE(ctx, st, ICARUS_PH_NORM, launch_rmsnorm(dm, z, ctx->base.norm_ffn, xn, R, d, st));
+    {   // gate and up (ICaRusLinear x 2) with the SwiGLU product in the epilogue
+        GemmArgs g{};
+        g.X = xn; g.ldx = d; g.R = R; g.K = d;
+        g.W[0] = W(ICARUS_PROJ_GATE); g.W[1] = W(ICARUS_PROJ_UP); g.n_seg[0] = F; g.nseg = 1;
+        g.mode = GEMM_DUAL; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
+        bool lg = lo(ICARUS_PROJ_GATE), lu = lo(ICARUS_PROJ_UP);
+        if (lg && lu) {
+            LORA_TRY(run_shrink(ctx, ws, L, rm, R, xn, d, ICARUS_PROJ_GATE, ICARUS_PROJ_UP, st));
+            g.T = T; g.ldt = 2 * mr; g.B[0] = Bw(ICARUS_PROJ_GATE); g.B[1] = Bw(ICARUS_PROJ_UP);
+        } else if (lg || lu) {
+            return fail(ctx, ICARUS_ERR_UNSUPPORTED, "adapters on only one of gate/up need the generic kernels (set kernel mode 1)");
+        }
+        g.Y = h; g.ldy = F;
+        PHASE(ctx, st, ICARUS_PH_GEMM_GATEUP, launch_gemm_mfma(g, st));
+    }
+    {   // down projection (ICaRusLinear) + residual
+        GemmArgs g{};
+        g.X = h; g.ldx = F; g.R = R; g.K = F;
+        g.W[0] = W(ICARUS_PROJ_DOWN); g.n_seg[0] = d; g.nseg = 1;
+        g.mode = GEMM_PLAIN; g.epi = EPI_BF16_RESID; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
+        if (lo(ICARUS_PROJ_DOWN)) {
+            LORA_TRY(run_shrink(ctx, ws, L, rm, R, h, F, ICARUS_PROJ_DOWN, -1, st));
+            g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_DOWN);
+        }
+        g.Y = x_out; g.ldy = d; g.resid = z; g.ldr = d;
+        PHASE(ctx, st, ICARUS_PH_GEMM_DOWN, launch_gemm_mfma(g, st));
+    }
+    return ICARUS_OK;
+}
+
 // ---- the layer, after metadata is on the device ---------------------------------------
 // rows: x_in [R, d].  use_lora: decoder rows get adapter deltas.  kv_only: stop after the append.
 icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp, int R, bool use_lora, bool kv_only,
                         int slot_by_row, void *pool, const int32_t *bt, int max_blocks, const void *x_in, void *x_out,
                         int64_t *slot_out, hipStream_t st) {
+    if (layer_mfma_supported(ctx)) {
+        bool lg = use_lora && has_lora(ctx, ICARUS_PROJ_GATE), lu = use_lora && has_lora(ctx, ICARUS_PROJ_UP);
+        if (lg == lu)
+            return run_layer_mfma(ctx, ws, L, rm, hp, R, use_lora, kv_only, slot_by_row, pool, bt, max_blocks, x_in, x_out, slot_out, st);
+    }
     const icarus_layer_config &c = ctx->cfg;
     const Dims &dm = ctx->dm;
     int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, F = c.d_ffn;
@@ -342,7 +462,6 @@ icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowM
         PHASE(ctx, st, ICARUS_PH_LORA, launch_lora_expand_generic(dm, t, ctx->lora.B[p], proj_out(c, p), rm.row_model, Y, ldy, R, st));
         return ICARUS_OK;
     };
-#define LORA_TRY(call) do { icarus_status rc__ = (call); if (rc__) return rc__; } while (0)
     PHASE(ctx, st, ICARUS_PH_NORM, launch_rmsnorm(dm, x_in, ctx->base.norm_attn, xn, R, d, st));
     if (!kv_only) {
         PHASE(ctx, st, ICARUS_PH_GEMM_QKV, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_Q], R, qd, d, qkv, ldq, st));

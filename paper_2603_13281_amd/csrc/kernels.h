@@ -6,6 +6,8 @@
 
 namespace icarus {
 
+typedef uint16_t bf16_raw;  // raw bfloat16 bits
+
 struct Dims {
     int d, Hq, Hkv, D, F, Bk, M, r;
     int bf16;      // storage type: 1 = bfloat16, 0 = float32
@@ -63,6 +65,28 @@ struct AttnPlan {
     const int32_t *seq_nparts;   // [S] number of chunks
     int n_items, chunk, g_max;   // g_max: largest stacked group (rows * Hq/Hkv) in the call
 };
+// ICaRusLinear GEMM on matrix cores.  Y = X W^T (+ T Bcat^T), see gemm_mfma.hip.
+enum { GEMM_PLAIN = 0, GEMM_DUAL = 1 };          // DUAL: W[0] = gate, W[1] = up, Y = silu(gate) * up
+enum { EPI_F32 = 0, EPI_BF16_RESID = 1 };        // plain epilogues (DUAL always stores bf16)
+struct GemmArgs {
+    const bf16_raw *X; int ldx; int R; int K;    // activations [R, K] (row stride ldx)
+    const bf16_raw *W[3]; int n_seg[3]; int nseg; // weight segments stacked along N, each [n_seg, K]
+    const bf16_raw *T; int ldt;                  // masked shrink result [R, ldt] or null
+    const bf16_raw *B[2]; int r; int M_models;   // adapter B [M, n_seg[0], r] of segment 0 (DUAL: gate, up)
+    int mode, epi;
+    void *Y; int ldy;                            // EPI_F32: float [splits][R][ldy]; else bf16 [R][ldy]
+    const bf16_raw *resid; int ldr;              // EPI_BF16_RESID: added to the result
+    int splits;                                  // split-K slices (EPI_F32 without adapters only)
+    // filled by the launcher
+    int tiles_seg[3]; int m_tiles, n_tiles, K_ext, k_per_split;
+};
+bool gemm_mfma_supported(const Dims &dm, int K);
+hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st);
+// T[row, c] = bf16(scale * sum_z P[z][row][c]) where column c belongs to the row's model, else 0;
+// C = n_targets * M * r columns.
+hipError_t launch_lora_mask(const float *P, int splits, int R, int C, int r, const int32_t *row_model, float scale,
+                            void *T, int n_targets, hipStream_t st);
+
 bool attn_decode_mfma_supported(const Dims &dm, int g_max);
 // part_o: fp32 [slots, Hkv, g_max, D]; part_ml: fp32 [slots, Hkv, g_max, 2] (max in log2 units, sum)
 hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
