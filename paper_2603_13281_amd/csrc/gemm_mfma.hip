@@ -105,8 +105,29 @@ __global__ void __launch_bounds__(256) k_gemm_mfma(GemmArgs g) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     uint4 ra[A_LD], rb[B_LD];
+    // Row pointers of this thread's 16-byte loads at k = 0 (null: the row is outside the matrix).
+    // Inside the base-K range a load is pointer + k; only the few adapter slabs past K take the
+    // general source functions.
+    const bf16_t *pa[A_LD], *pb[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        int e = tid + i * 256;
+        pa[i] = a_src(g, row0 + (e >> 3), (e & 7) * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        int e = tid + i * 256;
+        pb[i] = b_src<BN>(g, tile_n, e >> 3, (e & 7) * 8);
+    }
     auto gload = [&](int kt) {
         int k0 = k_begin + kt * kBK;
+        if (k0 + kBK <= g.K) {  // whole slab inside the base weights (K is a multiple of the slab)
+#pragma unroll
+            for (int i = 0; i < A_LD; ++i) ra[i] = pa[i] ? ldg16(pa[i] + k0) : uint4{0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < B_LD; ++i) rb[i] = pb[i] ? ldg16(pb[i] + k0) : uint4{0, 0, 0, 0};
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
             int e = tid + i * 256, rr = e >> 3, kc = (e & 7) * 8;
@@ -223,6 +244,29 @@ __global__ void __launch_bounds__(256) k_lora_mask(const float *__restrict__ P, 
     T[idx] = f32_to_bf16(v);
 }
 
+// Second pass of a split-K GEMM: sum the fp32 partials P[z][row][n] and apply the epilogue.
+__global__ void __launch_bounds__(256) k_splitk_reduce(const float *__restrict__ P, int splits, int R, int N, int epi,
+                                                       void *__restrict__ Y, int ldy, const bf16_t *__restrict__ resid, int ldr) {
+    size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (idx >= (size_t)R * N) return;
+    int row = (int)(idx / N), n = (int)(idx % N);  // N is a multiple of 4
+    float4 v = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < splits; ++z) {
+        float4 p = *(const float4 *)(P + ((size_t)z * R + row) * N + n);
+        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    if (epi == EPI_F32) {
+        *(float4 *)((float *)Y + (size_t)row * ldy + n) = v;
+    } else {
+        const bf16_t *rp = resid + (size_t)row * ldr + n;
+        bf16_t *yp = (bf16_t *)Y + (size_t)row * ldy + n;
+        yp[0] = f32_to_bf16(v.x + bf16_to_f32(rp[0]));
+        yp[1] = f32_to_bf16(v.y + bf16_to_f32(rp[1]));
+        yp[2] = f32_to_bf16(v.z + bf16_to_f32(rp[2]));
+        yp[3] = f32_to_bf16(v.w + bf16_to_f32(rp[3]));
+    }
+}
+
 template <int BN>
 hipError_t launch_bn(const GemmArgs &g, hipStream_t st) {
     size_t shm = (size_t)2 * (kBM + BN) * kLd * sizeof(bf16_t);
@@ -259,6 +303,23 @@ hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st) {
     if (g.splits < 1) g.splits = 1;
     g.k_per_split = ((g.K_ext + g.splits - 1) / g.splits + kBK - 1) / kBK * kBK;
     return launch_bn<128>(g, st);
+}
+
+int gemm_mfma_tiles(const GemmArgs &g) {
+    const int BN = 128;
+    int m_tiles = (g.R + kBM - 1) / kBM, n_tiles = 0;
+    if (g.mode == GEMM_DUAL) return m_tiles * ((g.n_seg[0] + BN / 2 - 1) / (BN / 2));
+    for (int s = 0; s < g.nseg; ++s) n_tiles += (g.n_seg[s] + BN - 1) / BN;
+    return m_tiles * n_tiles;
+}
+
+hipError_t launch_splitk_reduce(const float *P, int splits, int R, int N, int epi, void *Y, int ldy, const void *resid,
+                                int ldr, hipStream_t st) {
+    size_t quads = (size_t)R * N / 4;
+    if (!quads) return hipSuccess;
+    hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, P, splits, R, N, epi, Y, ldy,
+                       (const bf16_t *)resid, ldr);
+    return hipGetLastError();
 }
 
 hipError_t launch_lora_mask(const float *P, int splits, int R, int C, int r, const int32_t *row_model, float scale,

@@ -100,12 +100,13 @@ bool has_lora(const icarus_ctx *ctx, int p) {
 // ---- workspace layout ---------------------------------------------------------------
 struct WsLayout {
     size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, part_o, part_ml, lora_part, lora_t, total;
-    size_t meta_ints, max_items;
+    size_t meta_ints, max_items, gemm_part, gemm_part_bytes;
 };
 
 constexpr int kAttnTargetWgs = 2048;  // decode attention: aim for about this many workgroups
 constexpr int kAttnGMax = 80;         // largest stacked query group the MFMA attention covers
 constexpr int kShrinkMaxSplits = 16;  // split-K slices of the LoRA shrink GEMM
+constexpr int kGemmMaxSplits = 16;    // split-K slices of a narrow ICaRusLinear GEMM
 
 // Upper bounds used for sizing: chunks (= partial slots) of a call and its largest stacked group.
 size_t attn_max_items(const icarus_ctx *ctx, size_t seqs) { return (size_t)kAttnTargetWgs / ctx->cfg.n_kv_heads + seqs + 1; }
@@ -141,6 +142,8 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t /*max
         w.lora_part = take((size_t)kShrinkMaxSplits * rows * cols * 4);
         w.lora_t = take(rows * cols * 2);
     }
+    w.gemm_part_bytes = (size_t)400 * 128 * 128 * 4;  // split-K partials: splits * tiles <= 384 tiles of 128 x 128
+    w.gemm_part = take(w.gemm_part_bytes);
     w.total = off;
     return w;
 }
@@ -360,6 +363,30 @@ icarus_status run_shrink(icarus_ctx *ctx, char *ws, const WsLayout &L, const Row
     return ICARUS_OK;
 }
 
+// One plain ICaRusLinear GEMM.  When its grid would leave most of the chip idle (few rows and a
+// narrow output), K is split over several workgroups into fp32 partials and a second small kernel
+// sums them and applies the epilogue.
+icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, GemmArgs g, hipStream_t st) {
+    int tiles = gemm_mfma_tiles(g);
+    int n_total = 0;
+    for (int s = 0; s < g.nseg; ++s) n_total += g.n_seg[s];
+    int k_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
+    int splits = 1;
+    if (tiles < 160) splits = std::max(1, std::min({kGemmMaxSplits, 384 / tiles, k_ext / 256}));
+    if (splits > 1 && (size_t)splits * g.R * n_total * 4 > L.gemm_part_bytes) splits = 1;
+    if (splits == 1) {
+        g.splits = 1;
+        PHASE(ctx, st, phase, launch_gemm_mfma(g, st));
+        return ICARUS_OK;
+    }
+    GemmArgs p = g;
+    p.epi = EPI_F32; p.Y = ws + L.gemm_part; p.ldy = n_total; p.splits = splits;
+    PHASE(ctx, st, phase, launch_gemm_mfma(p, st));
+    PHASE(ctx, st, phase, launch_splitk_reduce((const float *)(ws + L.gemm_part), splits, g.R, n_total, g.epi, g.Y, g.ldy, g.resid,
+                                               g.ldr, st));
+    return ICARUS_OK;
+}
+
 icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp, int R,
                              bool use_lora, bool kv_only, int slot_by_row, void *pool, const int32_t *bt, int max_blocks,
                              const void *x_in, void *x_out, int64_t *slot_out, hipStream_t st) {
@@ -391,7 +418,7 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
             g.W[2] = W(ICARUS_PROJ_V); g.n_seg[2] = kvd; g.nseg = 3;
             g.Y = qkv; g.ldy = ldq;
         }
-        PHASE(ctx, st, ICARUS_PH_GEMM_QKV, launch_gemm_mfma(g, st));
+        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_QKV, g, st));
     }
     PHASE(ctx, st, ICARUS_PH_ROPE_APPEND, launch_rope_append(dm, qkv, ldq, rm, bt, max_blocks, pool, q, slot_out, slot_by_row,
                                                              ctx->base.q_norm, ctx->base.k_norm, R, st));
@@ -407,7 +434,7 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
             g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_O);
         }
         g.Y = z; g.ldy = d; g.resid = (const bf16_raw *)x_in; g.ldr = d;
-        PHASE(ctx, st, ICARUS_PH_GEMM_O, launch_gemm_mfma(g, st));
+        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_O, g, st));
     }
     PHASE(ctx, st, ICARUS_PH_NORM, launch_rmsnorm(dm, z, ctx->base.norm_ffn, xn, R, d, st));
     {   // gate and up (ICaRusLinear x 2) with the SwiGLU product in the epilogue
@@ -435,7 +462,7 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
             g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_DOWN);
         }
         g.Y = x_out; g.ldy = d; g.resid = z; g.ldr = d;
-        PHASE(ctx, st, ICARUS_PH_GEMM_DOWN, launch_gemm_mfma(g, st));
+        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_DOWN, g, st));
     }
     return ICARUS_OK;
 }

@@ -82,6 +82,10 @@ struct GemmArgs {
 };
 bool gemm_mfma_supported(const Dims &dm, int K);
 hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st);
+int gemm_mfma_tiles(const GemmArgs &g);  // workgroups of one K slice
+// Sum split-K partials P[splits][R][N] (fp32) and apply the epilogue `epi` into Y.
+hipError_t launch_splitk_reduce(const float *P, int splits, int R, int N, int epi, void *Y, int ldy, const void *resid,
+                                int ldr, hipStream_t st);
 // T[row, c] = bf16(scale * sum_z P[z][row][c]) where column c belongs to the row's model, else 0;
 // C = n_targets * M * r columns.
 hipError_t launch_lora_mask(const float *P, int splits, int R, int C, int r, const int32_t *row_model, float scale,
