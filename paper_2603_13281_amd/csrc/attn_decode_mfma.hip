@@ -3,13 +3,19 @@
 //
 // All stacked queries of one sequence that share a kv-head -- (1 + m_s) streams x g heads --
 // form the N dimension of the MFMA tiles, so each KV block is fetched from HBM once for all
-// of the sequence's models.  A workgroup (4 waves) owns one (sequence, kv-head, token chunk);
-// wave w walks the chunk's 32-token groups w, w+4, ...  Per group a wave computes
+// of the sequence's models.  A workgroup (4 waves) owns one (sequence, kv-head, token chunk).
+// Per 32-token group a wave computes
 //     S^T[32 tok x G]  = K[32 tok x 128] . Q^T          (A = K straight from global memory)
 //     O^T[128 x G]    += V^T[128 x 32 tok] . P^T         (A = V^T straight from global memory)
 // with an online softmax on the S^T accumulators.  The cache layout (K token-major, V
 // transposed inside the block) makes every global load a 128-bit load that lands directly in
 // MFMA operand registers: no LDS staging and no register shuffles for P.
+//
+// Work split inside the workgroup:
+//   up to 3 query tiles (G <= 48): the four waves take the chunk's groups w, w+4, ... with all tiles;
+//   4 or 5 query tiles (G <= 80):  the O^T accumulators of all tiles do not fit one wave, so waves
+//     0,1 take tiles [0, NA) and waves 2,3 tiles [NA, NA+NB), each pair splitting the groups two
+//     ways.  A group is then loaded by two waves; the second load is served by the caches.
 //
 // MFMA 16x16x32 bf16 operand layout (lane l, q = l / 16):
 //   A[row l%16][k 8q..8q+7], B[k 8q..8q+7][col l%16], C[row 4q+i][col l%16] (i = 0..3).
@@ -33,6 +39,7 @@ constexpr int kGrp = 32;      // tokens per wave iteration (two blocks)
 constexpr int kKS = kD / 32;  // k-steps of the QK^T contraction
 constexpr int kDT = kD / 16;  // d tiles of the PV product
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kAttnMaxChunk = 16384;  // tokens per workgroup chunk, at most
 
 struct KVFrag {
     bf16x8 k[2][kKS];  // k[t][ks]: A operand of S^T tile t, k-step ks
@@ -65,18 +72,19 @@ __device__ __forceinline__ void load_group(KVFrag &f, const bf16_t *__restrict__
     for (int dt = 0; dt < kDT; ++dt) f.v[dt] = *(const bf16x8 *)(vb + (size_t)(16 * dt + m) * kBk + 8 * (q & 1));
 }
 
-template <int NQT>
+// Per-wave running state for NT query tiles.
+template <int NT>
 struct State {
-    f32x4 o[kDT][NQT];  // O^T accumulators: [d 16dt + 4q + i][query 16qt + l%16]
-    float m[NQT];       // running max (log2 domain), uniform over the 4 lanes sharing a query
-    float l[NQT];       // running sum, per-lane partial (reduced over q at the end)
+    f32x4 o[kDT][NT];  // O^T accumulators: [d 16dt + 4q + i][query 16qt + l%16]
+    float m[NT];       // running max (log2 domain), uniform over the 4 lanes sharing a query
+    float l[NT];       // running sum, per-lane partial (reduced over q at the end)
 };
 
 // One 32-token group: S^T, online softmax, PV, one 16-query tile at a time so that only one
-// tile's scores are live.  qlds: Q fragments in LDS as [qt][ks][lane] (B operands).
-// n_valid: valid tokens in this group (1..32).
-template <int NQT, bool tail>
-__device__ __forceinline__ void compute_group(State<NQT> &st, KVFrag &f, const bf16x8 *__restrict__ qlds, int n_valid,
+// tile's scores are live.  Uses the first N tiles of st.  qlds: Q fragments of those tiles in LDS
+// as [qt][ks][lane] (B operands).  n_valid: valid tokens in this group (1..32).
+template <int NT, int N, bool tail>
+__device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf16x8 *__restrict__ qlds, int n_valid,
                                               float scale_log2, int lane) {
     const int q = lane >> 4;
     // token index inside the group of S^T element (tile t, register i) on this lane: tbase + 4t + i
@@ -90,7 +98,7 @@ __device__ __forceinline__ void compute_group(State<NQT> &st, KVFrag &f, const b
                 if (tbase + e >= n_valid) f.v[dt][e] = (__bf16)0.f;
     }
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
+    for (int qt = 0; qt < N; ++qt) {
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < kKS; ++ks) {
@@ -139,15 +147,40 @@ __device__ __forceinline__ void compute_group(State<NQT> &st, KVFrag &f, const b
     }
 }
 
-// Merge another wave's state (read from LDS) into st.
-template <int NQT>
-__device__ __forceinline__ void merge_from_lds(State<NQT> &st, const float *__restrict__ lds, int lane) {
-    // LDS image of a state: o as [dt][qt][i][lane], then m[qt][lane], l[qt][lane]
+// A wave's walk over its share of the chunk: groups first, first + stride, ... with N query tiles.
+// Full groups run in a loop with two register buffers, loads issued one group ahead; the chunk's
+// one partial group (if any) is done last by the wave it falls to.
+template <int NT, int N>
+__device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
+                                          int n_blk, int n_tok, int first, int stride, int c, int Hkv,
+                                          const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
+    const int n_full = n_tok / kGrp, rem = n_tok % kGrp;
+    auto blk_of = [&](int grp, int which) {
+        return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
+    };
+    KVFrag f0, f1;
+    if (first < n_full) load_group(f0, pool, blk_of(first, 0), blk_of(first, 1), c, Hkv, lane);
+#pragma nounroll
+    for (int grp = first; grp < n_full; grp += 2 * stride) {
+        if (grp + stride < n_full) load_group(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
+        compute_group<NT, N, false>(st, f0, qlds, kGrp, scale_log2, lane);
+        if (grp + 2 * stride < n_full) load_group(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
+        if (grp + stride < n_full) compute_group<NT, N, false>(st, f1, qlds, kGrp, scale_log2, lane);
+    }
+    if (rem && n_full % stride == first) {
+        load_group(f0, pool, blk_of(n_full, 0), blk_of(n_full, 1), c, Hkv, lane);
+        compute_group<NT, N, true>(st, f0, qlds, rem, scale_log2, lane);
+    }
+}
+
+// LDS image of a state: o as [dt][qt][i][lane], then m[qt][lane], l[qt][lane].
+template <int NT>
+__device__ __forceinline__ void merge_from_lds(State<NT> &st, const float *__restrict__ lds, int lane) {
     const float *lo = lds;
-    const float *lm = lds + kDT * NQT * 4 * 64;
-    const float *ll = lm + NQT * 64;
+    const float *lm = lds + kDT * NT * 4 * 64;
+    const float *ll = lm + NT * 64;
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
+    for (int qt = 0; qt < NT; ++qt) {
         float m2 = lm[qt * 64 + lane], l2 = ll[qt * 64 + lane];
         float mn = fmaxf(st.m[qt], m2);
         float a1 = st.m[qt] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(st.m[qt] - mn);
@@ -157,105 +190,39 @@ __device__ __forceinline__ void merge_from_lds(State<NQT> &st, const float *__re
 #pragma unroll
         for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) st.o[dt][qt][i] = st.o[dt][qt][i] * a1 + lo[((dt * NQT + qt) * 4 + i) * 64 + lane] * a2;
+            for (int i = 0; i < 4; ++i) st.o[dt][qt][i] = st.o[dt][qt][i] * a1 + lo[((dt * NT + qt) * 4 + i) * 64 + lane] * a2;
     }
 }
-template <int NQT>
-__device__ __forceinline__ void store_to_lds(const State<NQT> &st, float *__restrict__ lds, int lane) {
+template <int NT>
+__device__ __forceinline__ void store_to_lds(const State<NT> &st, float *__restrict__ lds, int lane) {
     float *lo = lds;
-    float *lm = lds + kDT * NQT * 4 * 64;
-    float *ll = lm + NQT * 64;
+    float *lm = lds + kDT * NT * 4 * 64;
+    float *ll = lm + NT * 64;
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
+    for (int qt = 0; qt < NT; ++qt) {
         lm[qt * 64 + lane] = st.m[qt];
         ll[qt * 64 + lane] = st.l[qt];
 #pragma unroll
         for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) lo[((dt * NQT + qt) * 4 + i) * 64 + lane] = st.o[dt][qt][i];
+            for (int i = 0; i < 4; ++i) lo[((dt * NT + qt) * 4 + i) * 64 + lane] = st.o[dt][qt][i];
     }
 }
 
-template <int NQT>
-__global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ qg, const bf16_t *__restrict__ pool,
-                                                     const int32_t *__restrict__ bt, int max_blocks, AttnPlan pl,
-                                                     bf16_t *__restrict__ out, float *__restrict__ part_o,
-                                                     float *__restrict__ part_ml, int Hq, int Hkv, float scale_log2) {
-    extern __shared__ float lds[];
-    const int item = blockIdx.x / Hkv, c = blockIdx.x % Hkv;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int s = pl.item_seq[item];
-    const int tok_begin = pl.item_begin[item];
-    const int kvlen = pl.seq_kvlen[s];
-    const int tok_end = min(tok_begin + pl.chunk, kvlen);
-    const int row0 = pl.seq_row0[s], T = pl.seq_rows[s];
-    const int g = Hq / Hkv, G = T * g;
+// Write tiles [0, n) of st as the call's query tiles qt0 .. qt0+n-1: the final output when the
+// sequence has a single chunk, else this chunk's partial result.
+template <int NT>
+__device__ __forceinline__ void finish(State<NT> &st, int qt0, int n, int G, int g, int row0, int c, int Hq, int Hkv,
+                                       int direct, int slot, int g_max, bf16_t *__restrict__ out,
+                                       float *__restrict__ part_o, float *__restrict__ part_ml, int lane) {
     const int m = lane & 15, q = lane >> 4;
-    const int32_t *btr = bt + (size_t)s * max_blocks;
-    const int last_blk = (kvlen - 1) / kBk;
-
-    // Q fragments (B operands) go to LDS once, as [qt][ks][lane]; wave w stages k-step w.
-    // query j = 16qt + m  ->  row row0 + j / g, head c*g + j % g; rows past G are zero.
-    constexpr int kImg = kDT * NQT * 4 * 64 + 2 * NQT * 64;  // floats per wave image of the merge
-    bf16x8 *qlds = (bf16x8 *)(lds + 2 * kImg);
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-        int j = 16 * qt + m;
-        const bf16_t *qp = qg + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD + 8 * q + 32 * w;
-        qlds[(qt * kKS + w) * 64 + lane] = j < G ? *(const bf16x8 *)qp : zero8();
-    }
-    __syncthreads();
-    State<NQT> st;
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-        st.m[qt] = -INFINITY;
-        st.l[qt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < kDT; ++dt) st.o[dt][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    // wave w takes groups w, w+4, ... of the chunk.  Full groups run in a loop with two register
-    // buffers, loads issued one group ahead; the chunk's one partial group (if any) is done last.
-    const int n_tok = tok_end - tok_begin;
-    const int n_full = n_tok / kGrp, rem = n_tok % kGrp;
-    auto blk_of = [&](int grp, int which) {
-        int b = (tok_begin + grp * kGrp) / kBk + which;
-        return __builtin_amdgcn_readfirstlane(btr[min(b, last_blk)]);
-    };
-    KVFrag f0, f1;
-    if (w < n_full) load_group(f0, pool, blk_of(w, 0), blk_of(w, 1), c, Hkv, lane);
-#pragma nounroll
-    for (int grp = w; grp < n_full; grp += 8) {
-        if (grp + 4 < n_full) load_group(f1, pool, blk_of(grp + 4, 0), blk_of(grp + 4, 1), c, Hkv, lane);
-        compute_group<NQT, false>(st, f0, qlds, kGrp, scale_log2, lane);
-        if (grp + 8 < n_full) load_group(f0, pool, blk_of(grp + 8, 0), blk_of(grp + 8, 1), c, Hkv, lane);
-        if (grp + 4 < n_full) compute_group<NQT, false>(st, f1, qlds, kGrp, scale_log2, lane);
-    }
-    if (rem && (n_full & 3) == w) {
-        load_group(f0, pool, blk_of(n_full, 0), blk_of(n_full, 1), c, Hkv, lane);
-        compute_group<NQT, true>(st, f0, qlds, rem, scale_log2, lane);
-    }
-
-    // tree merge of the four waves through LDS: (2,3) -> (0,1), then 1 -> 0
-    if (w >= 2) store_to_lds<NQT>(st, lds + (w - 2) * kImg, lane);
-    __syncthreads();
-    if (w < 2) merge_from_lds<NQT>(st, lds + w * kImg, lane);
-    __syncthreads();
-    if (w == 1) store_to_lds<NQT>(st, lds, lane);
-    __syncthreads();
-    if (w != 0) return;
-    merge_from_lds<NQT>(st, lds, lane);
-
-    // finish: reduce l over the 4 lanes of a query, then write the final output or a partial
-    const int direct = pl.item_direct[item];
-    const int slot = pl.item_part[item];
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
+    for (int qt = 0; qt < NT; ++qt) {
         float l = st.l[qt];
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
-        int j = 16 * qt + m;
-        if (j >= G) continue;
+        int j = 16 * (qt0 + qt) + m;
+        if (qt >= n || j >= G) continue;
         if (direct) {
             float inv = 1.f / l;
             bf16_t *op = out + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD;
@@ -267,7 +234,7 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
                 *(uint2 *)(op + 16 * dt + 4 * q) = pk;
             }
         } else {
-            size_t pj = ((size_t)slot * Hkv + c) * pl.g_max + j;
+            size_t pj = ((size_t)slot * Hkv + c) * g_max + j;
             float *po = part_o + pj * kD;
 #pragma unroll
             for (int dt = 0; dt < kDT; ++dt) *(f32x4 *)(po + 16 * dt + 4 * q) = st.o[dt][qt];
@@ -276,6 +243,81 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
                 part_ml[pj * 2 + 1] = l;
             }
         }
+    }
+}
+
+// NA: query tiles of waves 0,1 (of all four waves when NB == 0); NB: query tiles of waves 2,3.
+template <int NA, int NB>
+__global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ qg, const bf16_t *__restrict__ pool,
+                                                     const int32_t *__restrict__ bt, int max_blocks, AttnPlan pl,
+                                                     bf16_t *__restrict__ out, float *__restrict__ part_o,
+                                                     float *__restrict__ part_ml, int Hq, int Hkv, float scale_log2) {
+    constexpr int NQT = NA + NB;
+    constexpr int kImg = kDT * NA * 4 * 64 + 2 * NA * 64;  // floats per wave image of the merge
+    extern __shared__ float lds[];
+    const int item = blockIdx.x / Hkv, c = blockIdx.x % Hkv;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int s = pl.item_seq[item];
+    const int tok_begin = pl.item_begin[item];
+    const int kvlen = pl.seq_kvlen[s];
+    const int tok_end = min(tok_begin + pl.chunk, kvlen);
+    const int row0 = pl.seq_row0[s], T = pl.seq_rows[s];
+    const int g = Hq / Hkv, G = T * g;
+    const int m = lane & 15, q = lane >> 4;
+    const int32_t *btr = bt + (size_t)s * max_blocks;
+
+    // Q fragments (B operands) go to LDS once, as [qt][ks][lane]; wave w stages k-step w.
+    // query j = 16qt + m  ->  row row0 + j / g, head c*g + j % g; rows past G are zero.
+    bf16x8 *qlds = (bf16x8 *)(lds + 2 * kImg);
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) {
+        int j = 16 * qt + m;
+        const bf16_t *qp = qg + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD + 8 * q + 32 * w;
+        qlds[(qt * kKS + w) * 64 + lane] = j < G ? *(const bf16x8 *)qp : zero8();
+    }
+    // The chunk's block ids go to LDS too: a lookup in the loop is then an LDS read, not a global
+    // load whose wait would also drain the KV loads in flight.
+    int *blds = (int *)(qlds + NQT * kKS * 64);
+    const int n_tok = tok_end - tok_begin;
+    const int n_blk = (n_tok + kBk - 1) / kBk;
+    for (int i = threadIdx.x; i < n_blk; i += 256) blds[i] = btr[tok_begin / kBk + i];
+    __syncthreads();
+
+    State<NA> st;
+#pragma unroll
+    for (int qt = 0; qt < NA; ++qt) {
+        st.m[qt] = -INFINITY;
+        st.l[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt) st.o[dt][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const int direct = pl.item_direct[item];
+    const int slot = pl.item_part[item];
+
+    if constexpr (NB == 0) {
+        wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, w, 4, c, Hkv, qlds, scale_log2, lane);
+        // tree merge of the four waves through LDS: (2,3) -> (0,1), then 1 -> 0
+        if (w >= 2) store_to_lds<NA>(st, lds + (w - 2) * kImg, lane);
+        __syncthreads();
+        if (w < 2) merge_from_lds<NA>(st, lds + w * kImg, lane);
+        __syncthreads();
+        if (w == 1) store_to_lds<NA>(st, lds, lane);
+        __syncthreads();
+        if (w != 0) return;
+        merge_from_lds<NA>(st, lds, lane);
+        finish<NA>(st, 0, NA, G, g, row0, c, Hq, Hkv, direct, slot, pl.g_max, out, part_o, part_ml, lane);
+    } else {
+        const int role = w >> 1, half = w & 1;  // role: which query tiles; half: which groups
+        if (role == 0)
+            wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, half, 2, c, Hkv, qlds, scale_log2, lane);
+        else
+            wave_walk<NA, NB>(st, pool, blds, n_blk, n_tok, half, 2, c, Hkv, qlds + NA * kKS * 64, scale_log2, lane);
+        // each pair merges its two halves through its own LDS image
+        if (half == 1) store_to_lds<NA>(st, lds + role * kImg, lane);
+        __syncthreads();
+        if (half == 1) return;
+        merge_from_lds<NA>(st, lds + role * kImg, lane);
+        finish<NA>(st, role ? NA : 0, role ? NB : NA, G, g, row0, c, Hq, Hkv, direct, slot, pl.g_max, out, part_o, part_ml, lane);
     }
 }
 
@@ -303,19 +345,20 @@ __global__ void __launch_bounds__(128) k_attn_merge(const float *__restrict__ pa
     out[((size_t)row * Hq + h) * kD + d] = f32_to_bf16(num / den);
 }
 
-template <int NQT>
+template <int NA, int NB>
 hipError_t launch_one(const void *q, const void *pool, const int32_t *bt, int max_blocks, const AttnPlan &pl, void *out,
                       float *part_o, float *part_ml, int Hq, int Hkv, float scale_log2, hipStream_t st) {
-    constexpr int kImg = kDT * NQT * 4 * 64 + 2 * NQT * 64;
-    size_t shm = (size_t)2 * kImg * sizeof(float) + (size_t)NQT * kKS * 64 * 16;  // merge images + Q fragments
+    constexpr int kImg = kDT * NA * 4 * 64 + 2 * NA * 64;
+    // merge images + Q fragments + the chunk's block ids (chunk <= kAttnMaxChunk tokens)
+    size_t shm = (size_t)2 * kImg * sizeof(float) + (size_t)(NA + NB) * kKS * 64 * 16 + (size_t)(kAttnMaxChunk / kBk) * 4;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_attn_decode<NQT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+        hipError_t e = hipFuncSetAttribute((const void *)k_attn_decode<NA, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(k_attn_decode<NQT>, dim3(pl.n_items * Hkv), dim3(256), shm, st, (const bf16_t *)q, (const bf16_t *)pool, bt,
-                       max_blocks, pl, (bf16_t *)out, part_o, part_ml, Hq, Hkv, scale_log2);
+    hipLaunchKernelGGL((k_attn_decode<NA, NB>), dim3(pl.n_items * Hkv), dim3(256), shm, st, (const bf16_t *)q, (const bf16_t *)pool,
+                       bt, max_blocks, pl, (bf16_t *)out, part_o, part_ml, Hq, Hkv, scale_log2);
     return hipGetLastError();
 }
 
@@ -328,14 +371,15 @@ bool attn_decode_mfma_supported(const Dims &dm, int g_max) {
 hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
                                    const AttnPlan &pl, void *out, float *part_o, float *part_ml, hipStream_t st) {
     if (pl.n_items <= 0) return hipSuccess;
+    if (pl.chunk > kAttnMaxChunk || pl.chunk % 128) return hipErrorInvalidValue;
     float scale_log2 = kLog2e / sqrtf((float)dm.D);
     int nqt = (pl.g_max + 15) / 16;
     switch (nqt) {
-    case 1: return launch_one<1>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
-    case 2: return launch_one<2>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
-    case 3: return launch_one<3>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
-    case 4: return launch_one<4>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
-    case 5: return launch_one<5>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 1: return launch_one<1, 0>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 2: return launch_one<2, 0>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 3: return launch_one<3, 0>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 4: return launch_one<2, 2>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 5: return launch_one<3, 2>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
     default: return hipErrorInvalidValue;
     }
 }

@@ -103,22 +103,26 @@ struct WsLayout {
     size_t meta_ints, max_items, gemm_part, gemm_part_bytes;
 };
 
-constexpr int kAttnTargetWgs = 2048;  // decode attention: aim for about this many workgroups
+constexpr int kAttnTargetWgs = 1280;  // decode attention: aim for about this many workgroups (5 per CU)
+constexpr int kAttnMaxChunk = 16384;  // tokens per attention chunk, at most (block ids of a chunk sit in LDS)
 constexpr int kAttnGMax = 80;         // largest stacked query group the MFMA attention covers
 constexpr int kShrinkMaxSplits = 16;  // split-K slices of the LoRA shrink GEMM
 constexpr int kGemmMaxSplits = 16;    // split-K slices of a narrow ICaRusLinear GEMM
 
 // Upper bounds used for sizing: chunks (= partial slots) of a call and its largest stacked group.
-size_t attn_max_items(const icarus_ctx *ctx, size_t seqs) { return (size_t)kAttnTargetWgs / ctx->cfg.n_kv_heads + seqs + 1; }
+size_t attn_max_items(const icarus_ctx *ctx, size_t seqs, size_t max_ctx) {
+    size_t by_target = (size_t)4 * kAttnTargetWgs / ctx->cfg.n_kv_heads, by_cap = seqs * (max_ctx / kAttnMaxChunk);
+    return std::max(by_target, by_cap) + seqs + 1;
+}
 
-WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t /*max_ctx*/) {
+WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t max_ctx) {
     const icarus_layer_config &c = ctx->cfg;
     size_t es = c.dtype == ICARUS_BF16 ? 2 : 4;
     size_t qd = (size_t)c.n_q_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim;
     WsLayout w{};
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    w.max_items = attn_max_items(ctx, seqs);
+    w.max_items = attn_max_items(ctx, seqs, max_ctx);
     w.meta_ints = 4 * rows + 5 * seqs + 4 * w.max_items + 64;
     w.meta = take(w.meta_ints * 4);
     {
@@ -279,7 +283,7 @@ void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t
     if (!attn_decode_mfma_supported(ctx->dm, g_max) || g_max > kAttnGMax) return;
     int64_t chunk = (total * c.n_kv_heads + kAttnTargetWgs - 1) / kAttnTargetWgs;
     if (ctx->attn_chunk_override > 0) chunk = ctx->attn_chunk_override;
-    chunk = std::max<int64_t>(128, (chunk + 127) / 128 * 128);
+    chunk = std::min<int64_t>(kAttnMaxChunk, std::max<int64_t>(ctx->attn_chunk_override > 0 ? 128 : 256, (chunk + 127) / 128 * 128));
     size_t n_items = 0;
     for (int s = 0; s < S; ++s)
         if (seq_rows[s] > 0) n_items += (size_t)((kv_lens[s] + chunk - 1) / chunk);
