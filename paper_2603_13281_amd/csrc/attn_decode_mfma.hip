@@ -39,7 +39,9 @@ constexpr int kGrp = 32;      // tokens per wave iteration (two blocks)
 constexpr int kKS = kD / 32;  // k-steps of the QK^T contraction
 constexpr int kDT = kD / 16;  // d tiles of the PV product
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kSlack = 8.f;  // log2 units a score may exceed the softmax reference before it is moved
 constexpr int kAttnMaxChunk = 16384;  // tokens per workgroup chunk, at most
+constexpr size_t kRingBytes = (size_t)2 * 4 * 16 * 64 * 16;  // shared KV ring: 2 rounds x 4 groups x 16 KB
 
 struct KVFrag {
     bf16x8 k[2][kKS];  // k[t][ks]: A operand of S^T tile t, k-step ks
@@ -120,26 +122,30 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
         float mx = sv[0];
 #pragma unroll
         for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_old = st.m[qt];
-        const float m_new = fmaxf(m_old, mx);  // finite: every group has at least one valid token
-        st.m[qt] = m_new;
-        float rs = 0.f;
-        bf16x8 pb;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float p = __builtin_amdgcn_exp2f(sv[e] - m_new);
-            rs += p;
-            pb[e] = (__bf16)p;
-        }
-        if (__any(m_new != m_old)) {  // the running max moved for some query of this tile: rescale
+        // st.m is a reference exponent, not necessarily the exact running max: it moves (and the
+        // accumulators are rescaled) only when some score exceeds it by more than kSlack, so
+        // p = 2^(s - m) stays below 2^kSlack and the common case needs no cross-lane exchange.
+        if (__any(mx > st.m[qt] + kSlack)) {
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_old = st.m[qt];
+            const float m_new = fmaxf(m_old, mx);  // finite: every group has at least one valid token
+            st.m[qt] = m_new;
             float alpha = __builtin_amdgcn_exp2f(m_old - m_new);
             st.l[qt] *= alpha;
 #pragma unroll
             for (int dt = 0; dt < kDT; ++dt) {
                 st.o[dt][qt][0] *= alpha; st.o[dt][qt][1] *= alpha; st.o[dt][qt][2] *= alpha; st.o[dt][qt][3] *= alpha;
             }
+        }
+        const float m_ref = st.m[qt];
+        float rs = 0.f;
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float p = __builtin_amdgcn_exp2f(sv[e] - m_ref);
+            rs += p;
+            pb[e] = (__bf16)p;
         }
         st.l[qt] += rs;
 #pragma unroll
@@ -150,7 +156,10 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
 // A wave's walk over its share of the chunk: groups first, first + stride, ... with N query tiles.
 // Full groups run in a loop with two register buffers, loads issued one group ahead; the chunk's
 // one partial group (if any) is done last by the wave it falls to.
-template <int NT, int N>
+// LOCKSTEP: every wave of the workgroup runs the same number of loop iterations and meets at a
+// barrier before each round of loads, so that the two waves that load the same group do it at the
+// same time and the second load is served by the caches instead of HBM.
+template <int NT, int N, bool LOCKSTEP>
 __device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
                                           int n_blk, int n_tok, int first, int stride, int c, int Hkv,
                                           const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
@@ -160,10 +169,13 @@ __device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restric
     };
     KVFrag f0, f1;
     if (first < n_full) load_group(f0, pool, blk_of(first, 0), blk_of(first, 1), c, Hkv, lane);
+    const int n_it = (n_full + 2 * stride - 1) / (2 * stride);  // the same for every wave
 #pragma nounroll
-    for (int grp = first; grp < n_full; grp += 2 * stride) {
+    for (int it = 0; it < n_it; ++it) {
+        const int grp = first + it * 2 * stride;
+        if (LOCKSTEP && (it & 1) == 0) __syncthreads();
         if (grp + stride < n_full) load_group(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
-        compute_group<NT, N, false>(st, f0, qlds, kGrp, scale_log2, lane);
+        if (grp < n_full) compute_group<NT, N, false>(st, f0, qlds, kGrp, scale_log2, lane);
         if (grp + 2 * stride < n_full) load_group(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
         if (grp + stride < n_full) compute_group<NT, N, false>(st, f1, qlds, kGrp, scale_log2, lane);
     }
@@ -171,6 +183,56 @@ __device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restric
         load_group(f0, pool, blk_of(n_full, 0), blk_of(n_full, 1), c, Hkv, lane);
         compute_group<NT, N, true>(st, f0, qlds, rem, scale_log2, lane);
     }
+}
+
+// The walk used when the query tiles are split over wave pairs (more than 3 tiles).  Every group
+// must reach two waves (one per tile set) but should come from HBM once and stay a distinct load
+// in flight, so loading and computing are decoupled: in each round of four groups wave w loads
+// group 4r + w into registers, publishes it to an LDS ring as MFMA fragments in lane order, and
+// after one barrier computes the two groups of its parity (half) for its own tiles from the ring.
+// The loads of the next round are in flight while a round is computed.  ring: [2][4][16][64] x 16 B.
+template <int NT, int N>
+__device__ __forceinline__ void shared_walk(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
+                                            int n_blk, int n_tok, int w, int half, int c, int Hkv, bf16x8 *__restrict__ ring,
+                                            const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
+    const int n_grp = (n_tok + kGrp - 1) / kGrp, rem = n_tok % kGrp;  // groups, the partial one included
+    const int n_round = (n_grp + 3) / 4;                               // the same for every wave
+    auto blk_of = [&](int grp, int which) {
+        return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
+    };
+    KVFrag f;
+    if (w < n_grp) load_group(f, pool, blk_of(w, 0), blk_of(w, 1), c, Hkv, lane);
+#pragma nounroll
+    for (int r = 0; r < n_round; ++r) {
+        bf16x8 *stage = ring + (size_t)(r & 1) * 4 * 16 * 64;
+        const int mine = 4 * r + w;
+        if (mine < n_grp) {
+            bf16x8 *dst = stage + (size_t)w * 16 * 64 + lane;
+#pragma unroll
+            for (int i = 0; i < 2 * kKS; ++i) dst[i * 64] = f.k[i / kKS][i % kKS];
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) dst[(2 * kKS + dt) * 64] = f.v[dt];
+        }
+        if (mine + 4 < n_grp) load_group(f, pool, blk_of(mine + 4, 0), blk_of(mine + 4, 1), c, Hkv, lane);
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int gi = half + 2 * u, grp = 4 * r + gi;
+            if (grp < n_grp) {
+                const bf16x8 *src = stage + (size_t)gi * 16 * 64 + lane;
+                KVFrag gfr;
+#pragma unroll
+                for (int i = 0; i < 2 * kKS; ++i) gfr.k[i / kKS][i % kKS] = src[i * 64];
+#pragma unroll
+                for (int dt = 0; dt < kDT; ++dt) gfr.v[dt] = src[(2 * kKS + dt) * 64];
+                if (rem && grp == n_grp - 1)
+                    compute_group<NT, N, true>(st, gfr, qlds, rem, scale_log2, lane);
+                else
+                    compute_group<NT, N, false>(st, gfr, qlds, kGrp, scale_log2, lane);
+            }
+        }
+    }
+    __syncthreads();  // the ring may be reused now
 }
 
 // LDS image of a state: o as [dt][qt][i][lane], then m[qt][lane], l[qt][lane].
@@ -268,7 +330,10 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
 
     // Q fragments (B operands) go to LDS once, as [qt][ks][lane]; wave w stages k-step w.
     // query j = 16qt + m  ->  row row0 + j / g, head c*g + j % g; rows past G are zero.
-    bf16x8 *qlds = (bf16x8 *)(lds + 2 * kImg);
+    // LDS: [merge images | KV ring] [Q fragments] [block ids]; the merge images reuse the ring.
+    constexpr size_t kHead = NB ? kRingBytes : (size_t)2 * kImg * sizeof(float);
+    static_assert(!NB || kRingBytes >= (size_t)2 * kImg * sizeof(float), "merge images must fit the ring");
+    bf16x8 *qlds = (bf16x8 *)((char *)lds + kHead);
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
         int j = 16 * qt + m;
@@ -295,7 +360,7 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     const int slot = pl.item_part[item];
 
     if constexpr (NB == 0) {
-        wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, w, 4, c, Hkv, qlds, scale_log2, lane);
+        wave_walk<NA, NA, false>(st, pool, blds, n_blk, n_tok, w, 4, c, Hkv, qlds, scale_log2, lane);
         // tree merge of the four waves through LDS: (2,3) -> (0,1), then 1 -> 0
         if (w >= 2) store_to_lds<NA>(st, lds + (w - 2) * kImg, lane);
         __syncthreads();
@@ -308,10 +373,11 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
         finish<NA>(st, 0, NA, G, g, row0, c, Hq, Hkv, direct, slot, pl.g_max, out, part_o, part_ml, lane);
     } else {
         const int role = w >> 1, half = w & 1;  // role: which query tiles; half: which groups
+        bf16x8 *ring = (bf16x8 *)lds;
         if (role == 0)
-            wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, half, 2, c, Hkv, qlds, scale_log2, lane);
+            shared_walk<NA, NA>(st, pool, blds, n_blk, n_tok, w, half, c, Hkv, ring, qlds, scale_log2, lane);
         else
-            wave_walk<NA, NB>(st, pool, blds, n_blk, n_tok, half, 2, c, Hkv, qlds + NA * kKS * 64, scale_log2, lane);
+            shared_walk<NA, NB>(st, pool, blds, n_blk, n_tok, w, half, c, Hkv, ring, qlds + NA * kKS * 64, scale_log2, lane);
         // each pair merges its two halves through its own LDS image
         if (half == 1) store_to_lds<NA>(st, lds + role * kImg, lane);
         __syncthreads();
@@ -350,7 +416,8 @@ hipError_t launch_one(const void *q, const void *pool, const int32_t *bt, int ma
                       float *part_o, float *part_ml, int Hq, int Hkv, float scale_log2, hipStream_t st) {
     constexpr int kImg = kDT * NA * 4 * 64 + 2 * NA * 64;
     // merge images + Q fragments + the chunk's block ids (chunk <= kAttnMaxChunk tokens)
-    size_t shm = (size_t)2 * kImg * sizeof(float) + (size_t)(NA + NB) * kKS * 64 * 16 + (size_t)(kAttnMaxChunk / kBk) * 4;
+    size_t shm = (NB ? kRingBytes : (size_t)2 * kImg * sizeof(float)) + (size_t)(NA + NB) * kKS * 64 * 16 +
+                 (size_t)(kAttnMaxChunk / kBk) * 4;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)k_attn_decode<NA, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
