@@ -8,13 +8,17 @@
 // each row exactly its own adapter.  The extension costs M*r extra K on top of K (3-5 %) and needs
 // no row reordering: the base weights are still read once for all streams (Alg. 2).
 //
-// Tiling: 256 threads = 4 waves as 2 x 2; workgroup tile 128 rows x BN columns, K staged 64 at a
-// time through double-buffered LDS (16-byte coalesced global loads -> registers -> LDS), MFMA
-// 32x32x16 bf16 on 64 x (BN/2) wave tiles.  LDS rows are padded to 144 bytes so that fragment reads
+// Tiling: 256 threads = 4 waves as 2 x 2; workgroup tile 128 rows x BN columns; MFMA 32x32x16 bf16
+// on 64 x (BN/2) wave tiles.  K advances BK at a time: 16-byte coalesced global loads land in a ring
+// of PF register stages (so PF-1 slabs are in flight while one is computed), go to double-buffered
+// LDS, and are read back as MFMA fragments.  LDS rows are padded by 16 bytes so that fragment reads
 // (16 bytes per lane, 32 consecutive rows) are bank-conflict free.
 //
 // MFMA 32x32x16 bf16 operand layout (lane l): A[row l%32][k 8(l/32)..+7], B[k 8(l/32)..+7][col l%32],
 // C[row 8(r/4) + 4(l/32) + r%4][col l%32] for accumulator register r = 0..15.
+#include <cstdio>
+#include <cstdlib>
+
 #include "device_util.h"
 #include "kernels.h"
 
@@ -25,54 +29,66 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 namespace {
 
-constexpr int kBM = 128, kBK = 64;
-constexpr int kLd = kBK + 8;  // LDS row stride in elements (144 bytes)
+constexpr int kBM = 128;
+constexpr int kKAlign = 64;  // K of every GEMM is a multiple of this
 
 __device__ __forceinline__ uint4 ldg16(const bf16_t *p) { return *(const uint4 *)p; }
 
-// Source row of LDS B-row `b` of this tile at extended-K position k (multiple of 8):
-// returns a pointer to 8 consecutive bf16, or nullptr for zeros.
+// Per-thread description of one 16-byte load of the weight (B) tile, fixed for the whole K loop.
+// Every address the loop forms from it is valid memory (rows and columns past the matrix are
+// clamped to its last row / column: they only feed outputs that are never stored), so that loads
+// are unconditional and many can be in flight; chunks that must read as zeros are masked after
+// the load.
+struct BRow {
+    const bf16_t *w;   // weight row + chunk offset: base-K loads are w + k
+    const bf16_t *b;   // adapter B of this output column: &B[0][n][0] + chunk offset inside a model
+    int kind;          // 0: no adapter columns; 1: adapter range [0, M*r); 2: range [M*r, 2*M*r) (up rows)
+};
+
 template <int BN>
-__device__ __forceinline__ const bf16_t *b_src(const GemmArgs &g, int tile_n, int b, int k) {
+__device__ __forceinline__ BRow b_row(const GemmArgs &g, int tile_n, int b) {
+    BRow o;
     if (g.mode == GEMM_DUAL) {
         // tile covers BN/2 output columns: LDS row b -> wave column b / (BN/2), j = gate/up, nn
         constexpr int HW = BN / 2;          // rows per wave column
         int wn = b / HW, j = (b % HW) / (HW / 2), nn = b % (HW / 2);
-        int n = tile_n * (BN / 2) + wn * (HW / 2) + nn;
-        if (n >= g.n_seg[0]) return nullptr;
-        if (k < g.K) return g.W[j] + (size_t)n * g.K + k;
-        int k2 = k - g.K;                   // [0, r*M): gate adapters, [r*M, 2*r*M): up adapters
-        int mr = g.M_models * g.r;
-        if (k2 >= 2 * mr || (k2 >= mr) != (j == 1)) return nullptr;
-        k2 -= j * mr;
-        return g.B[j] + ((size_t)(k2 / g.r) * g.n_seg[0] + n) * g.r + k2 % g.r;
+        int n = min(tile_n * (BN / 2) + wn * (HW / 2) + nn, g.n_seg[0] - 1);
+        o.w = (j ? g.W[1] : g.W[0]) + (size_t)n * g.K;
+        const bf16_t *B = j ? g.B[1] : g.B[0];
+        o.kind = (g.T && B) ? 1 + j : 0;
+        o.b = o.kind ? B + (size_t)n * g.r : o.w;
+        return o;
     }
     // plain: up to three weight segments stacked along N; tiles never straddle segments
-    int seg = 0, t = tile_n;
-    while (seg + 1 < g.nseg && t >= g.tiles_seg[seg]) { t -= g.tiles_seg[seg]; ++seg; }
-    int n = t * BN + b;
-    if (n >= g.n_seg[seg]) return nullptr;
-    if (k < g.K) return g.W[seg] + (size_t)n * g.K + k;
-    int k2 = k - g.K;
-    if (seg != 0 || !g.B[0] || k2 >= g.M_models * g.r) return nullptr;
-    return g.B[0] + ((size_t)(k2 / g.r) * g.n_seg[0] + n) * g.r + k2 % g.r;
+    int t = tile_n;
+    const bf16_t *W = g.W[0];
+    int n_seg = g.n_seg[0];
+    bool first = true;
+    if (g.nseg > 1 && t >= g.tiles_seg[0]) {
+        t -= g.tiles_seg[0]; W = g.W[1]; n_seg = g.n_seg[1]; first = false;
+        if (g.nseg > 2 && t >= g.tiles_seg[1]) { t -= g.tiles_seg[1]; W = g.W[2]; n_seg = g.n_seg[2]; }
+    }
+    int n = min(t * BN + b, n_seg - 1);
+    o.w = W + (size_t)n * g.K;
+    o.kind = (first && g.T && g.B[0]) ? 1 : 0;
+    o.b = o.kind ? g.B[0] + (size_t)n * g.r : o.w;
+    return o;
 }
 
-// Source of A-row (activation row) at extended-K position k.
-__device__ __forceinline__ const bf16_t *a_src(const GemmArgs &g, int row, int k) {
-    if (row >= g.R) return nullptr;
-    if (k < g.K) return g.X + (size_t)row * g.ldx + k;
-    int k2 = k - g.K;
-    if (!g.T || k2 >= g.ldt) return nullptr;
-    return g.T + (size_t)row * g.ldt + k2;
+__device__ __forceinline__ uint4 masked(uint4 v, bool ok) {
+    uint32_t m = ok ? 0xffffffffu : 0u;
+    return uint4{v.x & m, v.y & m, v.z & m, v.w & m};
 }
 
-template <int BN>
+template <int BN, int BK, int PF>
 __global__ void __launch_bounds__(256) k_gemm_mfma(GemmArgs g) {
     constexpr int WN = BN / 2;        // wave tile columns
     constexpr int TN = WN / 32;       // 32-col MFMA tiles per wave
-    constexpr int A_LD = kBM * kBK / 8 / 256;  // 16-byte loads per thread for the A tile (4)
-    constexpr int B_LD = BN * kBK / 8 / 256;
+    constexpr int CPR = BK / 8;       // 16-byte chunks per tile row
+    constexpr int A_LD = kBM * CPR / 256;  // 16-byte loads per thread for the A tile
+    constexpr int B_LD = BN * CPR / 256;
+    constexpr int kLd = BK + 8;       // LDS row stride in elements
+    static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for 256 threads");
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     bf16_t *As = smem;                         // [2][kBM][kLd]
     bf16_t *Bs = smem + 2 * kBM * kLd;         // [2][BN][kLd]
@@ -90,7 +106,7 @@ __global__ void __launch_bounds__(256) k_gemm_mfma(GemmArgs g) {
     const int kz = blockIdx.y;                  // split-K slice
     const int k_begin = kz * g.k_per_split;
     const int k_end = min(g.K_ext, k_begin + g.k_per_split);
-    const int nk = (k_end - k_begin + kBK - 1) / kBK;
+    const int nk = (k_end - k_begin + BK - 1) / BK;
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wm = w >> 1, wn = w & 1;
@@ -104,80 +120,95 @@ __global__ void __launch_bounds__(256) k_gemm_mfma(GemmArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 ra[A_LD], rb[B_LD];
-    // Row pointers of this thread's 16-byte loads at k = 0 (null: the row is outside the matrix).
-    // Inside the base-K range a load is pointer + k; only the few adapter slabs past K take the
-    // general source functions.
-    const bf16_t *pa[A_LD], *pb[B_LD];
+    // This thread's 16-byte loads: row sources fixed for the whole K loop.  Base-K slabs are
+    // pointer + k; the few adapter slabs past K read T (activations side) and the models' B.
+    const bf16_t *pa[A_LD], *pt[A_LD];
+    BRow br[B_LD];
+    int kca[A_LD], kcb[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-        int e = tid + i * 256;
-        pa[i] = a_src(g, row0 + (e >> 3), (e & 7) * 8);
+        int e = tid + i * 256, row = min(row0 + e / CPR, g.R - 1);
+        kca[i] = (e % CPR) * 8;
+        pa[i] = g.X + (size_t)row * g.ldx + kca[i];
+        pt[i] = g.T ? g.T + (size_t)row * g.ldt + kca[i] : pa[i];
     }
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
         int e = tid + i * 256;
-        pb[i] = b_src<BN>(g, tile_n, e >> 3, (e & 7) * 8);
+        kcb[i] = (e % CPR) * 8;
+        br[i] = b_row<BN>(g, tile_n, e / CPR);
+        br[i].w += kcb[i];
     }
-    auto gload = [&](int kt) {
-        int k0 = k_begin + kt * kBK;
-        if (k0 + kBK <= g.K) {  // whole slab inside the base weights (K is a multiple of the slab)
+    const int K_base = g.K, mr = g.M_models * g.r, lr = 31 - __clz(max(g.r, 1)), ldt = g.T ? g.ldt : 0;
+    const size_t model_stride = (size_t)g.n_seg[0] * g.r;  // elements between consecutive models' B
+    uint4 ra[PF][A_LD], rb[PF][B_LD];
+    auto gload = [&](int kt, uint4 (&qa)[A_LD], uint4 (&qb)[B_LD]) {
+        const int k0 = k_begin + kt * BK;
+        if (k0 < K_base) {  // slab inside the base weights (K is a multiple of the slab)
 #pragma unroll
-            for (int i = 0; i < A_LD; ++i) ra[i] = pa[i] ? ldg16(pa[i] + k0) : uint4{0, 0, 0, 0};
+            for (int i = 0; i < A_LD; ++i) qa[i] = ldg16(pa[i] + k0);
 #pragma unroll
-            for (int i = 0; i < B_LD; ++i) rb[i] = pb[i] ? ldg16(pb[i] + k0) : uint4{0, 0, 0, 0};
+            for (int i = 0; i < B_LD; ++i) qb[i] = ldg16(br[i].w + k0);
             return;
         }
+        const int k2 = k0 - K_base;  // adapter slab (r is a power of two)
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
-            int e = tid + i * 256, rr = e >> 3, kc = (e & 7) * 8;
-            const bf16_t *p = (k0 + kc < k_end) ? a_src(g, row0 + rr, k0 + kc) : nullptr;
-            ra[i] = p ? ldg16(p) : uint4{0, 0, 0, 0};
+            bool ok = k2 + kca[i] < ldt && k0 + kca[i] < k_end;
+            qa[i] = masked(ldg16(ok ? pt[i] + k2 : pa[i]), ok);
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
-            int e = tid + i * 256, rr = e >> 3, kc = (e & 7) * 8;
-            const bf16_t *p = (k0 + kc < k_end) ? b_src<BN>(g, tile_n, rr, k0 + kc) : nullptr;
-            rb[i] = p ? ldg16(p) : uint4{0, 0, 0, 0};
+            int kk = k2 + kcb[i] - (br[i].kind == 2 ? mr : 0);
+            bool ok = br[i].kind != 0 && kk >= 0 && kk < mr && k0 + kcb[i] < k_end;
+            const bf16_t *p = br[i].b + (size_t)(kk >> lr) * model_stride + (kk & (g.r - 1));
+            qb[i] = masked(ldg16(ok ? p : br[i].w), ok);
         }
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](int buf, const uint4 (&qa)[A_LD], const uint4 (&qb)[B_LD]) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
-            int e = tid + i * 256, rr = e >> 3, kc = (e & 7) * 8;
-            *(uint4 *)(As + ((size_t)buf * kBM + rr) * kLd + kc) = ra[i];
+            int e = tid + i * 256, rr = e / CPR, kc = (e % CPR) * 8;
+            *(uint4 *)(As + ((size_t)buf * kBM + rr) * kLd + kc) = qa[i];
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
-            int e = tid + i * 256, rr = e >> 3, kc = (e & 7) * 8;
-            *(uint4 *)(Bs + ((size_t)buf * BN + rr) * kLd + kc) = rb[i];
+            int e = tid + i * 256, rr = e / CPR, kc = (e % CPR) * 8;
+            *(uint4 *)(Bs + ((size_t)buf * BN + rr) * kLd + kc) = qb[i];
         }
     };
 
-    if (nk > 0) {
-        gload(0);
-        sstore(0);
-    }
+    // slab t lives in register stage t % PF from its load until it is stored to LDS buffer t & 1
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+        if (p < nk) gload(p, ra[p], rb[p]);
+    if (nk > 0) sstore(0, ra[0], rb[0]);
     __syncthreads();
     const int fr = lane & 31, fk = (lane >> 5) * 8;
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) gload(kt + 1);
-        const bf16_t *Ab = As + ((size_t)buf * kBM + wm * 64 + fr) * kLd + fk;
-        const bf16_t *Bb = Bs + ((size_t)buf * BN + wn * WN + fr) * kLd + fk;
+    for (int kt0 = 0; kt0 < nk; kt0 += PF) {
 #pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) {
-            bf16x8 a0 = *(const bf16x8 *)(Ab + ks * 16);
-            bf16x8 a1 = *(const bf16x8 *)(Ab + 32 * kLd + ks * 16);
+        for (int p = 0; p < PF; ++p) {
+            const int kt = kt0 + p;
+            if (kt < nk) {
+                const int buf = kt & 1;
+                if (kt + PF < nk) gload(kt + PF, ra[p], rb[p]);  // stage p was emptied into LDS one step ago
+                const bf16_t *Ab = As + ((size_t)buf * kBM + wm * 64 + fr) * kLd + fk;
+                const bf16_t *Bb = Bs + ((size_t)buf * BN + wn * WN + fr) * kLd + fk;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                bf16x8 b = *(const bf16x8 *)(Bb + (size_t)j * 32 * kLd + ks * 16);
-                acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0][j], 0, 0, 0);
-                acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1][j], 0, 0, 0);
+                for (int ks = 0; ks < BK / 16; ++ks) {
+                    bf16x8 a0 = *(const bf16x8 *)(Ab + ks * 16);
+                    bf16x8 a1 = *(const bf16x8 *)(Ab + 32 * kLd + ks * 16);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        bf16x8 b = *(const bf16x8 *)(Bb + (size_t)j * 32 * kLd + ks * 16);
+                        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0][j], 0, 0, 0);
+                        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1][j], 0, 0, 0);
+                    }
+                }
+                if (kt + 1 < nk) sstore(buf ^ 1, ra[(p + 1) % PF], rb[(p + 1) % PF]);
             }
+            __syncthreads();
         }
-        if (kt + 1 < nk) sstore(buf ^ 1);
-        __syncthreads();
     }
 
     // epilogue: accumulator register r of tile (i, j) is row 8(r/4) + 4(lane/32) + r%4, column lane%32
@@ -267,23 +298,48 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(const float *__restrict__
     }
 }
 
-template <int BN>
-hipError_t launch_bn(const GemmArgs &g, hipStream_t st) {
-    size_t shm = (size_t)2 * (kBM + BN) * kLd * sizeof(bf16_t);
+template <int BN, int BK, int PF>
+hipError_t launch_cfg(const GemmArgs &g, hipStream_t st) {
+    size_t shm = (size_t)2 * (kBM + BN) * (BK + 8) * sizeof(bf16_t);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_mfma<BN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_mfma<BN, BK, PF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(g.m_tiles * g.n_tiles, g.splits);
-    hipLaunchKernelGGL(k_gemm_mfma<BN>, grid, dim3(256), shm, st, g);
+    hipLaunchKernelGGL((k_gemm_mfma<BN, BK, PF>), grid, dim3(256), shm, st, g);
     return hipGetLastError();
+}
+
+// Pipeline shape: K slab width and register prefetch depth.  ICARUS_GEMM_CFG = "bk,pf" overrides
+// the default for experiments.
+int gemm_cfg() {
+    static int cfg = -1;
+    if (cfg < 0) {
+        cfg = 641;
+        if (const char *e = getenv("ICARUS_GEMM_CFG")) {
+            int bk = 0, pf = 0;
+            if (sscanf(e, "%d,%d", &bk, &pf) == 2) cfg = bk * 10 + pf;
+        }
+    }
+    return cfg;
 }
 
 }  // namespace
 
-bool gemm_mfma_supported(const Dims &dm, int K) { return dm.bf16 && K % kBK == 0 && (dm.r % 8 == 0); }
+bool gemm_mfma_supported(const Dims &dm, int K) {
+    bool r_ok = dm.r == 0 || (dm.r >= 8 && (dm.r & (dm.r - 1)) == 0);  // adapter rank: a power of two >= 8
+    return dm.bf16 && K % kKAlign == 0 && r_ok;
+}
+
+int gemm_mfma_tiles(const GemmArgs &g) {
+    const int BN = 128;
+    int m_tiles = (g.R + kBM - 1) / kBM, n_tiles = 0;
+    if (g.mode == GEMM_DUAL) return m_tiles * ((g.n_seg[0] + BN / 2 - 1) / (BN / 2));
+    for (int s = 0; s < g.nseg; ++s) n_tiles += (g.n_seg[s] + BN - 1) / BN;
+    return m_tiles * n_tiles;
+}
 
 hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st) {
     if (g.R <= 0) return hipSuccess;
@@ -301,16 +357,12 @@ hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st) {
         g.K_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
     }
     if (g.splits < 1) g.splits = 1;
-    g.k_per_split = ((g.K_ext + g.splits - 1) / g.splits + kBK - 1) / kBK * kBK;
-    return launch_bn<128>(g, st);
-}
-
-int gemm_mfma_tiles(const GemmArgs &g) {
-    const int BN = 128;
-    int m_tiles = (g.R + kBM - 1) / kBM, n_tiles = 0;
-    if (g.mode == GEMM_DUAL) return m_tiles * ((g.n_seg[0] + BN / 2 - 1) / (BN / 2));
-    for (int s = 0; s < g.nseg; ++s) n_tiles += (g.n_seg[s] + BN - 1) / BN;
-    return m_tiles * n_tiles;
+    g.k_per_split = ((g.K_ext + g.splits - 1) / g.splits + kKAlign - 1) / kKAlign * kKAlign;
+    switch (gemm_cfg()) {
+    case 642: return launch_cfg<128, 64, 2>(g, st);
+    case 322: return launch_cfg<128, 32, 2>(g, st);
+    default: return launch_cfg<128, 64, 1>(g, st);
+    }
 }
 
 hipError_t launch_splitk_reduce(const float *P, int splits, int R, int N, int epi, void *Y, int ldy, const void *resid,

@@ -291,21 +291,33 @@ void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t
     int32_t *item_seq = m + at, *item_begin = item_seq + n_items, *item_part = item_begin + n_items,
             *item_direct = item_part + n_items, *seq_kvlen = item_direct + n_items, *row0 = seq_kvlen + S,
             *rows = row0 + S, *part0 = rows + S, *nparts = part0 + S;
-    size_t it = 0;
+    // Workgroups start in item order: longest chunks first, so the short tail chunks fill the gaps
+    // at the end of the launch.  Partial slots stay contiguous per sequence.
+    struct Item { int64_t cost; int32_t s, p; };
+    std::vector<Item> items;
+    items.reserve(n_items);
+    size_t slot = 0;
     for (int s = 0; s < S; ++s) {
         int np = seq_rows[s] > 0 ? (int)((kv_lens[s] + chunk - 1) / chunk) : 0;
         seq_kvlen[s] = kv_lens[s];
         row0[s] = seq_row0[s];
         rows[s] = seq_rows[s];
-        part0[s] = (int32_t)it;
+        part0[s] = (int32_t)slot;
         nparts[s] = np;
-        for (int p = 0; p < np; ++p, ++it) {
-            item_seq[it] = s;
-            item_begin[it] = (int32_t)(p * chunk);
-            item_part[it] = (int32_t)it;
-            item_direct[it] = np == 1;
-            if (np > 1) hp->has_split = true;
+        slot += (size_t)np;
+        for (int p = 0; p < np; ++p) {
+            int64_t len = std::min<int64_t>(chunk, kv_lens[s] - p * chunk);
+            items.push_back({len * (8 + seq_rows[s] * g), s, p});
         }
+        if (np > 1) hp->has_split = true;
+    }
+    std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) { return a.cost > b.cost; });
+    for (size_t it = 0; it < n_items; ++it) {
+        const Item &e = items[it];
+        item_seq[it] = e.s;
+        item_begin[it] = (int32_t)(e.p * chunk);
+        item_part[it] = part0[e.s] + e.p;
+        item_direct[it] = nparts[e.s] == 1;
     }
     const int32_t *d = dmeta + at;
     pl->item_seq = d;
