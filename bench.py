@@ -115,12 +115,89 @@ def cpu_baseline(wl, step, x_dev_out, budget_seqs=2):
             "seconds": dt}
 
 
+def main_prefill(args):
+    """Config 4: one step = icarus_prefill_kv of every sequence's chunk over its cached prefix."""
+    import numpy as np
+    import torch
+    import oracle
+    from helpers import assert_close, fill_pool
+    from paper_2603_13281_amd import workloads
+
+    K, W = min(args.steps, 20), min(args.warmup, 3)
+    wl = workloads.build_prefill_workload(args.workload, "cuda:0", verbose=True)
+    wl.layer.set_kernel_mode(args.kernel_mode)
+    sh, S = wl.shape, len(wl.chunk_lens)
+    pre = wl.batch.ctx_lens
+    x_out = torch.empty_like(wl.x)
+    run = lambda: wl.layer.prefill_kv(wl.pool, wl.block_tables, pre, wl.chunk_lens, wl.x, x_out=x_out)
+    # sample for parity + CPU baseline: sequence 0, first / last / 8 seeded chunk tokens
+    base = None
+    if not args.no_cpu_baseline:
+        s0, T, L = 0, int(wl.chunk_lens[0]), int(pre[0])
+        Kp, Vp = workloads.sequence_kv_to_host(wl, s0, L)          # prefix as cached before the call
+    run()
+    torch.cuda.synchronize()
+    if not args.no_cpu_baseline:
+        Bk = sh.block_size
+        nb = (L + T + Bk - 1) // Bk
+        cfg = oracle.LayerConfig(d_model=sh.d_model, n_q_heads=sh.n_q_heads, n_kv_heads=sh.n_kv_heads, head_dim=sh.head_dim,
+                                 d_ffn=sh.d_ffn, block_size=Bk, num_blocks=nb, qk_norm=sh.qk_norm, bf16=sh.bf16,
+                                 rope_theta=sh.rope_theta, rms_eps=sh.rms_eps, lora_scale=sh.lora_scale)
+        orc = oracle.Oracle(cfg, wl.base, None)
+        pool = orc.new_pool()
+        bt = np.arange(nb, dtype=np.int32)[None]
+        fill_pool(pool, bt[0], Kp, Vp)
+        sel = np.zeros(T, dtype=np.uint8)
+        pick = sorted(set([0, T - 1] + [int(v) for v in np.random.default_rng(7).choice(T, size=min(8, T), replace=False)]))
+        sel[pick] = 1
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        t0 = time.perf_counter()
+        want, _ = orc.prefill(pool, bt, [L], [T], wl.x_host[:T], select=sel)
+        dt = time.perf_counter() - t0
+        got = x_out[:T].to(torch.float32).cpu().numpy()
+        assert_close(got[pick], want[pick], 2e-2, "bench prefill sample vs oracle")
+        base = {"value": len(pick) / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                "sample": f"sequence 0: K/V of all {T} chunk tokens and the full layer for tokens {pick} over its {L}-token "
+                          f"prefix, {dt:.2f} s; GPU rows match the oracle within 2e-2", "seconds": dt}
+        log(f"[bench] cpu baseline: {base['value']:.2f} tok/s; sample parity ok")
+    for _ in range(W):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    wl.layer.timing_enable(True)
+    for _ in range(K):
+        run()
+    torch.cuda.synchronize()
+    ph = wl.layer.timing_read()
+    per = {k: v[0] / K for k, v in ph.items() if v[1]}
+    n_tok = wl.n_tokens
+    d, F, qd, kvd = sh.d_model, sh.d_ffn, sh.n_q_heads * sh.head_dim, sh.n_kv_heads * sh.head_dim
+    flops = {"gemm_qkv": 2 * n_tok * d * (qd + 2 * kvd), "gemm_o": 2 * n_tok * d * qd, "gemm_gateup": 4 * n_tok * d * F,
+             "gemm_down": 2 * n_tok * d * F,
+             "attn": 4 * sh.head_dim * sh.n_q_heads * int(sum(int(c) * int(p) + int(c) * (int(c) + 1) // 2 for p, c in zip(pre, wl.chunk_lens)))}
+    phases = {k: {"ms": round(ms, 4), **({"TFLOPs": round(flops[k] / (ms * 1e-3) / 1e12, 1)} if k in flops else {})} for k, ms in per.items()}
+    gemm_ms = sum(per.get(k, 0) for k in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down"))
+    gemm_tf = sum(flops[k] for k in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down")) / (gemm_ms * 1e-3) / 1e12
+    out = {"metric": "prefill tokens/s per layer step (frozen encoder over a cached prefix)", "value": n_tok / (dt / K),
+           "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": dt / K * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": wl.description, "rows": n_tok, "sequences": S},
+           "roofline": {"bound": "mfma", "achieved": gemm_tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": gemm_tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "the four ICaRusLinear GEMMs"},
+           "cpu_baseline": base, "phases": phases}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c4", "c4-small"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-mode", type=int, default=0)
     args = ap.parse_args()
@@ -136,6 +213,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     K, W = args.steps, args.warmup
+    if args.workload.startswith("c4"):
+        return main_prefill(args)
     t_build = time.perf_counter()
     wl = workloads.build_decode_workload(args.workload, dev, headroom=2 * (K + W) + 16, verbose=True)
     wl.layer.set_kernel_mode(args.kernel_mode)

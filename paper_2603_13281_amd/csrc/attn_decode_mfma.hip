@@ -84,10 +84,15 @@ struct State {
 
 // One 32-token group: S^T, online softmax, PV, one 16-query tile at a time so that only one
 // tile's scores are live.  Uses the first N tiles of st.  qlds: Q fragments of those tiles in LDS
-// as [qt][ks][lane] (B operands).  n_valid: valid tokens in this group (1..32).
+// as [qt][ks][lane] (B operands).
+// tail == false: all 32 tokens are valid for every query.
+// tail == true:  `left` tokens of the chunk remain from this group's first token on (for the row
+//   with the longest context); query tile qt of this lane may attend only to the first
+//   left - stag[qt] of them (stag: how many positions the lane's query row ends before the last
+//   row -- 0 at decode, the causal stagger of a prefill chunk).
 template <int NT, int N, bool tail>
-__device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf16x8 *__restrict__ qlds, int n_valid,
-                                              float scale_log2, int lane) {
+__device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf16x8 *__restrict__ qlds, int left,
+                                              const int (&stag)[NT], float scale_log2, int lane) {
     const int q = lane >> 4;
     // token index inside the group of S^T element (tile t, register i) on this lane: tbase + 4t + i
     const int tbase = 16 * (q >> 1) + 8 * (q & 1);
@@ -97,7 +102,7 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
         for (int dt = 0; dt < kDT; ++dt)
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                if (tbase + e >= n_valid) f.v[dt][e] = (__bf16)0.f;
+                if (tbase + e >= left) f.v[dt][e] = (__bf16)0.f;
     }
 #pragma unroll
     for (int qt = 0; qt < N; ++qt) {
@@ -115,9 +120,10 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
             sv[4 + i] = s1[i] * scale_log2;
         }
         if (tail) {
+            const int lim = left - stag[qt];
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                if (tbase + e >= n_valid) sv[e] = -INFINITY;
+                if (tbase + e >= lim) sv[e] = -INFINITY;
         }
         float mx = sv[0];
 #pragma unroll
@@ -129,9 +135,10 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_old = st.m[qt];
-            const float m_new = fmaxf(m_old, mx);  // finite: every group has at least one valid token
+            const float m_new = fmaxf(m_old, mx);
             st.m[qt] = m_new;
-            float alpha = __builtin_amdgcn_exp2f(m_old - m_new);
+            // in a tail group a query may have no valid token yet (m_new still -inf): nothing to rescale
+            float alpha = (tail && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_old - m_new);
             st.l[qt] *= alpha;
 #pragma unroll
             for (int dt = 0; dt < kDT; ++dt) {
@@ -144,6 +151,7 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             float p = __builtin_amdgcn_exp2f(sv[e] - m_ref);
+            if (tail && m_ref == -INFINITY) p = 0.f;
             rs += p;
             pb[e] = (__bf16)p;
         }
@@ -154,34 +162,31 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
 }
 
 // A wave's walk over its share of the chunk: groups first, first + stride, ... with N query tiles.
-// Full groups run in a loop with two register buffers, loads issued one group ahead; the chunk's
-// one partial group (if any) is done last by the wave it falls to.
-// LOCKSTEP: every wave of the workgroup runs the same number of loop iterations and meets at a
-// barrier before each round of loads, so that the two waves that load the same group do it at the
-// same time and the second load is served by the caches instead of HBM.
-template <int NT, int N, bool LOCKSTEP>
+// The first n_clean groups are valid for every query: they run in a loop with two register buffers,
+// loads issued one group ahead.  The few groups after them (a partial last group, the causal
+// stagger of a prefill chunk) are done with masks by the waves they fall to.
+template <int NT, int N>
 __device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
-                                          int n_blk, int n_tok, int first, int stride, int c, int Hkv,
-                                          const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
-    const int n_full = n_tok / kGrp, rem = n_tok % kGrp;
+                                          int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int first, int stride,
+                                          int c, int Hkv, const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
+    const int n_grp = (n_tok + kGrp - 1) / kGrp;
     auto blk_of = [&](int grp, int which) {
         return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
     };
     KVFrag f0, f1;
-    if (first < n_full) load_group(f0, pool, blk_of(first, 0), blk_of(first, 1), c, Hkv, lane);
-    const int n_it = (n_full + 2 * stride - 1) / (2 * stride);  // the same for every wave
+    if (first < n_clean) load_group(f0, pool, blk_of(first, 0), blk_of(first, 1), c, Hkv, lane);
 #pragma nounroll
-    for (int it = 0; it < n_it; ++it) {
-        const int grp = first + it * 2 * stride;
-        if (LOCKSTEP && (it & 1) == 0) __syncthreads();
-        if (grp + stride < n_full) load_group(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
-        if (grp < n_full) compute_group<NT, N, false>(st, f0, qlds, kGrp, scale_log2, lane);
-        if (grp + 2 * stride < n_full) load_group(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
-        if (grp + stride < n_full) compute_group<NT, N, false>(st, f1, qlds, kGrp, scale_log2, lane);
+    for (int grp = first; grp < n_clean; grp += 2 * stride) {
+        if (grp + stride < n_clean) load_group(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
+        compute_group<NT, N, false>(st, f0, qlds, kGrp, stag, scale_log2, lane);
+        if (grp + 2 * stride < n_clean) load_group(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
+        if (grp + stride < n_clean) compute_group<NT, N, false>(st, f1, qlds, kGrp, stag, scale_log2, lane);
     }
-    if (rem && n_full % stride == first) {
-        load_group(f0, pool, blk_of(n_full, 0), blk_of(n_full, 1), c, Hkv, lane);
-        compute_group<NT, N, true>(st, f0, qlds, rem, scale_log2, lane);
+#pragma nounroll
+    for (int grp = n_clean; grp < n_grp; ++grp) {
+        if (grp % stride != first) continue;
+        load_group(f0, pool, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
+        compute_group<NT, N, true>(st, f0, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
     }
 }
 
@@ -193,9 +198,10 @@ __device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restric
 // The loads of the next round are in flight while a round is computed.  ring: [2][4][16][64] x 16 B.
 template <int NT, int N>
 __device__ __forceinline__ void shared_walk(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
-                                            int n_blk, int n_tok, int w, int half, int c, int Hkv, bf16x8 *__restrict__ ring,
-                                            const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
-    const int n_grp = (n_tok + kGrp - 1) / kGrp, rem = n_tok % kGrp;  // groups, the partial one included
+                                            int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int half, int c,
+                                            int Hkv, bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds,
+                                            float scale_log2, int lane) {
+    const int n_grp = (n_tok + kGrp - 1) / kGrp;                       // groups, the masked ones included
     const int n_round = (n_grp + 3) / 4;                               // the same for every wave
     auto blk_of = [&](int grp, int which) {
         return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
@@ -225,10 +231,10 @@ __device__ __forceinline__ void shared_walk(State<NT> &st, const bf16_t *__restr
                 for (int i = 0; i < 2 * kKS; ++i) gfr.k[i / kKS][i % kKS] = src[i * 64];
 #pragma unroll
                 for (int dt = 0; dt < kDT; ++dt) gfr.v[dt] = src[(2 * kKS + dt) * 64];
-                if (rem && grp == n_grp - 1)
-                    compute_group<NT, N, true>(st, gfr, qlds, rem, scale_log2, lane);
+                if (grp >= n_clean)
+                    compute_group<NT, N, true>(st, gfr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
                 else
-                    compute_group<NT, N, false>(st, gfr, qlds, kGrp, scale_log2, lane);
+                    compute_group<NT, N, false>(st, gfr, qlds, kGrp, stag, scale_log2, lane);
             }
         }
     }
@@ -326,7 +332,7 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     const int row0 = pl.seq_row0[s], T = pl.seq_rows[s];
     const int g = Hq / Hkv, G = T * g;
     const int m = lane & 15, q = lane >> 4;
-    const int32_t *btr = bt + (size_t)s * max_blocks;
+    const int32_t *btr = bt + (size_t)pl.seq_bt[s] * max_blocks;
 
     // Q fragments (B operands) go to LDS once, as [qt][ks][lane]; wave w stages k-step w.
     // query j = 16qt + m  ->  row row0 + j / g, head c*g + j % g; rows past G are zero.
@@ -358,9 +364,16 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     }
     const int direct = pl.item_direct[item];
     const int slot = pl.item_part[item];
+    // Causal stagger (prefill chunks): row t of the sequence ends T-1-t positions before its last row.
+    // Groups below n_clean are valid for every query.
+    const int max_stag = pl.causal ? T - 1 : 0;
+    const int n_clean = max(0, n_tok - (tok_end == kvlen ? max_stag : 0)) / kGrp;
+    int stag[NA];
 
     if constexpr (NB == 0) {
-        wave_walk<NA, NA, false>(st, pool, blds, n_blk, n_tok, w, 4, c, Hkv, qlds, scale_log2, lane);
+#pragma unroll
+        for (int qt = 0; qt < NA; ++qt) stag[qt] = pl.causal && tok_end == kvlen ? T - 1 - min((16 * qt + m) / g, T - 1) : 0;
+        wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
         // tree merge of the four waves through LDS: (2,3) -> (0,1), then 1 -> 0
         if (w >= 2) store_to_lds<NA>(st, lds + (w - 2) * kImg, lane);
         __syncthreads();
@@ -374,10 +387,14 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     } else {
         const int role = w >> 1, half = w & 1;  // role: which query tiles; half: which groups
         bf16x8 *ring = (bf16x8 *)lds;
+#pragma unroll
+        for (int qt = 0; qt < NA; ++qt)
+            stag[qt] = pl.causal && tok_end == kvlen ? T - 1 - min((16 * ((role ? NA : 0) + qt) + m) / g, T - 1) : 0;
         if (role == 0)
-            shared_walk<NA, NA>(st, pool, blds, n_blk, n_tok, w, half, c, Hkv, ring, qlds, scale_log2, lane);
+            shared_walk<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
         else
-            shared_walk<NA, NB>(st, pool, blds, n_blk, n_tok, w, half, c, Hkv, ring, qlds + NA * kKS * 64, scale_log2, lane);
+            shared_walk<NA, NB>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
+                                scale_log2, lane);
         // each pair merges its two halves through its own LDS image
         if (half == 1) store_to_lds<NA>(st, lds + role * kImg, lane);
         __syncthreads();
@@ -390,7 +407,7 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
 // Combine the partial results of sequences that were split into several chunks.
 // One block of 128 threads per (row, query head); thread d owns output element d.
 __global__ void __launch_bounds__(128) k_attn_merge(const float *__restrict__ part_o, const float *__restrict__ part_ml,
-                                                    AttnPlan pl, const int32_t *__restrict__ row_seq,
+                                                    AttnPlan pl, const int32_t *__restrict__ row_seq /* row -> plan sequence */,
                                                     bf16_t *__restrict__ out, int Hq, int Hkv) {
     const int row = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
     const int s = row_seq[row];

@@ -123,7 +123,9 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t max_c
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     w.max_items = attn_max_items(ctx, seqs, max_ctx);
-    w.meta_ints = 4 * rows + 5 * seqs + 4 * w.max_items + 64;
+    // metadata: 4 row arrays, the split plan (6 arrays per plan sequence, 4 per chunk); a prefill call
+    // has up to `rows` plan sequences of one chunk each
+    w.meta_ints = 4 * rows + 6 * std::max(rows, seqs) + 4 * std::max(rows, w.max_items) + 64;
     w.meta = take(w.meta_ints * 4);
     {
         size_t g = (size_t)c.n_q_heads / c.n_kv_heads;
@@ -265,8 +267,12 @@ struct HostPlan {
     size_t ints = 0;
 };
 
+// seq_bt: block-table row of each plan sequence (null: sequence s reads row s).  causal: the rows of a
+// plan sequence are consecutive tokens of a prefill chunk (row t attends to kv_len - (rows-1-t) tokens);
+// such a sequence is never split, so the call is covered only if every kv_len fits one chunk.
 void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t *dmeta, int S, const int32_t *kv_lens,
-                     const int32_t *seq_row0, const int32_t *seq_rows, size_t max_items, HostPlan *hp) {
+                     const int32_t *seq_row0, const int32_t *seq_rows, const int32_t *seq_bt, bool causal, size_t max_items,
+                     HostPlan *hp) {
     AttnPlan *pl = &hp->pl;
     hp->valid = false;
     hp->has_split = false;
@@ -277,6 +283,7 @@ void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t
     int64_t total = 0;
     for (int s = 0; s < S; ++s) {
         if (seq_rows[s] > 0 && kv_lens[s] <= 0) return;  // empty context: generic kernel writes zeros
+        if (causal && kv_lens[s] > kAttnMaxChunk) return;
         g_max = std::max(g_max, seq_rows[s] * g);
         if (seq_rows[s] > 0) total += kv_lens[s];
     }
@@ -284,13 +291,15 @@ void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t
     int64_t chunk = (total * c.n_kv_heads + kAttnTargetWgs - 1) / kAttnTargetWgs;
     if (ctx->attn_chunk_override > 0) chunk = ctx->attn_chunk_override;
     chunk = std::min<int64_t>(kAttnMaxChunk, std::max<int64_t>(ctx->attn_chunk_override > 0 ? 128 : 256, (chunk + 127) / 128 * 128));
+    if (causal) chunk = kAttnMaxChunk;
     size_t n_items = 0;
     for (int s = 0; s < S; ++s)
         if (seq_rows[s] > 0) n_items += (size_t)((kv_lens[s] + chunk - 1) / chunk);
-    if (n_items > max_items) return;
+    if (n_items > (causal ? (size_t)INT32_MAX : max_items)) return;  // partial slots (a causal plan has no splits)
     int32_t *item_seq = m + at, *item_begin = item_seq + n_items, *item_part = item_begin + n_items,
             *item_direct = item_part + n_items, *seq_kvlen = item_direct + n_items, *row0 = seq_kvlen + S,
-            *rows = row0 + S, *part0 = rows + S, *nparts = part0 + S;
+            *rows = row0 + S, *part0 = rows + S, *nparts = part0 + S, *sbt = nparts + S;
+    for (int s = 0; s < S; ++s) sbt[s] = seq_bt ? seq_bt[s] : s;
     // Workgroups start in item order: longest chunks first, so the short tail chunks fill the gaps
     // at the end of the launch.  Partial slots stay contiguous per sequence.
     struct Item { int64_t cost; int32_t s, p; };
@@ -329,10 +338,12 @@ void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t
     pl->seq_rows = pl->seq_row0 + S;
     pl->seq_part0 = pl->seq_rows + S;
     pl->seq_nparts = pl->seq_part0 + S;
+    pl->seq_bt = pl->seq_nparts + S;
     pl->n_items = (int)n_items;
     pl->chunk = (int)chunk;
     pl->g_max = g_max;
-    hp->ints = 4 * n_items + 5 * (size_t)S;
+    pl->causal = causal ? 1 : 0;
+    hp->ints = 4 * n_items + 6 * (size_t)S;
     hp->valid = n_items > 0;
 }
 
@@ -681,7 +692,7 @@ icarus_status icarus_decode_step(icarus_ctx *ctx, void *kv_pool, const int32_t *
     char *ws = (char *)workspace;
     const int32_t *dmeta = (const int32_t *)(ws + L.meta);
     HostPlan hp;
-    build_attn_plan(ctx, m, (size_t)4 * R, dmeta, S, kvl.data(), row0.data(), rows.data(), L.max_items, &hp);
+    build_attn_plan(ctx, m, (size_t)4 * R, dmeta, S, kvl.data(), row0.data(), rows.data(), nullptr, false, L.max_items, &hp);
     rc = stage_commit(ctx, slot, ws + L.meta, ((size_t)4 * R + hp.ints) * 4, st);
     if (rc) return rc;
     RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
@@ -719,8 +730,7 @@ icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *b
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     StageSlot *slot;
-    size_t meta_bytes = (size_t)4 * R * 4;
-    rc = stage_acquire(ctx, meta_bytes, &slot);
+    rc = stage_acquire(ctx, L.meta_ints * 4, &slot);
     if (rc) return rc;
     int32_t *m = (int32_t *)slot->host;
     int r = 0;
@@ -731,12 +741,32 @@ icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *b
             m[2 * R + r] = ctx_lens[s] + i;
             m[3 * R + r] = ctx_lens[s] + i + 1;
         }
+    // Attention plan: the chunk's tokens are cut into groups of consecutive tokens whose stacked query
+    // heads fill up to three 16-query tiles; each group is one plan sequence with a causal stagger.
     char *ws = (char *)workspace;
-    rc = stage_commit(ctx, slot, ws + L.meta, meta_bytes, st);
-    if (rc) return rc;
     const int32_t *dmeta = (const int32_t *)(ws + L.meta);
+    HostPlan hp;
+    if (x_out) {
+        int g = c.n_q_heads / c.n_kv_heads, tq = std::max(1, 48 / g);
+        std::vector<int32_t> vkv, vrow0, vrows, vbt;
+        int row = 0;
+        for (int s = 0; s < S; ++s) {
+            for (int t0 = 0; t0 < chunk_lens[s]; t0 += tq) {
+                int n = std::min(tq, chunk_lens[s] - t0);
+                vkv.push_back(ctx_lens[s] + t0 + n);
+                vrow0.push_back(row + t0);
+                vrows.push_back(n);
+                vbt.push_back(s);
+            }
+            row += chunk_lens[s];
+        }
+        build_attn_plan(ctx, m, (size_t)4 * R, dmeta, (int)vkv.size(), vkv.data(), vrow0.data(), vrows.data(), vbt.data(), true,
+                        L.max_items, &hp);
+    }
+    rc = stage_commit(ctx, slot, ws + L.meta, ((size_t)4 * R + hp.ints) * 4, st);
+    if (rc) return rc;
     RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
-    return run_layer(ctx, ws, L, rm, nullptr, R, false, x_out == nullptr, 1, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
+    return run_layer(ctx, ws, L, rm, &hp, R, false, x_out == nullptr, 1, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
 }
 
 icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *kv_pool, const int32_t *block_tables,
@@ -783,7 +813,7 @@ icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *
     char *ws = (char *)workspace;
     const int32_t *dmeta = (const int32_t *)(ws + L.meta);
     HostPlan hp;
-    build_attn_plan(ctx, m, (size_t)4 * R, dmeta, S, kv_lens, row0.data(), rows.data(), L.max_items, &hp);
+    build_attn_plan(ctx, m, (size_t)4 * R, dmeta, S, kv_lens, row0.data(), rows.data(), nullptr, false, L.max_items, &hp);
     rc = stage_commit(ctx, slot, ws + L.meta, ((size_t)4 * R + hp.ints) * 4, st);
     if (rc) return rc;
     RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};

@@ -63,7 +63,9 @@ struct AttnPlan {
     const int32_t *seq_rows;     // [S] rows (stacked streams) of the sequence
     const int32_t *seq_part0;    // [S] first partial slot
     const int32_t *seq_nparts;   // [S] number of chunks
+    const int32_t *seq_bt;       // [S] row of the block table the sequence reads
     int n_items, chunk, g_max;   // g_max: largest stacked group (rows * Hq/Hkv) in the call
+    int causal;                  // 1: row t of a sequence attends to kv_len - (rows - 1 - t) tokens (prefill)
 };
 // ICaRusLinear GEMM on matrix cores.  Y = X W^T (+ T Bcat^T), see gemm_mfma.hip.
 enum { GEMM_PLAIN = 0, GEMM_DUAL = 1 };          // DUAL: W[0] = gate, W[1] = up, Y = silu(gate) * up

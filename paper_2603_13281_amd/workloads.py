@@ -74,7 +74,8 @@ def layer_config(shape: synth.LayerShape, num_blocks: int, max_position: int) ->
 def build_decode_workload(name: str, device="cuda:0", headroom: int = 128, seed: int = 0, n_x: int = 4,
                           verbose: bool = False) -> DecodeWorkload:
     shape, S, (lo, hi), (alo, ahi), desc = SPECS[name]
-    say = (lambda *a: print(*a, flush=True)) if verbose else (lambda *a: None)
+    import sys
+    say = (lambda *a: print(*a, file=sys.stderr, flush=True)) if verbose else (lambda *a: None)
     say(f"[workload {name}] weights")
     base = synth.make_base(shape, seed=seed)
     lora = synth.make_lora(shape, seed=seed)
@@ -109,3 +110,57 @@ def sequence_kv_to_host(wl: DecodeWorkload, s: int, n_tokens: int):
     K = blk[:, :, 0].reshape(nb, sh.n_kv_heads, Bk, D).transpose(0, 2, 1, 3).reshape(nb * Bk, sh.n_kv_heads, D)
     V = blk[:, :, 1].reshape(nb, sh.n_kv_heads, D, Bk).transpose(0, 3, 1, 2).reshape(nb * Bk, sh.n_kv_heads, D)
     return np.ascontiguousarray(K[:n_tokens]), np.ascontiguousarray(V[:n_tokens])
+
+
+@dataclass
+class PrefillWorkload:
+    name: str
+    description: str
+    shape: synth.LayerShape
+    batch: synth.Batch          # ctx_lens = cached prefix lengths; rows unused
+    chunk_lens: np.ndarray
+    base: dict
+    layer: binding.IcarusLayer
+    pool: torch.Tensor
+    block_tables: torch.Tensor
+    x: torch.Tensor             # [sum chunk, d]
+    x_host: np.ndarray
+
+    @property
+    def n_tokens(self) -> int:
+        return int(self.chunk_lens.sum())
+
+
+PREFILL_SPECS = {
+    "c4": (synth.LLAMA8B, 32, 8192, 512,
+           "config 4: cross-model prefill reuse, Llama-3-8B-shaped layer, 32 sequences with 8192-token cached "
+           "prefixes, each appends a 512-token chunk through the frozen encoder"),
+    "c4-small": (synth.LLAMA_SMALL, 4, 300, 70, "reduced config 4"),
+}
+
+
+def build_prefill_workload(name: str, device="cuda:0", seed: int = 0, verbose: bool = False) -> PrefillWorkload:
+    import sys
+    shape, S, prefix, chunk, desc = PREFILL_SPECS[name]
+    say = (lambda *a: print(*a, file=sys.stderr, flush=True)) if verbose else (lambda *a: None)
+    say(f"[workload {name}] weights")
+    base = synth.make_base(shape, seed=seed)
+    lens = np.full(S, prefix, dtype=np.int32)
+    batch = synth.make_batch(shape, lens, np.zeros(S, dtype=np.int32), seed=seed, headroom=chunk + 16)
+    cfg = layer_config(shape, batch.num_blocks, prefix + chunk + 17)
+    cfg.n_models, cfg.lora_rank, cfg.lora_target_mask = 0, 0, 0      # prefill uses the frozen encoder only
+    dbase = {k: upload(v, shape.bf16, device) for k, v in base.items()}
+    layer = binding.IcarusLayer(cfg, dbase, None)
+    say(f"[workload {name}] pool: {batch.num_blocks} blocks")
+    gen = torch.Generator(device=device)
+    gen.manual_seed(2000 + seed)
+    pool = torch.empty(cfg.pool_shape(), dtype=cfg.torch_dtype, device=device)
+    step_blocks = max(1, (1 << 28) // (pool[0].numel()))
+    for b0 in range(0, batch.num_blocks, step_blocks):
+        sl = pool[b0:b0 + step_blocks]
+        sl.copy_(torch.randn(sl.shape, generator=gen, device=device, dtype=torch.float32))
+    bt = torch.from_numpy(batch.block_tables).to(device)
+    chunk_lens = np.full(S, chunk, dtype=np.int32)
+    x_host = synth.make_hidden(shape, int(chunk_lens.sum()), seed=seed, tag=20)
+    x = upload(x_host, shape.bf16, device)
+    return PrefillWorkload(name, desc, shape, batch, chunk_lens, base, layer, pool, bt, x, x_host)

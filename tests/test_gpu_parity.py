@@ -299,3 +299,34 @@ def test_attn_mfma_tiles_splits_and_tails(g, rows, chunk, monkeypatch):
     got = layer.attn_shared_kv(dev(q, True), dpool, torch.from_numpy(batch.block_tables).cuda(), lens, row_seq)
     torch.cuda.synchronize()
     assert_close(host(got), want, 2e-2, "attention out")
+
+
+@pytest.mark.parametrize("shape", [synth.LLAMA_SMALL, synth.QWEN_SMALL], ids=lambda s: s.name)
+def test_prefill_causal_groups_and_boundaries(shape):
+    # prefill attention on the matrix cores: chunks cut into groups of consecutive tokens with a causal
+    # stagger; prefixes and chunk lengths around the 16-token block, 32-token group and group-size boundaries
+    _say("case: prefill causal boundaries", shape.name)
+    pre = [0, 1, 20, 31, 32, 33, 63, 64, 500, 27]
+    chunk = [1, 5, 12, 13, 25, 7, 66, 3, 130, 40]
+    base = synth.make_base(shape, seed=13, norm_ones=False)
+    batch = synth.make_batch(shape, pre, [0] * len(pre), seed=13, headroom=140)
+    pool = filled_batch(shape, batch, seed=13)
+    pool[pool == 0] = np.nan                      # never-written slots hold NaN: masked positions must not leak
+    x = synth.make_hidden(shape, sum(chunk), seed=13, tag=5)
+    orc = oracle.Oracle(oracle_config(shape, batch.num_blocks), base, None)
+    want_pool = pool.copy()
+    want, want_slots = orc.prefill(want_pool, batch.block_tables, pre, chunk, x)
+    layer = make_layer(shape, base, None, batch.num_blocks)
+    dpool = dev(pool_to_device_layout(pool), True)
+    bt = torch.from_numpy(batch.block_tables).cuda()
+    slots = torch.zeros(sum(chunk), dtype=torch.int64, device="cuda")
+    got = layer.prefill_kv(dpool, bt, pre, chunk, dev(x, True), slot_out=slots)
+    torch.cuda.synchronize()
+    assert np.array_equal(slots.cpu().numpy(), want_slots)
+    assert_close(host(got), want, 2e-2, "prefill x_out")
+    # generic kernels give the same answer (GPU vs GPU, to tolerance)
+    layer.set_kernel_mode(1)
+    dpool2 = dev(pool_to_device_layout(pool), True)
+    got2 = layer.prefill_kv(dpool2, bt, pre, chunk, dev(x, True))
+    torch.cuda.synchronize()
+    assert_close(host(got2), want, 2e-2, "prefill x_out (generic kernels)")
