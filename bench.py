@@ -54,6 +54,29 @@ def phase_model(wl, step):
     }
 
 
+PROFILE_FILES = {"c3": "attn_decode_and_layer_step__config3.md", "c5": "attn_decode_and_layer_step__config5.md",
+                 "c2": "attn_decode_and_layer_step__config2.md"}
+PHASE_KERNEL = {"attn": "k_attn_decode", "gemm_qkv": "k_gemm_mfma", "gemm_o": "k_gemm_mfma", "gemm_gateup": "k_gemm_mfma",
+                "gemm_down": "k_gemm_mfma"}
+
+
+def committed_traffic(workload, phase):
+    """HBM bytes per launch of the phase's kernel from the committed rocprofv3 FETCH_SIZE + WRITE_SIZE summary
+    (profiles/, counters scaled by the plain copy kernel).  Only attention has one launch shape per step, so only
+    its figure is per-launch exact; None when no summary is committed."""
+    path = os.path.join(ROOT, "profiles", PROFILE_FILES.get(workload, ""))
+    if phase != "attn" or not os.path.isfile(path):
+        return None
+    total = 0.0
+    found = 0
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 6 and PHASE_KERNEL[phase] in f[0] and f[1] in ("FETCH_SIZE", "WRITE_SIZE"):
+            total += float(f[-1]) * 1e6
+            found += 1
+    return total if found == 2 else None
+
+
 def run_steps(wl, n, first_step, x_out):
     for i in range(n):
         st = first_step + i
@@ -200,6 +223,8 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c4", "c4-small"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-mode", type=int, default=0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run the library's plain copy kernel on 1 GiB (for scaling rocprofv3 traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -213,6 +238,14 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     K, W = args.steps, args.warmup
+    if args.copy_calibration:
+        from paper_2603_13281_amd import binding
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)      # 1 GiB, larger than the 256 MB Infinity Cache
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            binding.bench_copy(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
     if args.workload.startswith("c4"):
         return main_prefill(args)
     t_build = time.perf_counter()
@@ -267,7 +300,7 @@ def main():
         else:
             roof = {"bound": "mfma", "achieved": flops / t / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
         roof["frac"] = roof["achieved"] / roof["peak"]
-        roof["traffic"] = None
+        roof["traffic"] = committed_traffic(args.workload, dominant)
         roof["kernel"] = dominant
         roof["avg_launch_ms"] = per_step_ms[dominant]
         roof["algorithmic_bytes"] = byts

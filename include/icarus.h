@@ -182,6 +182,11 @@ enum { ICARUS_PH_NORM = 0, ICARUS_PH_LORA, ICARUS_PH_GEMM_QKV, ICARUS_PH_ROPE_AP
 icarus_status icarus_timing_enable(icarus_ctx *ctx, int32_t on);
 icarus_status icarus_timing_read(icarus_ctx *ctx, double *ms /*host*/, int32_t *launches /*host*/);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; src, dst device, 16-byte aligned) by a
+ * grid-stride kernel named k_bench_copy.  For measurements only: a kernel that moves a known number of
+ * bytes, against which the profiler's HBM traffic counters are calibrated. */
+icarus_status icarus_bench_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

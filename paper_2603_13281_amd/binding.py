@@ -25,7 +25,7 @@ STATUS = {0: "OK", 1: "INVALID_ARG", 2: "SHAPE", 3: "ALIGNMENT", 4: "MODEL_ID", 
 
 EXPORTS = ("icarus_create", "icarus_destroy", "icarus_last_error", "icarus_workspace_bytes",
            "icarus_validate_decode", "icarus_prefill_kv", "icarus_decode_step", "icarus_attn_shared_kv",
-           "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read")
+           "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read", "icarus_bench_copy")
 
 PHASES = ("norm", "lora", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gateup", "gemm_down",
           "elementwise")
@@ -82,6 +82,8 @@ def _load():
     lib.icarus_timing_enable.argtypes = [vp, i32]
     lib.icarus_timing_read.restype = C.c_int
     lib.icarus_timing_read.argtypes = [vp, vp, vp]
+    lib.icarus_bench_copy.restype = C.c_int
+    lib.icarus_bench_copy.argtypes = [vp, vp, sz, vp]
     return lib
 
 
@@ -141,6 +143,14 @@ def _ptr(t) -> C.c_void_p:
 
 def _host_i32(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def bench_copy(src: torch.Tensor, dst: torch.Tensor):
+    """dst <- src by the library's plain copy kernel (profiler counter calibration)."""
+    n = src.numel() * src.element_size()
+    rc = _lib.icarus_bench_copy(_ptr(src), _ptr(dst), n, C.c_void_p(torch.cuda.current_stream(src.device).cuda_stream))
+    if rc != 0:
+        raise IcarusError(rc, "icarus_bench_copy failed")
 
 
 class IcarusLayer:

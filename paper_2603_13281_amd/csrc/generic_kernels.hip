@@ -4,6 +4,8 @@
 #include "device_util.h"
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace icarus {
 
 #define DISPATCH_T(bf16, ...)                         \
@@ -309,4 +311,19 @@ hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, 
     return hipGetLastError();
 }
 
+}  // namespace icarus
+
+// ------------------------------------------------------------------ plain copy (counter calibration)
+namespace icarus {
+__global__ void __launch_bounds__(256) k_bench_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, stride = (size_t)gridDim.x * 256;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+hipError_t launch_bench_copy(const void *src, void *dst, size_t bytes, hipStream_t st) {
+    size_t n16 = bytes / 16;
+    if (!n16) return hipSuccess;
+    unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(k_bench_copy, dim3(blocks), dim3(256), 0, st, (const uint4 *)src, (uint4 *)dst, n16);
+    return hipGetLastError();
+}
 }  // namespace icarus

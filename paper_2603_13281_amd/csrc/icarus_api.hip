@@ -646,6 +646,11 @@ icarus_status icarus_timing_read(icarus_ctx *ctx, double *ms, int32_t *launches)
     return ICARUS_OK;
 }
 
+icarus_status icarus_bench_copy(const void *src, void *dst, size_t bytes, void *stream) {
+    if (!src || !dst || bytes % 16 || !aligned16(src) || !aligned16(dst)) return ICARUS_ERR_INVALID_ARG;
+    return launch_bench_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? ICARUS_OK : ICARUS_ERR_HIP;
+}
+
 size_t icarus_workspace_bytes(const icarus_ctx *ctx, int32_t max_rows, int32_t max_seqs, int32_t max_ctx) {
     if (!ctx || max_rows < 0 || max_seqs < 0 || max_ctx < 0) return 0;
     return ws_layout(ctx, (size_t)std::max(1, max_rows), (size_t)std::max(1, max_seqs), (size_t)max_ctx).total;

@@ -50,6 +50,9 @@ hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, const R
 hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
                                const RowMeta &rm, void *out, int R, hipStream_t st);
 
+// plain grid-stride copy of `bytes` bytes (multiple of 16), kernel k_bench_copy: profiler calibration
+hipError_t launch_bench_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+
 // ---- matrix-core kernels (bf16 storage) ------------------------------------------------------
 // Host-built split plan of the decode attention: a sequence's cached tokens are cut into chunks
 // of `chunk` tokens; one workgroup per (chunk, kv-head).  All arrays are device int32.
