@@ -71,7 +71,7 @@ def committed_traffic(workload, phase):
     found = 0
     for line in open(path):
         f = line.split()
-        if len(f) >= 6 and PHASE_KERNEL[phase] in f[0] and f[1] in ("FETCH_SIZE", "WRITE_SIZE"):
+        if len(f) >= 6 and PHASE_KERNEL[phase] in f[0] and ("FETCH_SIZE" in f or "WRITE_SIZE" in f):
             total += float(f[-1]) * 1e6
             found += 1
     return total if found == 2 else None
