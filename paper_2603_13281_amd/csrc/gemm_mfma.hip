@@ -8,14 +8,20 @@
 // each row exactly its own adapter.  The extension costs M*r extra K on top of K (3-5 %) and needs
 // no row reordering: the base weights are still read once for all streams (Alg. 2).
 //
-// Tiling: 256 threads = 4 waves as 2 x 2; workgroup tile 128 rows x BN columns; MFMA 32x32x16 bf16
-// on 64 x (BN/2) wave tiles.  K advances BK at a time: 16-byte coalesced global loads land in a ring
-// of PF register stages (so PF-1 slabs are in flight while one is computed), go to double-buffered
-// LDS, and are read back as MFMA fragments.  LDS rows are padded by 16 bytes so that fragment reads
-// (16 bytes per lane, 32 consecutive rows) are bank-conflict free.
+// Tiling: a workgroup of WAVES_M x WAVES_N waves owns a BM x BN output tile; each wave a
+// (BM/WAVES_M) x (BN/WAVES_N) sub-tile of 32x32x16 bf16 MFMAs.  K advances BK at a time through a
+// ring of NS LDS stages filled by 16-byte LDS-direct loads (global memory -> LDS without passing
+// through registers), so NS-1 slabs are in flight or landed while one is computed and one barrier
+// per slab suffices.  Inside LDS the 16-byte chunks of each 256-byte line are XOR-swizzled with
+// the line number: the wave-wide loads write 1 KiB contiguously, and the MFMA fragment reads
+// (16 bytes per lane, 32 consecutive rows) spread over all banks.  Every load reads an always-valid
+// address (rows and columns past the matrix are clamped: they only feed outputs that are never
+// stored; chunks that must read as zeros come from a page of zeros), so the K loop is branch-free
+// apart from the switch from base-weight slabs to adapter slabs.
 //
 // MFMA 32x32x16 bf16 operand layout (lane l): A[row l%32][k 8(l/32)..+7], B[k 8(l/32)..+7][col l%32],
 // C[row 8(r/4) + 4(l/32) + r%4][col l%32] for accumulator register r = 0..15.
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 
@@ -29,30 +35,24 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 namespace {
 
-constexpr int kBM = 128;
 constexpr int kKAlign = 64;  // K of every GEMM is a multiple of this
 
-__device__ __forceinline__ uint4 ldg16(const bf16_t *p) { return *(const uint4 *)p; }
-
 // Per-thread description of one 16-byte load of the weight (B) tile, fixed for the whole K loop.
-// Every address the loop forms from it is valid memory (rows and columns past the matrix are
-// clamped to its last row / column: they only feed outputs that are never stored), so that loads
-// are unconditional and many can be in flight; chunks that must read as zeros are masked after
-// the load.
 struct BRow {
     const bf16_t *w;   // weight row + chunk offset: base-K loads are w + k
     const bf16_t *b;   // adapter B of this output column: &B[0][n][0] + chunk offset inside a model
     int kind;          // 0: no adapter columns; 1: adapter range [0, M*r); 2: range [M*r, 2*M*r) (up rows)
 };
 
-template <int BN>
+// LDS B-row b of weight tile tile_n -> weight row.  DUAL: a tile covers BN/2 output columns; inside
+// each wave column of WN LDS rows the first WN/2 are gate rows and the next WN/2 the up rows of the
+// same WN/2 output columns.
+template <int BN, int WN>
 __device__ __forceinline__ BRow b_row(const GemmArgs &g, int tile_n, int b) {
     BRow o;
     if (g.mode == GEMM_DUAL) {
-        // tile covers BN/2 output columns: LDS row b -> wave column b / (BN/2), j = gate/up, nn
-        constexpr int HW = BN / 2;          // rows per wave column
-        int wn = b / HW, j = (b % HW) / (HW / 2), nn = b % (HW / 2);
-        int n = min(tile_n * (BN / 2) + wn * (HW / 2) + nn, g.n_seg[0] - 1);
+        int wn = b / WN, j = (b % WN) / (WN / 2), nn = b % (WN / 2);
+        int n = min(tile_n * (BN / 2) + wn * (WN / 2) + nn, g.n_seg[0] - 1);
         o.w = (j ? g.W[1] : g.W[0]) + (size_t)n * g.K;
         const bf16_t *B = j ? g.B[1] : g.B[0];
         o.kind = (g.T && B) ? 1 + j : 0;
@@ -75,156 +75,253 @@ __device__ __forceinline__ BRow b_row(const GemmArgs &g, int tile_n, int b) {
     return o;
 }
 
-__device__ __forceinline__ uint4 masked(uint4 v, bool ok) {
-    uint32_t m = ok ? 0xffffffffu : 0u;
-    return uint4{v.x & m, v.y & m, v.z & m, v.w & m};
+// 256 bytes of zeros: the source of LDS-direct loads that must read as zeros (adapter columns a
+// row does not have, padding past the last adapter column).
+__device__ uint4 g_zero_page[16];
+
+// 16-byte LDS-direct load: lane i of the wave copies 16 bytes from its own global address g to LDS
+// byte address lds_base + 16 i (lds_base wave-uniform).  The data bypasses the registers and the
+// load stays in flight, counted by vmcnt, until it has been written to LDS.  Written as inline
+// assembly so that the compiler does not tie later LDS reads to it with a full vmcnt(0) wait: the
+// pipeline below waits explicitly.  m0 carries the LDS base; nothing else in these kernels uses m0.
+__device__ __forceinline__ void dma16(const void *g, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(g) : "memory");
 }
 
-template <int BN, int BK, int PF>
-__global__ void __launch_bounds__(256) k_gemm_mfma(GemmArgs g) {
-    constexpr int WN = BN / 2;        // wave tile columns
-    constexpr int TN = WN / 32;       // 32-col MFMA tiles per wave
-    constexpr int CPR = BK / 8;       // 16-byte chunks per tile row
-    constexpr int A_LD = kBM * CPR / 256;  // 16-byte loads per thread for the A tile
-    constexpr int B_LD = BN * CPR / 256;
-    constexpr int kLd = BK + 8;       // LDS row stride in elements
-    static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for 256 threads");
-    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    bf16_t *As = smem;                         // [2][kBM][kLd]
-    bf16_t *Bs = smem + 2 * kBM * kLd;         // [2][BN][kLd]
+// s_waitcnt immediate (gfx9 encoding) for vmcnt <= N and lgkmcnt == 0: all LDS reads of the wave
+// have returned and at most N of its global loads are still in flight.
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }
 
-    // XCD-aware tile order: the 8 XCDs take workgroups round-robin, so consecutive ids on one XCD
-    // walk the row tiles of the same weight tile (weights stay in that XCD's L2).
+template <int N>
+__device__ __forceinline__ void wait_loads() { __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(N)); }
+
+// Byte offset of 16-byte chunk c of tile row `row` inside an operand's LDS stage.  Rows are stored
+// densely (CPR chunks each); inside every 256-byte line (one pass over the 64 banks) the chunk
+// position is XOR-ed with the low bits of the line number, so that the 16-byte fragment reads of
+// 16 consecutive rows, which the LDS serves together, fall into 16 different bank groups.
+template <int CPR>
+__device__ __forceinline__ int swz(int row, int c) {
+    int q = row * CPR + c, line = q >> 4, p = q & 15;
+    return (line << 8) + ((p ^ (line & (CPR - 1))) << 4);
+}
+
+template <int BM, int BN, int BK, int NS, int WAVES_M, int WAVES_N>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
+    constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 MFMA tiles per wave
+    constexpr int CPR = BK / 8;                          // 16-byte chunks per tile row
+    constexpr int RPU = 64 / CPR;                        // tile rows per 1 KiB unit (one wave-wide load)
+    constexpr int A_LD = BM / RPU / NW, B_LD = BN / RPU / NW;  // loads per wave and slab
+    constexpr int NL = A_LD + B_LD;
+    constexpr int kBOff = BM * BK * 2, kStage = (BM + BN) * BK * 2;
+    static_assert(BM % (RPU * NW) == 0 && BN % (RPU * NW) == 0, "tile / wave mismatch");
+    static_assert(TM >= 1 && TN >= 1 && NS >= 2 && NS <= 5 && (NS - 2) * NL < 64, "tile shape");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];  // [NS] stages of { A [BM][BK], B [BN][BK] }
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)smem;
+
+    // XCD-aware tile order.  The 8 XCDs take workgroups round-robin and each runs about 32 of them
+    // at a time (one per CU).  The tile grid is cut into panels of panel_m x panel_n <= run tiles
+    // (run = 32 for a grid that fills the chip, less for small ones so that every XCD gets work);
+    // `run` consecutive workgroups of one XCD work on one panel, so that what they stream through
+    // that XCD's L2 at any moment is panel_m slabs of X and panel_n slabs of W instead of run + 1.
+    // Consecutive panels (on different XCDs at the same time) walk down the rows first, sharing
+    // their weight columns in the memory-side cache.
     const int Mt = g.m_tiles, Nt = g.n_tiles;
-    int bid = blockIdx.x, tile_m, tile_n;
+    int tile_m, tile_n;
     {
-        int grp = bid / (8 * Mt), rem = bid % (8 * Mt);
-        int ncols = min(8, Nt - grp * 8);       // weight tiles in this group of 8
-        tile_n = grp * 8 + rem % ncols;
-        tile_m = rem / ncols;
+        const int bid = blockIdx.x, xcd = bid & 7, s = bid >> 3;
+        const int panel = (s / g.run) * 8 + xcd, within = s % g.run;
+        if (panel >= g.n_panels || within >= g.panel_m * g.panel_n) return;
+        tile_m = (panel % g.panels_m) * g.panel_m + within % g.panel_m;
+        tile_n = (panel / g.panels_m) * g.panel_n + within / g.panel_m;
+        if (tile_m >= Mt || tile_n >= Nt) return;
     }
-    const int kz = blockIdx.y;                  // split-K slice
+    const int kz = blockIdx.y;  // split-K slice
     const int k_begin = kz * g.k_per_split;
     const int k_end = min(g.K_ext, k_begin + g.k_per_split);
     const int nk = (k_end - k_begin + BK - 1) / BK;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int wm = w >> 1, wn = w & 1;
-    const int row0 = tile_m * kBM;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w / WAVES_N, wn = w % WAVES_N;
+    const int row0 = tile_m * BM;
 
-    f32x16 acc[2][TN];
+    f32x16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // This thread's 16-byte loads: row sources fixed for the whole K loop.  Base-K slabs are
-    // pointer + k; the few adapter slabs past K read T (activations side) and the models' B.
+    // This lane's part of every wave-wide load: LDS slot `lane` of a 1 KiB unit is 256-byte line
+    // lane/16, position lane%16, which (un-swizzled) holds chunk kc/8 of unit row ru.  A wave's units
+    // are NW apart (NW even), so the swizzle key of its lines is the same for every unit.  Row
+    // sources are fixed for the whole K loop: base-K slabs read pointer + k, the few adapter slabs
+    // past K read T (activation side) and the models' B (weight side), or the zero page.
+    static_assert(NW % 2 == 0, "swizzle key must not depend on the unit");
+    const int lin = lane >> 4, key = (w * 4 + lin) & (CPR - 1);
+    const int qd = lin * 16 + ((lane & 15) ^ key);
+    const int ru = qd / CPR, kc = (qd % CPR) * 8;
+    const bf16_t *zero = (const bf16_t *)g_zero_page;
     const bf16_t *pa[A_LD], *pt[A_LD];
     BRow br[B_LD];
-    int kca[A_LD], kcb[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-        int e = tid + i * 256, row = min(row0 + e / CPR, g.R - 1);
-        kca[i] = (e % CPR) * 8;
-        pa[i] = g.X + (size_t)row * g.ldx + kca[i];
-        pt[i] = g.T ? g.T + (size_t)row * g.ldt + kca[i] : pa[i];
+        int row = min(row0 + (w + NW * i) * RPU + ru, g.R - 1);  // clamped rows feed outputs that are never stored
+        pa[i] = g.X + (size_t)row * g.ldx + kc;
+        pt[i] = g.T ? g.T + (size_t)row * g.ldt + kc : zero;
     }
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
-        int e = tid + i * 256;
-        kcb[i] = (e % CPR) * 8;
-        br[i] = b_row<BN>(g, tile_n, e / CPR);
-        br[i].w += kcb[i];
+        br[i] = b_row<BN, WN>(g, tile_n, (w + NW * i) * RPU + ru);
+        br[i].w += kc;
     }
     const int K_base = g.K, mr = g.M_models * g.r, lr = 31 - __clz(max(g.r, 1)), ldt = g.T ? g.ldt : 0;
+    const int rmask = g.r - 1;
     const size_t model_stride = (size_t)g.n_seg[0] * g.r;  // elements between consecutive models' B
-    uint4 ra[PF][A_LD], rb[PF][B_LD];
-    auto gload = [&](int kt, uint4 (&qa)[A_LD], uint4 (&qb)[B_LD]) {
+
+    // enqueue the loads of slab kt into ring stage `stage`
+    auto issue = [&](int kt, int stage) {
         const int k0 = k_begin + kt * BK;
+        const uint32_t la = lds0 + stage * kStage + w * 1024;
         if (k0 < K_base) {  // slab inside the base weights (K is a multiple of the slab)
 #pragma unroll
-            for (int i = 0; i < A_LD; ++i) qa[i] = ldg16(pa[i] + k0);
+            for (int i = 0; i < A_LD; ++i) dma16(pa[i] + k0, la + i * (NW * 1024));
 #pragma unroll
-            for (int i = 0; i < B_LD; ++i) qb[i] = ldg16(br[i].w + k0);
+            for (int i = 0; i < B_LD; ++i) dma16(br[i].w + k0, la + kBOff + i * (NW * 1024));
             return;
         }
-        const int k2 = k0 - K_base;  // adapter slab (r is a power of two)
+        const int k2 = k0 - K_base + kc;  // this lane's adapter column (r is a power of two)
 #pragma unroll
-        for (int i = 0; i < A_LD; ++i) {
-            bool ok = k2 + kca[i] < ldt && k0 + kca[i] < k_end;
-            qa[i] = masked(ldg16(ok ? pt[i] + k2 : pa[i]), ok);
-        }
+        for (int i = 0; i < A_LD; ++i) dma16(k2 < ldt ? pt[i] + (k2 - kc) : zero, la + i * (NW * 1024));
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
-            int kk = k2 + kcb[i] - (br[i].kind == 2 ? mr : 0);
-            bool ok = br[i].kind != 0 && kk >= 0 && kk < mr && k0 + kcb[i] < k_end;
-            const bf16_t *p = br[i].b + (size_t)(kk >> lr) * model_stride + (kk & (g.r - 1));
-            qb[i] = masked(ldg16(ok ? p : br[i].w), ok);
-        }
-    };
-    auto sstore = [&](int buf, const uint4 (&qa)[A_LD], const uint4 (&qb)[B_LD]) {
-#pragma unroll
-        for (int i = 0; i < A_LD; ++i) {
-            int e = tid + i * 256, rr = e / CPR, kc = (e % CPR) * 8;
-            *(uint4 *)(As + ((size_t)buf * kBM + rr) * kLd + kc) = qa[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) {
-            int e = tid + i * 256, rr = e / CPR, kc = (e % CPR) * 8;
-            *(uint4 *)(Bs + ((size_t)buf * BN + rr) * kLd + kc) = qb[i];
+            int kk = k2 - (br[i].kind == 2 ? mr : 0);
+            bool ok = br[i].kind != 0 && kk >= 0 && kk < mr;
+            dma16(ok ? br[i].b + (size_t)(kk >> lr) * model_stride + (kk & rmask) : zero, la + kBOff + i * (NW * 1024));
         }
     };
 
-    // slab t lives in register stage t % PF from its load until it is stored to LDS buffer t & 1
+    // Ring of NS stages.  One barrier per slab, placed before the last 16-wide K step of slab kt is
+    // multiplied: by then every wave has read all of slab kt into registers, so after the barrier
+    // (which also follows each wave's wait for its own loads of slab kt+1) slab kt+1 is complete
+    // in LDS and the stage of slab kt can be refilled with slab kt+NS.  The first fragments of slab
+    // kt+1 are fetched right after the barrier and the pending MFMAs of slab kt cover their latency,
+    // the refill's issue and the barrier's wake-up.
+    const int fr = lane & 31, fh = lane >> 5;
+    constexpr int KS = BK / 16;
+    bf16x8 fa[TM], fb[TN];  // fragments of the K step to multiply next
+    auto read_frags = [&](int stage, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+        const char *sA = smem + stage * kStage, *sB = sA + kBOff;
 #pragma unroll
-    for (int p = 0; p < PF; ++p)
-        if (p < nk) gload(p, ra[p], rb[p]);
-    if (nk > 0) sstore(0, ra[0], rb[0]);
-    __syncthreads();
-    const int fr = lane & 31, fk = (lane >> 5) * 8;
-    for (int kt0 = 0; kt0 < nk; kt0 += PF) {
+        for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8 *)(sA + swz<CPR>(wm * WM + i * 32 + fr, 2 * ks + fh));
 #pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int kt = kt0 + p;
-            if (kt < nk) {
-                const int buf = kt & 1;
-                if (kt + PF < nk) gload(kt + PF, ra[p], rb[p]);  // stage p was emptied into LDS one step ago
-                const bf16_t *Ab = As + ((size_t)buf * kBM + wm * 64 + fr) * kLd + fk;
-                const bf16_t *Bb = Bs + ((size_t)buf * BN + wn * WN + fr) * kLd + fk;
+        for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8 *)(sB + swz<CPR>(wn * WN + j * 32 + fr, 2 * ks + fh));
+    };
+    auto mma = [&](const bf16x8 (&af)[TM], const bf16x8 (&bfr)[TN]) {
 #pragma unroll
-                for (int ks = 0; ks < BK / 16; ++ks) {
-                    bf16x8 a0 = *(const bf16x8 *)(Ab + ks * 16);
-                    bf16x8 a1 = *(const bf16x8 *)(Ab + 32 * kLd + ks * 16);
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        bf16x8 b = *(const bf16x8 *)(Bb + (size_t)j * 32 * kLd + ks * 16);
-                        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0][j], 0, 0, 0);
-                        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1][j], 0, 0, 0);
-                    }
-                }
-                if (kt + 1 < nk) sstore(buf ^ 1, ra[(p + 1) % PF], rb[(p + 1) % PF]);
-            }
-            __syncthreads();
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    };
+    auto wait_for_slab = [&](int younger) {  // younger: slabs enqueued after the one waited for
+        if (NS > 4 && younger >= 3) wait_loads<(NS > 4 ? 3 : 0) * NL>();
+        else if (NS > 3 && younger >= 2) wait_loads<(NS > 3 ? 2 : 0) * NL>();
+        else if (younger >= 1) wait_loads<NL>();
+        else wait_loads<0>();
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nk) issue(s, s);
+    wait_for_slab(min(NS - 2, nk - 1));
+    __builtin_amdgcn_s_barrier();
+    if (NS - 1 < nk) issue(NS - 1, NS - 1);
+    read_frags(0, 0, fa, fb);
+    int stage = 0, kt = 0;
+    // Steady state: the slab to enqueue (kt+NS) lies in the base weights, so the section after the
+    // barrier is straight-line code, scheduled by hand: fetch the first fragments of slab kt+1,
+    // then alternate the pending MFMAs of slab kt with the loads of slab kt+NS, so that the matrix
+    // pipe is fed while the wave issues its memory instructions.
+    const int n_steady = min(nk, max(0, (K_base - k_begin) / BK)) - NS;
+    for (; kt < n_steady; ++kt) {
+        bf16x8 ga[TM], gb[TN];
+#pragma unroll
+        for (int ks = 0; ks + 1 < KS; ++ks) {
+            read_frags(stage, ks + 1, ga, gb);
+            mma(fa, fb);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = ga[i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = gb[j];
         }
+        const int next = stage + 1 == NS ? 0 : stage + 1;
+        wait_loads<(NS - 2) * NL>();
+        __builtin_amdgcn_s_barrier();
+        read_frags(next, 0, ga, gb);
+        const int k0 = k_begin + (kt + NS) * BK;
+        const uint32_t la = lds0 + stage * kStage + w * 1024;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < TM * TN; ++t) {
+            acc[t / TN][t % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[t / TN], fb[t % TN], acc[t / TN][t % TN], 0, 0, 0);
+#pragma unroll
+            for (int l = t * NL / (TM * TN); l < (t + 1) * NL / (TM * TN); ++l) {
+                if (l < A_LD) dma16(pa[l] + k0, la + l * (NW * 1024));
+                else dma16(br[l - A_LD].w + k0, la + kBOff + (l - A_LD) * (NW * 1024));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = ga[i];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = gb[j];
+        stage = next;
+    }
+    for (; kt < nk; ++kt) {  // the last slabs: adapter columns to enqueue, or nothing left to enqueue
+        bf16x8 ga[TM], gb[TN];
+#pragma unroll
+        for (int ks = 0; ks + 1 < KS; ++ks) {
+            read_frags(stage, ks + 1, ga, gb);
+            mma(fa, fb);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = ga[i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = gb[j];
+        }
+        const int next = stage + 1 == NS ? 0 : stage + 1;
+        if (kt + 1 < nk) {
+            wait_for_slab(min(NS - 2, nk - 2 - kt));
+            __builtin_amdgcn_s_barrier();
+            if (kt + NS < nk) issue(kt + NS, stage);
+            read_frags(next, 0, ga, gb);
+        }
+        mma(fa, fb);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = ga[i];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = gb[j];
+        stage = next;
     }
 
     // epilogue: accumulator register r of tile (i, j) is row 8(r/4) + 4(lane/32) + r%4, column lane%32
     const int col_l = lane & 31, row_l = (lane >> 5) * 4;
     if (g.mode == GEMM_DUAL) {
-        // wave columns: tile j = 0 gate, j = 1 up (TN == 2), same output column
-        if constexpr (TN == 2) {
-            int n = tile_n * (BN / 2) + wn * (WN / 2) + col_l;
-            if (n < g.n_seg[0]) {
+        // in a wave, MFMA tile j < TN/2 holds gate and tile j + TN/2 up of the same output columns
+        if constexpr (TN % 2 == 0) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < TN / 2; ++j) {
+                int n = tile_n * (BN / 2) + wn * (WN / 2) + j * 32 + col_l;
+                if (n >= g.n_seg[0]) continue;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        int row = row0 + wm * 64 + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
+                        int row = row0 + wm * WM + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
                         if (row < g.R) {
-                            float gt = acc[i][0][r], up = acc[i][1][r];
+                            float gt = acc[i][j][r], up = acc[i][j + TN / 2][r];
                             float hv = gt / (1.f + __expf(-gt)) * up;
                             ((bf16_t *)g.Y)[(size_t)row * g.ldy + n] = f32_to_bf16(hv);
                         }
@@ -241,10 +338,10 @@ __global__ void __launch_bounds__(256) k_gemm_mfma(GemmArgs g) {
         if (n_in >= g.n_seg[seg]) continue;
         int n = col_base + n_in;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                int row = row0 + wm * 64 + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
+                int row = row0 + wm * WM + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
                 if (row >= g.R) continue;
                 float v = acc[i][j][r];
                 if (g.epi == EPI_F32) {
@@ -298,32 +395,74 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(const float *__restrict__
     }
 }
 
-template <int BN, int BK, int PF>
-hipError_t launch_cfg(const GemmArgs &g, hipStream_t st) {
-    size_t shm = (size_t)2 * (kBM + BN) * (BK + 8) * sizeof(bf16_t);
+template <int BM, int BN, int BK, int NS, int WAVES_M, int WAVES_N>
+hipError_t launch_cfg(GemmArgs g, hipStream_t st) {
+    g.m_tiles = (g.R + BM - 1) / BM;
+    g.n_tiles = 0;
+    if (g.mode == GEMM_DUAL) {
+        g.n_tiles = (g.n_seg[0] + BN / 2 - 1) / (BN / 2);
+    } else {
+        for (int s = 0; s < g.nseg; ++s) {
+            g.tiles_seg[s] = (g.n_seg[s] + BN - 1) / BN;
+            g.n_tiles += g.tiles_seg[s];
+        }
+    }
+    g.run = std::max(1, std::min(32, g.m_tiles * g.n_tiles / 8));
+    g.panel_m = std::min({g.m_tiles, 8, g.run});
+    g.panel_n = g.run / g.panel_m;
+    g.panels_m = (g.m_tiles + g.panel_m - 1) / g.panel_m;
+    g.n_panels = g.panels_m * ((g.n_tiles + g.panel_n - 1) / g.panel_n);
+    size_t shm = (size_t)NS * (BM + BN) * BK * sizeof(bf16_t);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_mfma<BN, BK, PF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+        hipError_t e = hipFuncSetAttribute((const void *)k_gemm_mfma<BM, BN, BK, NS, WAVES_M, WAVES_N>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid(g.m_tiles * g.n_tiles, g.splits);
-    hipLaunchKernelGGL((k_gemm_mfma<BN, BK, PF>), grid, dim3(256), shm, st, g);
+    dim3 grid((g.n_panels + 7) / 8 * 8 * g.run, g.splits);
+    hipLaunchKernelGGL((k_gemm_mfma<BM, BN, BK, NS, WAVES_M, WAVES_N>), grid, dim3(64 * WAVES_M * WAVES_N), shm, st, g);
     return hipGetLastError();
 }
 
-// Pipeline shape: K slab width and register prefetch depth.  ICARUS_GEMM_CFG = "bk,pf" overrides
-// the default for experiments.
-int gemm_cfg() {
-    static int cfg = -1;
-    if (cfg < 0) {
-        cfg = 641;
+// Tile shapes (rows x weight rows x K slab, ring stages, waves).  What bounds a tile is the bytes it
+// pulls through the CU's vector memory path per MFMA cycle, 4096 (1/BM + 1/BN): 64 for 128 x 128
+// (the path's peak), 32 for 256 x 256.  Many rows (prefill): 256 x 256.  Few rows (decode): the
+// grid must still fill 256 CUs, so tiles stay 128 wide in N; the fused gate/up GEMM, which cannot
+// split K, takes one row tile that covers all stacked rows (every weight is then fetched by exactly
+// one workgroup); the narrow GEMMs take 128 x 128 tiles with narrow K slabs (two workgroups per CU)
+// and split K.
+enum TileKind { TILE_AUTO = 0, TILE_128, TILE_128_NARROW, TILE_256x128, TILE_384x128, TILE_384x128_W8, TILE_256x256,
+                TILE_KINDS };
+struct TileShape { int bm, bn; };
+constexpr TileShape kTileShape[TILE_KINDS] = {{0, 0}, {128, 128}, {128, 128}, {256, 128}, {384, 128}, {384, 128}, {256, 256}};
+
+// ICARUS_GEMM_CFG = "<tile kind>" forces one tile shape for every GEMM (experiments, tests).
+int forced_tile() {
+    static int t = -1;
+    if (t < 0) {
+        t = 0;
         if (const char *e = getenv("ICARUS_GEMM_CFG")) {
-            int bk = 0, pf = 0;
-            if (sscanf(e, "%d,%d", &bk, &pf) == 2) cfg = bk * 10 + pf;
+            int a = 0;
+            if (sscanf(e, "%d", &a) == 1 && a > 0 && a < TILE_KINDS) t = a;
         }
     }
-    return cfg;
+    return t;
+}
+
+int n_tiles_for(const GemmArgs &g, int bm, int bn) {
+    int m_tiles = (g.R + bm - 1) / bm, n_tiles = 0;
+    if (g.mode == GEMM_DUAL) return m_tiles * ((g.n_seg[0] + bn / 2 - 1) / (bn / 2));
+    for (int s = 0; s < g.nseg; ++s) n_tiles += (g.n_seg[s] + bn - 1) / bn;
+    return m_tiles * n_tiles;
+}
+
+int pick_tile(const GemmArgs &g) {
+    if (int f = forced_tile()) return f;
+    if (g.R >= 1024 && n_tiles_for(g, 256, 256) >= 192) return TILE_256x256;  // enough large tiles for 256 CUs
+    if (g.mode == GEMM_DUAL && g.R > 128 && g.R <= 256) return TILE_256x128;
+    if (g.mode == GEMM_DUAL && g.R > 256 && g.R <= 384) return TILE_384x128_W8;
+    return g.R <= 384 ? TILE_128_NARROW : TILE_128;
 }
 
 }  // namespace
@@ -334,34 +473,25 @@ bool gemm_mfma_supported(const Dims &dm, int K) {
 }
 
 int gemm_mfma_tiles(const GemmArgs &g) {
-    const int BN = 128;
-    int m_tiles = (g.R + kBM - 1) / kBM, n_tiles = 0;
-    if (g.mode == GEMM_DUAL) return m_tiles * ((g.n_seg[0] + BN / 2 - 1) / (BN / 2));
-    for (int s = 0; s < g.nseg; ++s) n_tiles += (g.n_seg[s] + BN - 1) / BN;
-    return m_tiles * n_tiles;
+    int t = pick_tile(g);
+    return n_tiles_for(g, kTileShape[t].bm, kTileShape[t].bn);
 }
 
 hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st) {
     if (g.R <= 0) return hipSuccess;
-    const int BN = 128;
-    g.m_tiles = (g.R + kBM - 1) / kBM;
-    g.n_tiles = 0;
-    if (g.mode == GEMM_DUAL) {
-        g.n_tiles = (g.n_seg[0] + BN / 2 - 1) / (BN / 2);
+    if (g.mode == GEMM_DUAL)
         g.K_ext = g.K + (g.T ? 2 * g.M_models * g.r : 0);
-    } else {
-        for (int s = 0; s < g.nseg; ++s) {
-            g.tiles_seg[s] = (g.n_seg[s] + BN - 1) / BN;
-            g.n_tiles += g.tiles_seg[s];
-        }
+    else
         g.K_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
-    }
     if (g.splits < 1) g.splits = 1;
     g.k_per_split = ((g.K_ext + g.splits - 1) / g.splits + kKAlign - 1) / kKAlign * kKAlign;
-    switch (gemm_cfg()) {
-    case 642: return launch_cfg<128, 64, 2>(g, st);
-    case 322: return launch_cfg<128, 32, 2>(g, st);
-    default: return launch_cfg<128, 64, 1>(g, st);
+    switch (pick_tile(g)) {
+    case TILE_128_NARROW: return launch_cfg<128, 128, 32, 4, 2, 2>(g, st);
+    case TILE_256x128: return launch_cfg<256, 128, 32, 4, 2, 2>(g, st);
+    case TILE_384x128: return launch_cfg<384, 128, 32, 4, 4, 1>(g, st);
+    case TILE_384x128_W8: return launch_cfg<384, 128, 32, 4, 4, 2>(g, st);
+    case TILE_256x256: return launch_cfg<256, 256, 32, 4, 2, 4>(g, st);
+    default: return launch_cfg<128, 128, 64, 4, 2, 2>(g, st);
     }
 }
 

@@ -107,7 +107,7 @@ constexpr int kAttnTargetWgs = 1280;  // decode attention: aim for about this ma
 constexpr int kAttnMaxChunk = 16384;  // tokens per attention chunk, at most (block ids of a chunk sit in LDS)
 constexpr int kAttnGMax = 80;         // largest stacked query group the MFMA attention covers
 constexpr int kShrinkMaxSplits = 16;  // split-K slices of the LoRA shrink GEMM
-constexpr int kGemmMaxSplits = 16;    // split-K slices of a narrow ICaRusLinear GEMM
+constexpr int kGemmMaxSplits = 12;    // split-K slices of a narrow ICaRusLinear GEMM
 
 // Upper bounds used for sizing: chunks (= partial slots) of a call and its largest stacked group.
 size_t attn_max_items(const icarus_ctx *ctx, size_t seqs, size_t max_ctx) {
@@ -148,7 +148,8 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t max_c
         w.lora_part = take((size_t)kShrinkMaxSplits * rows * cols * 4);
         w.lora_t = take(rows * cols * 2);
     }
-    w.gemm_part_bytes = (size_t)400 * 128 * 128 * 4;  // split-K partials: splits * tiles <= 384 tiles of 128 x 128
+    // split-K partials of a narrow GEMM: only calls of a few hundred rows are split
+    w.gemm_part_bytes = (size_t)kGemmMaxSplits * std::min<size_t>(rows, 512) * std::max(qd + 2 * kvd, (size_t)c.d_model) * 4;
     w.gemm_part = take(w.gemm_part_bytes);
     w.total = off;
     return w;
@@ -400,7 +401,7 @@ icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, 
     int k_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
     int splits = 1;
     if (tiles < 160) splits = std::max(1, std::min({kGemmMaxSplits, 384 / tiles, k_ext / 256}));
-    if (splits > 1 && (size_t)splits * g.R * n_total * 4 > L.gemm_part_bytes) splits = 1;
+    splits = (int)std::max<size_t>(1, std::min<size_t>(splits, L.gemm_part_bytes / ((size_t)g.R * n_total * 4)));
     if (splits == 1) {
         g.splits = 1;
         PHASE(ctx, st, phase, launch_gemm_mfma(g, st));

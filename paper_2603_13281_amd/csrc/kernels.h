@@ -84,6 +84,7 @@ struct GemmArgs {
     int splits;                                  // split-K slices (EPI_F32 without adapters only)
     // filled by the launcher
     int tiles_seg[3]; int m_tiles, n_tiles, K_ext, k_per_split;
+    int run, panel_m, panel_n, panels_m, n_panels;  // tile order: panels of panel_m x panel_n <= run tiles
 };
 bool gemm_mfma_supported(const Dims &dm, int K);
 hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st);
