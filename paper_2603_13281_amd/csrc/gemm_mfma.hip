@@ -354,24 +354,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
     }
 }
 
-// T[row, c] = bf16(scale * sum_z P[z][row][c]) if c / r == model(row) else 0   (shrink epilogue)
-__global__ void __launch_bounds__(256) k_lora_mask(const float *__restrict__ P, int splits, int R, int C, int r,
-                                                   const int32_t *__restrict__ row_model, float scale,
-                                                   bf16_t *__restrict__ T, int n_targets) {
-    // C = n_targets * M * r columns; target t occupies columns [t*M*r, (t+1)*M*r)
-    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)R * C) return;
-    int row = (int)(idx / C), c = (int)(idx % C);
-    int per = C / n_targets;
-    int j = (c % per) / r;
-    float v = 0.f;
-    if (row_model[row] == j) {
-        for (int z = 0; z < splits; ++z) v += P[((size_t)z * R + row) * C + c];
-        v *= scale;
-    }
-    T[idx] = f32_to_bf16(v);
-}
-
 // Second pass of a split-K GEMM: sum the fp32 partials P[z][row][n] and apply the epilogue.
 __global__ void __launch_bounds__(256) k_splitk_reduce(const float *__restrict__ P, int splits, int R, int N, int epi,
                                                        void *__restrict__ Y, int ldy, const bf16_t *__restrict__ resid, int ldr) {
@@ -501,15 +483,6 @@ hipError_t launch_splitk_reduce(const float *P, int splits, int R, int N, int ep
     if (!quads) return hipSuccess;
     hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, P, splits, R, N, epi, Y, ldy,
                        (const bf16_t *)resid, ldr);
-    return hipGetLastError();
-}
-
-hipError_t launch_lora_mask(const float *P, int splits, int R, int C, int r, const int32_t *row_model, float scale,
-                            void *T, int n_targets, hipStream_t st) {
-    size_t total = (size_t)R * C;
-    if (!total) return hipSuccess;
-    hipLaunchKernelGGL(k_lora_mask, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, P, splits, R, C, r, row_model, scale,
-                       (bf16_t *)T, n_targets);
     return hipGetLastError();
 }
 

@@ -99,14 +99,13 @@ bool has_lora(const icarus_ctx *ctx, int p) {
 
 // ---- workspace layout ---------------------------------------------------------------
 struct WsLayout {
-    size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, part_o, part_ml, lora_part, lora_t, total;
+    size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, part_o, part_ml, lora_t, total;
     size_t meta_ints, max_items, gemm_part, gemm_part_bytes;
 };
 
 constexpr int kAttnTargetWgs = 1280;  // decode attention: aim for about this many workgroups (5 per CU)
 constexpr int kAttnMaxChunk = 16384;  // tokens per attention chunk, at most (block ids of a chunk sit in LDS)
 constexpr int kAttnGMax = 80;         // largest stacked query group the MFMA attention covers
-constexpr int kShrinkMaxSplits = 16;  // split-K slices of the LoRA shrink GEMM
 constexpr int kGemmMaxSplits = 12;    // split-K slices of a narrow ICaRusLinear GEMM
 
 // Upper bounds used for sizing: chunks (= partial slots) of a call and its largest stacked group.
@@ -143,11 +142,7 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t max_c
     w.f32a = take(rows * std::max<size_t>(c.d_ffn, c.d_model) * 4);
     w.f32b = take(rows * c.d_ffn * 4);
     w.t = take(rows * std::max(1, c.lora_rank) * 4 * 2);
-    {
-        size_t cols = (size_t)2 * std::max(1, c.n_models) * std::max(1, c.lora_rank);  // gate + up share a shrink
-        w.lora_part = take((size_t)kShrinkMaxSplits * rows * cols * 4);
-        w.lora_t = take(rows * cols * 2);
-    }
+    w.lora_t = take(rows * 2 * std::max(1, c.n_models) * std::max(1, c.lora_rank) * 2);  // gate + up share a shrink
     // split-K partials of a narrow GEMM: only calls of a few hundred rows are split
     w.gemm_part_bytes = (size_t)kGemmMaxSplits * std::min<size_t>(rows, 512) * std::max(qd + 2 * kvd, (size_t)c.d_model) * 4;
     w.gemm_part = take(w.gemm_part_bytes);
@@ -367,28 +362,9 @@ icarus_status run_decode_attention(icarus_ctx *ctx, char *ws, const WsLayout &L,
 // ---- the layer on matrix cores (bf16 storage) -----------------------------------------
 bool layer_mfma_supported(const icarus_ctx *ctx) {
     const icarus_layer_config &c = ctx->cfg;
+    bool shrink_ok = c.n_models == 0 || c.lora_rank == 0 || row_shrink_supported(c.lora_rank, 2);
     return ctx->mode == 0 && gemm_mfma_supported(ctx->dm, c.d_model) && gemm_mfma_supported(ctx->dm, c.n_q_heads * c.head_dim) &&
-           gemm_mfma_supported(ctx->dm, c.d_ffn);
-}
-
-// Masked shrink T = s * mask(X A^T) for the adapters of projections p0 (and p1) that share the
-// input X [R, K]: a split-K GEMM into fp32 partials, then reduce + mask + scale to bf16.
-icarus_status run_shrink(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, int R, const void *X, int K, int p0,
-                         int p1, hipStream_t st) {
-    const icarus_layer_config &c = ctx->cfg;
-    int mr = c.n_models * c.lora_rank, nt = p1 >= 0 ? 2 : 1, C = nt * mr;
-    GemmArgs g{};
-    g.X = (const bf16_raw *)X; g.ldx = K; g.R = R; g.K = K;
-    g.W[0] = (const bf16_raw *)ctx->lora.A[p0]; g.n_seg[0] = mr; g.nseg = nt;
-    if (p1 >= 0) { g.W[1] = (const bf16_raw *)ctx->lora.A[p1]; g.n_seg[1] = mr; }
-    g.mode = GEMM_PLAIN; g.epi = EPI_F32;
-    g.Y = ws + L.lora_part; g.ldy = C;
-    int m_tiles = (R + 127) / 128, n_tiles = nt * ((mr + 127) / 128);
-    g.splits = std::max(1, std::min({kShrinkMaxSplits, K / 64, 256 / (m_tiles * n_tiles)}));
-    PHASE(ctx, st, ICARUS_PH_LORA, launch_gemm_mfma(g, st));
-    PHASE(ctx, st, ICARUS_PH_LORA, launch_lora_mask((const float *)(ws + L.lora_part), g.splits, R, C, c.lora_rank, rm.row_model,
-                                                    ctx->dm.lora_scale, ws + L.lora_t, nt, st));
-    return ICARUS_OK;
+           gemm_mfma_supported(ctx->dm, c.d_ffn) && shrink_ok;
 }
 
 // One plain ICaRusLinear GEMM.  When its grid would leave most of the chip idle (few rows and a
@@ -429,7 +405,11 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
     auto lo = [&](int p) { return use_lora && has_lora(ctx, p); };
     auto Bw = [&](int p) { return (const bf16_raw *)ctx->lora.B[p]; };
 
-    PHASE(ctx, st, ICARUS_PH_NORM, launch_rmsnorm(dm, x_in, ctx->base.norm_attn, xn, R, d, st));
+    auto Aw = [&](int p) { return ctx->lora.A[p]; };
+    const bool lq = !kv_only && lo(ICARUS_PROJ_Q);
+    // RMSNorm, with the shrink of the Q adapters on the normalised rows
+    PHASE(ctx, st, ICARUS_PH_NORM, launch_norm_shrink(dm, x_in, ctx->base.norm_attn, xn, R, d, lq ? Aw(ICARUS_PROJ_Q) : nullptr, nullptr,
+                                                      rm.row_model, T, nullptr, 0, st));
     {   // Q (ICaRusLinear) and the encoder's K, V in one GEMM over [W_q; W_k; W_v]
         GemmArgs g{};
         g.X = xn; g.ldx = d; g.R = R; g.K = d;
@@ -438,10 +418,7 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
             g.W[0] = W(ICARUS_PROJ_K); g.n_seg[0] = kvd; g.W[1] = W(ICARUS_PROJ_V); g.n_seg[1] = kvd; g.nseg = 2;
             g.Y = qkv + qd; g.ldy = ldq;
         } else {
-            if (lo(ICARUS_PROJ_Q)) {
-                LORA_TRY(run_shrink(ctx, ws, L, rm, R, xn, d, ICARUS_PROJ_Q, -1, st));
-                g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_Q);
-            }
+            if (lq) { g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_Q); }
             g.W[0] = W(ICARUS_PROJ_Q); g.n_seg[0] = qd; g.W[1] = W(ICARUS_PROJ_K); g.n_seg[1] = kvd;
             g.W[2] = W(ICARUS_PROJ_V); g.n_seg[2] = kvd; g.nseg = 3;
             g.Y = qkv; g.ldy = ldq;
@@ -458,25 +435,22 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
         g.W[0] = W(ICARUS_PROJ_O); g.n_seg[0] = d; g.nseg = 1;
         g.mode = GEMM_PLAIN; g.epi = EPI_BF16_RESID; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
         if (lo(ICARUS_PROJ_O)) {
-            LORA_TRY(run_shrink(ctx, ws, L, rm, R, attn, qd, ICARUS_PROJ_O, -1, st));
+            PHASE(ctx, st, ICARUS_PH_LORA, launch_row_shrink(dm, attn, qd, R, qd, Aw(ICARUS_PROJ_O), rm.row_model, T, st));
             g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_O);
         }
         g.Y = z; g.ldy = d; g.resid = (const bf16_raw *)x_in; g.ldr = d;
         LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_O, g, st));
     }
-    PHASE(ctx, st, ICARUS_PH_NORM, launch_rmsnorm(dm, z, ctx->base.norm_ffn, xn, R, d, st));
+    const bool lg = lo(ICARUS_PROJ_GATE), lu = lo(ICARUS_PROJ_UP);
+    if (lg != lu) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "adapters on only one of gate/up need the generic kernels (set kernel mode 1)");
+    PHASE(ctx, st, ICARUS_PH_NORM, launch_norm_shrink(dm, z, ctx->base.norm_ffn, xn, R, d, lg ? Aw(ICARUS_PROJ_GATE) : nullptr,
+                                                      lg ? Aw(ICARUS_PROJ_UP) : nullptr, rm.row_model, T, nullptr, 0, st));
     {   // gate and up (ICaRusLinear x 2) with the SwiGLU product in the epilogue
         GemmArgs g{};
         g.X = xn; g.ldx = d; g.R = R; g.K = d;
         g.W[0] = W(ICARUS_PROJ_GATE); g.W[1] = W(ICARUS_PROJ_UP); g.n_seg[0] = F; g.nseg = 1;
         g.mode = GEMM_DUAL; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
-        bool lg = lo(ICARUS_PROJ_GATE), lu = lo(ICARUS_PROJ_UP);
-        if (lg && lu) {
-            LORA_TRY(run_shrink(ctx, ws, L, rm, R, xn, d, ICARUS_PROJ_GATE, ICARUS_PROJ_UP, st));
-            g.T = T; g.ldt = 2 * mr; g.B[0] = Bw(ICARUS_PROJ_GATE); g.B[1] = Bw(ICARUS_PROJ_UP);
-        } else if (lg || lu) {
-            return fail(ctx, ICARUS_ERR_UNSUPPORTED, "adapters on only one of gate/up need the generic kernels (set kernel mode 1)");
-        }
+        if (lg) { g.T = T; g.ldt = 2 * mr; g.B[0] = Bw(ICARUS_PROJ_GATE); g.B[1] = Bw(ICARUS_PROJ_UP); }
         g.Y = h; g.ldy = F;
         PHASE(ctx, st, ICARUS_PH_GEMM_GATEUP, launch_gemm_mfma(g, st));
     }
@@ -486,7 +460,7 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
         g.W[0] = W(ICARUS_PROJ_DOWN); g.n_seg[0] = d; g.nseg = 1;
         g.mode = GEMM_PLAIN; g.epi = EPI_BF16_RESID; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
         if (lo(ICARUS_PROJ_DOWN)) {
-            LORA_TRY(run_shrink(ctx, ws, L, rm, R, h, F, ICARUS_PROJ_DOWN, -1, st));
+            PHASE(ctx, st, ICARUS_PH_LORA, launch_row_shrink(dm, h, F, R, F, Aw(ICARUS_PROJ_DOWN), rm.row_model, T, st));
             g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_DOWN);
         }
         g.Y = x_out; g.ldy = d; g.resid = z; g.ldr = d;

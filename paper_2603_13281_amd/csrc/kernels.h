@@ -92,10 +92,17 @@ int gemm_mfma_tiles(const GemmArgs &g);  // workgroups of one K slice
 // Sum split-K partials P[splits][R][N] (fp32) and apply the epilogue `epi` into Y.
 hipError_t launch_splitk_reduce(const float *P, int splits, int R, int N, int epi, void *Y, int ldy, const void *resid,
                                 int ldr, hipStream_t st);
-// T[row, c] = bf16(scale * sum_z P[z][row][c]) where column c belongs to the row's model, else 0;
-// C = n_targets * M * r columns.
-hipError_t launch_lora_mask(const float *P, int splits, int R, int C, int r, const int32_t *row_model, float scale,
-                            void *T, int n_targets, hipStream_t st);
+// Row-wise kernels (bf16 storage).  T [R, targets*M*r] (bf16) is the masked LoRA shrink the GEMM reads
+// as extra K columns: T[row, t*M*r + j*r + i] = lora_scale * (A_t[j] x_row)_i for j = row_model[row], zero
+// in every other column (encoder rows: all zero).  A: [M][r][K].
+bool row_shrink_supported(int r, int targets);
+// y = rmsnorm(x) * wn for R rows of K, and (A0 != null) the shrink of y for one or two targets that
+// share y; also sets zero[0..n_zero) = 0.
+hipError_t launch_norm_shrink(const Dims &dm, const void *x, const void *wn, void *y, int R, int K, const void *A0, const void *A1,
+                              const int32_t *row_model, void *T, int *zero, int n_zero, hipStream_t st);
+// the shrink alone, of x [R, K] (row stride ldx)
+hipError_t launch_row_shrink(const Dims &dm, const void *x, int ldx, int R, int K, const void *A0, const int32_t *row_model, void *T,
+                             hipStream_t st);
 
 bool attn_decode_mfma_supported(const Dims &dm, int g_max);
 // part_o: fp32 [slots, Hkv, g_max, D]; part_ml: fp32 [slots, Hkv, g_max, 2] (max in log2 units, sum)
