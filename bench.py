@@ -84,57 +84,21 @@ def run_steps(wl, n, first_step, x_out):
                              wl.x[st % len(wl.x)], x_out=x_out)
 
 
-def cpu_baseline(wl, step, x_dev_out, budget_seqs=2):
-    """Oracle on a seeded sample of sequences (all their rows) of the same step: time + parity."""
-    import numpy as np
-    import torch
-    import oracle
-    from helpers import assert_close, fill_pool
-    from paper_2603_13281_amd import workloads
+def cpu_baseline(wl, step, x_dev_out, prefixes):
+    """Oracle on a seeded sample of sequences (all their rows) of the same step: time + parity.
+    `prefixes`: K/V of the sampled sequences as cached before the step (sampled.snapshot_prefixes)."""
+    import sampled
 
     sh, b = wl.shape, wl.batch
-    rng = np.random.default_rng(12345)
-    order = rng.permutation(b.S)
-    # prefer a sample of moderate cost: sequences in seeded random order until ~budget reached
-    sample = [int(s) for s in order[:budget_seqs]]
     ctx = wl.ctx_lens(step)
-    rows = np.flatnonzero(np.isin(b.row_seq, sample))
-    # compact pool for the sampled sequences
-    Bk = sh.block_size
-    need = [(int(ctx[s]) + 1 + Bk - 1) // Bk for s in sample]
-    nb = sum(need)
-    cfg = oracle.LayerConfig(d_model=sh.d_model, n_q_heads=sh.n_q_heads, n_kv_heads=sh.n_kv_heads, head_dim=sh.head_dim,
-                             d_ffn=sh.d_ffn, block_size=Bk, num_blocks=nb, n_models=sh.n_models, lora_rank=sh.lora_rank,
-                             lora_target_mask=sh.lora_target_mask, qk_norm=sh.qk_norm, bf16=sh.bf16,
-                             rope_theta=sh.rope_theta, rms_eps=sh.rms_eps, lora_scale=sh.lora_scale)
-    orc = oracle.Oracle(cfg, wl.base, wl.lora)
-    pool = orc.new_pool()
-    bt = np.zeros((len(sample), max(need)), dtype=np.int32)
-    k = 0
-    row_seq, row_model, xs = [], [], []
-    x_host = wl.x_host[step % len(wl.x_host)]
-    for i, s in enumerate(sample):
-        bt[i, :need[i]] = np.arange(k, k + need[i])
-        k += need[i]
-        K, V = workloads.sequence_kv_to_host(wl, s, int(ctx[s]))
-        fill_pool(pool, bt[i], K, V)
-        for r in np.flatnonzero(b.row_seq == s):
-            row_seq.append(i)
-            row_model.append(int(b.row_model[r]))
-            xs.append(x_host[r])
-    xs = np.stack(xs)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    t0 = time.perf_counter()
-    want, _ = orc.decode_step(pool, bt, ctx[sample], np.int32(row_seq), np.int32(row_model), xs)
-    dt = time.perf_counter() - t0
-    got = x_dev_out[torch.from_numpy(np.concatenate([np.flatnonzero(b.row_seq == s) for s in sample])).to(x_dev_out.device)]
-    got = got.to(torch.float32).cpu().numpy()
-    assert_close(got, want, 2e-2 if sh.bf16 else 1e-4, "bench sample vs oracle")
-    n_dec = int(sum(1 for m in row_model if m >= 0))
+    tol = 2e-2 if sh.bf16 else 1e-4
+    info = sampled.decode_sample_check(sh, wl.base, wl.lora, prefixes, ctx, b.row_seq, b.row_model,
+                                       wl.x_host[step % len(wl.x_host)], x_dev_out, tol, "bench sample vs oracle")
+    dt, n_dec = info["seconds"], info["decoder_rows"]
     return {"value": n_dec / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"sequences {sample} of the workload at step {step}: {len(row_seq)} rows ({n_dec} decoder rows), "
-                      f"{int(sum(ctx[s] + 1 for s in sample))} cached tokens, {dt:.2f} s; GPU output of these rows "
-                      f"matches the oracle within 2e-2",
+            "sample": f"sequences {info['sample']} of the workload at step {step}: {info['rows']} rows ({n_dec} decoder rows), "
+                      f"{info['cached_tokens']} cached tokens, {dt:.2f} s; GPU output of these rows matches the oracle within {tol:g}",
             "seconds": dt}
 
 
@@ -142,8 +106,7 @@ def main_prefill(args):
     """Config 4: one step = icarus_prefill_kv of every sequence's chunk over its cached prefix."""
     import numpy as np
     import torch
-    import oracle
-    from helpers import assert_close, fill_pool
+    import sampled
     from paper_2603_13281_amd import workloads
 
     K, W = min(args.steps, 20), min(args.warmup, 3)
@@ -157,28 +120,14 @@ def main_prefill(args):
     base = None
     if not args.no_cpu_baseline:
         s0, T, L = 0, int(wl.chunk_lens[0]), int(pre[0])
-        Kp, Vp = workloads.sequence_kv_to_host(wl, s0, L)          # prefix as cached before the call
+        prefix = sampled.kv_to_host(sh, wl.pool, wl.batch.block_tables[s0], L)   # prefix as cached before the call
     run()
     torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        Bk = sh.block_size
-        nb = (L + T + Bk - 1) // Bk
-        cfg = oracle.LayerConfig(d_model=sh.d_model, n_q_heads=sh.n_q_heads, n_kv_heads=sh.n_kv_heads, head_dim=sh.head_dim,
-                                 d_ffn=sh.d_ffn, block_size=Bk, num_blocks=nb, qk_norm=sh.qk_norm, bf16=sh.bf16,
-                                 rope_theta=sh.rope_theta, rms_eps=sh.rms_eps, lora_scale=sh.lora_scale)
-        orc = oracle.Oracle(cfg, wl.base, None)
-        pool = orc.new_pool()
-        bt = np.arange(nb, dtype=np.int32)[None]
-        fill_pool(pool, bt[0], Kp, Vp)
-        sel = np.zeros(T, dtype=np.uint8)
         pick = sorted(set([0, T - 1] + [int(v) for v in np.random.default_rng(7).choice(T, size=min(8, T), replace=False)]))
-        sel[pick] = 1
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        t0 = time.perf_counter()
-        want, _ = orc.prefill(pool, bt, [L], [T], wl.x_host[:T], select=sel)
-        dt = time.perf_counter() - t0
-        got = x_out[:T].to(torch.float32).cpu().numpy()
-        assert_close(got[pick], want[pick], 2e-2, "bench prefill sample vs oracle")
+        dt = sampled.prefill_sample_check(sh, wl.base, prefix, L, T, wl.x_host[:T], x_out[:T], pick, 2e-2,
+                                          "bench prefill sample vs oracle")["seconds"]
         base = {"value": len(pick) / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
                 "sample": f"sequence 0: K/V of all {T} chunk tokens and the full layer for tokens {pick} over its {L}-token "
                           f"prefix, {dt:.2f} s; GPU rows match the oracle within 2e-2", "seconds": dt}
@@ -222,6 +171,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c4", "c4-small"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-private-kv-baseline", action="store_true",
+                    help="skip the conventional per-model-KV run of the same traffic (same kernels, M private caches)")
     ap.add_argument("--kernel-mode", type=int, default=0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB (for scaling rocprofv3 traffic counters)")
@@ -260,8 +211,12 @@ def main():
     run_steps(wl, 1, 0, x_out)
     torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        nseq = {"c2": 1, "c3": 2, "c5": 1, "c3-small": 4}[args.workload]
-        base = cpu_baseline(wl, 0, x_out, nseq)
+        import sampled
+        nseq = {"c2": 1, "c3": 32, "c5": 4, "c3-small": 8}[args.workload]
+        sample = [int(s) for s in np.random.default_rng(12345).permutation(wl.batch.S)[:nseq]]
+        # positions 0..L_s-1 of the cache are what the step read; the step itself appended position L_s
+        prefixes = sampled.snapshot_prefixes(wl.shape, wl.pool, wl.batch.block_tables, wl.ctx_lens(0), sample)
+        base = cpu_baseline(wl, 0, x_out, prefixes)
         log(f"[bench] cpu baseline: {base['value']:.2f} tok/s on {base['cores']} threads; sample parity ok")
 
     # warmup, then EXACTLY K timed steps
@@ -309,6 +264,31 @@ def main():
                 "kernel": dominant}
     attn_gbps = model["attn"]["bytes"] / (per_step_ms["attn"] * 1e-3) / 1e9 if "attn" in per_step_ms else None
 
+    # the conventional alternative on the same GPU and kernels: a private KV cache per (sequence, model)
+    private = None
+    if not args.no_private_kv_baseline:
+        kb = min(K, 20)
+        pw = workloads.build_private_kv_baseline(wl, dev)
+        py = torch.empty_like(pw.x[0])
+        run_steps(pw, 3, 0, py)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(pw, kb, 3, py)
+        torch.cuda.synchronize()
+        pdt = (time.perf_counter() - t0) / kb
+        pw.layer.timing_enable(True)
+        run_steps(pw, kb, 3, py)
+        torch.cuda.synchronize()
+        pph = pw.layer.timing_read()
+        p_attn = pph["attn"][0] / kb if "attn" in pph else None
+        private = {"ms_per_step": pdt * 1e3, "tokens_per_s": pw.batch.R / pdt, "rows": pw.batch.R,
+                   "kv_bytes_per_step": pw.kv_bytes(3 + kb // 2), "attn_ms": p_attn,
+                   "pool_GiB": pw.pool.numel() * pw.pool.element_size() / 2**30,
+                   "shared_kv_speedup": pdt * 1e3 / ms_per_step,
+                   "note": "same kernels; each decoder row is its own sequence with its own cache, no encoder row, no adapter deltas"}
+        log(f"[bench] per-model-KV baseline: {pdt * 1e3:.3f} ms/step ({private['pool_GiB']:.1f} GiB of cache) vs shared {ms_per_step:.3f}")
+        del pw, py
+
     out = {
         "metric": METRIC, "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -318,6 +298,7 @@ def main():
         "attn_hbm_GBps": attn_gbps,
         "roofline": roof,
         "cpu_baseline": base,
+        "per_model_kv_baseline": private,
         "phases": phases,
     }
     print(json.dumps(out))

@@ -100,6 +100,33 @@ def build_decode_workload(name: str, device="cuda:0", headroom: int = 128, seed:
     return DecodeWorkload(name, desc, shape, batch, base, lora, layer, pool, bt, xs, xs_host, headroom)
 
 
+def build_private_kv_baseline(wl: DecodeWorkload, device="cuda:0", seed: int = 0, n_x: int = 4) -> DecodeWorkload:
+    """The same traffic served the conventional way, on the same kernels: every active (sequence, model)
+    pair keeps a private KV cache (what per-model K/V weights force), so each of the R_d decoder rows is
+    a sequence of its own that appends its own K/V and attends with a group of g query heads; there is
+    no encoder row.  Adapter deltas are left out (they would only add time to this baseline)."""
+    shape, b = wl.shape, wl.batch
+    m = np.bincount(b.row_seq[b.row_model >= 0], minlength=b.S)
+    lens = np.repeat(b.ctx_lens, m).astype(np.int32)
+    batch = synth.make_batch(shape, lens, np.zeros(len(lens), dtype=np.int32), seed=seed + 1, headroom=wl.headroom)
+    cfg = layer_config(shape, batch.num_blocks, int(lens.max()) + wl.headroom + 1)
+    cfg.n_models, cfg.lora_rank, cfg.lora_target_mask = 0, 0, 0
+    dbase = {k: upload(v, shape.bf16, device) for k, v in wl.base.items()}
+    layer = binding.IcarusLayer(cfg, dbase, None)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(3000 + seed)
+    pool = torch.empty(cfg.pool_shape(), dtype=cfg.torch_dtype, device=device)
+    step_blocks = max(1, (1 << 28) // (pool[0].numel()))
+    for b0 in range(0, batch.num_blocks, step_blocks):
+        sl = pool[b0:b0 + step_blocks]
+        sl.copy_(torch.randn(sl.shape, generator=gen, device=device, dtype=torch.float32))
+    bt = torch.from_numpy(batch.block_tables).to(device)
+    xs_host = [synth.make_hidden(shape, batch.R, seed=seed, tag=40 + i) for i in range(n_x)]
+    xs = [upload(x, shape.bf16, device) for x in xs_host]
+    return DecodeWorkload(wl.name + "-private-kv", "per-model KV baseline of " + wl.description, shape, batch, wl.base, None,
+                          layer, pool, bt, xs, xs_host, wl.headroom)
+
+
 def sequence_kv_to_host(wl: DecodeWorkload, s: int, n_tokens: int):
     """Copy sequence s's first n_tokens cached K, V from the device pool: float32 [n, Hkv, D] each."""
     sh = wl.shape

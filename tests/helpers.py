@@ -18,10 +18,10 @@ def fill_pool(pool: np.ndarray, bt_row: np.ndarray, K: np.ndarray, V: np.ndarray
     """Place K, V [n, Hkv, D] at logical positions 0..n-1 of one sequence.
     pool: oracle layout [num_blocks, 2, Hkv, Bk, D]."""
     Bk = pool.shape[3]
-    for t in range(K.shape[0]):
-        b, o = int(bt_row[t // Bk]), t % Bk
-        pool[b, 0, :, o, :] = K[t]
-        pool[b, 1, :, o, :] = V[t]
+    t = np.arange(K.shape[0])
+    b, o = np.asarray(bt_row)[t // Bk].astype(np.int64), t % Bk
+    pool[b, 0, :, o, :] = K          # advanced indices (b, o) first: [n, Hkv, D]
+    pool[b, 1, :, o, :] = V
 
 
 def read_pool(pool: np.ndarray, bt_row: np.ndarray, n: int):
