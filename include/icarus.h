@@ -187,6 +187,12 @@ icarus_status icarus_timing_read(icarus_ctx *ctx, double *ms /*host*/, int32_t *
  * bytes, against which the profiler's HBM traffic counters are calibrated. */
 icarus_status icarus_bench_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/* Register-resident matrix-core loop (kernel k_bench_mfma): `waves` wavefronts (a multiple of 4) each issue
+ * `iters` rounds of 8 independent 32x32x16 bf16 MFMAs on operands that never leave the registers, then write
+ * one float each to out (device, `waves` * 64 floats).  2 * 32*32*16 * 8 * iters * waves flops in all.  For
+ * measurements only: the bf16 MFMA rate this GPU sustains, beside the published peak. */
+icarus_status icarus_bench_mfma(float *out, int32_t waves, int32_t iters, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

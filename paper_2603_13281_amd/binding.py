@@ -25,7 +25,7 @@ STATUS = {0: "OK", 1: "INVALID_ARG", 2: "SHAPE", 3: "ALIGNMENT", 4: "MODEL_ID", 
 
 EXPORTS = ("icarus_create", "icarus_destroy", "icarus_last_error", "icarus_workspace_bytes",
            "icarus_validate_decode", "icarus_prefill_kv", "icarus_decode_step", "icarus_attn_shared_kv",
-           "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read", "icarus_bench_copy")
+           "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read", "icarus_bench_copy", "icarus_bench_mfma")
 
 PHASES = ("norm", "lora", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gateup", "gemm_down",
           "elementwise")
@@ -84,6 +84,8 @@ def _load():
     lib.icarus_timing_read.argtypes = [vp, vp, vp]
     lib.icarus_bench_copy.restype = C.c_int
     lib.icarus_bench_copy.argtypes = [vp, vp, sz, vp]
+    lib.icarus_bench_mfma.restype = C.c_int
+    lib.icarus_bench_mfma.argtypes = [vp, C.c_int32, C.c_int32, vp]
     return lib
 
 
@@ -151,6 +153,22 @@ def bench_copy(src: torch.Tensor, dst: torch.Tensor):
     rc = _lib.icarus_bench_copy(_ptr(src), _ptr(dst), n, C.c_void_p(torch.cuda.current_stream(src.device).cuda_stream))
     if rc != 0:
         raise IcarusError(rc, "icarus_bench_copy failed")
+
+
+def bench_mfma(waves: int, iters: int, device="cuda:0") -> float:
+    """Seconds of the library's register-resident bf16 MFMA loop (flops: 2*32*32*16*8*iters*waves)."""
+    out = torch.empty(waves * 64, dtype=torch.float32, device=device)
+    stream = C.c_void_p(torch.cuda.current_stream(out.device).cuda_stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    if _lib.icarus_bench_mfma(_ptr(out), waves, max(1, iters // 16), stream) != 0:      # warm-up
+        raise IcarusError(8, "icarus_bench_mfma failed")
+    ev[0].record()
+    rc = _lib.icarus_bench_mfma(_ptr(out), waves, iters, stream)
+    ev[1].record()
+    if rc != 0:
+        raise IcarusError(rc, "icarus_bench_mfma failed")
+    torch.cuda.synchronize()
+    return ev[0].elapsed_time(ev[1]) * 1e-3
 
 
 class IcarusLayer:

@@ -373,7 +373,15 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     if constexpr (NB == 0) {
 #pragma unroll
         for (int qt = 0; qt < NA; ++qt) stag[qt] = pl.causal && tok_end == kvlen ? T - 1 - min((16 * qt + m) / g, T - 1) : 0;
-        wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+        // the launch is sized for the largest stacked group of the call; a sequence with fewer
+        // streams multiplies only the query tiles it has
+        const int n_act = (G + 15) >> 4;
+        if (NA >= 3 && n_act >= 3)
+            wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+        else if (NA >= 2 && n_act == 2)
+            wave_walk<NA, (NA >= 2 ? 2 : 1)>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+        else
+            wave_walk<NA, 1>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
         // tree merge of the four waves through LDS: (2,3) -> (0,1), then 1 -> 0
         if (w >= 2) store_to_lds<NA>(st, lds + (w - 2) * kImg, lane);
         __syncthreads();

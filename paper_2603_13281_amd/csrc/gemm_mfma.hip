@@ -306,51 +306,71 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
         stage = next;
     }
 
-    // epilogue: accumulator register r of tile (i, j) is row 8(r/4) + 4(lane/32) + r%4, column lane%32
+    // Epilogue.  Accumulator register r of MFMA tile (i, j) is row 8(r/4) + 4(lane/32) + r%4, column
+    // lane%32: a lane owns single columns, which would make 2-byte stores.  Each wave therefore turns
+    // 32 rows of its tile at a time through its own slice of the (now dead) ring, and reads them back
+    // row-major, 8 columns per lane, for 16- and 32-byte global accesses.
+    __syncthreads();  // every wave has left the K loop
+    constexpr bool kMayBeDual = TN % 2 == 0;
+    const bool dual = kMayBeDual && g.mode == GEMM_DUAL;
+    constexpr int kEs = WN + 8;  // scratch row stride in floats: rows 4 apart fall into different bank halves
+    static_assert(NW * 32 * kEs * 4 <= NS * kStage, "epilogue scratch must fit the ring");
+    float *scr = (float *)smem + w * 32 * kEs;
     const int col_l = lane & 31, row_l = (lane >> 5) * 4;
-    if (g.mode == GEMM_DUAL) {
-        // in a wave, MFMA tile j < TN/2 holds gate and tile j + TN/2 up of the same output columns
-        if constexpr (TN % 2 == 0) {
+    int seg = 0, t = tile_n, col_base = 0;
+    if (!dual)
+        while (seg + 1 < g.nseg && t >= g.tiles_seg[seg]) { t -= g.tiles_seg[seg]; col_base += g.n_seg[seg]; ++seg; }
+    const int wcols = dual ? WN / 2 : WN;                                   // output columns of this wave
+    const int n_wave = dual ? tile_n * (BN / 2) + wn * (WN / 2) : t * BN + wn * WN;  // first of them, inside the segment
+    const int n_lim = g.n_seg[dual ? 0 : seg];
+    const int lpr = wcols / 8, rpp = 64 / lpr;                              // lanes per row, rows per pass
+    const int rr0 = lane / lpr, c8 = (lane % lpr) * 8;
 #pragma unroll
-            for (int j = 0; j < TN / 2; ++j) {
-                int n = tile_n * (BN / 2) + wn * (WN / 2) + j * 32 + col_l;
-                if (n >= g.n_seg[0]) continue;
+    for (int i = 0; i < TM; ++i) {
+        if (dual) {
+            if constexpr (kMayBeDual) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                for (int j = 0; j < TN / 2; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        int row = row0 + wm * WM + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
-                        if (row < g.R) {
-                            float gt = acc[i][j][r], up = acc[i][j + TN / 2][r];
-                            float hv = gt / (1.f + __expf(-gt)) * up;
-                            ((bf16_t *)g.Y)[(size_t)row * g.ldy + n] = f32_to_bf16(hv);
-                        }
+                        float gt = acc[i][j][r], up = acc[i][j + TN / 2][r];
+                        scr[(8 * (r >> 2) + row_l + (r & 3)) * kEs + j * 32 + col_l] = gt * __frcp_rn(1.f + __expf(-gt)) * up;
                     }
             }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) scr[(8 * (r >> 2) + row_l + (r & 3)) * kEs + j * 32 + col_l] = acc[i][j][r];
         }
-        return;
-    }
-    int seg = 0, t = tile_n, col_base = 0;
-    while (seg + 1 < g.nseg && t >= g.tiles_seg[seg]) { t -= g.tiles_seg[seg]; col_base += g.n_seg[seg]; ++seg; }
+        for (int rr = rr0; rr < 32; rr += rpp) {
+            const int row = row0 + wm * WM + i * 32 + rr, n_in = n_wave + c8;
+            if (row >= g.R || n_in >= n_lim) continue;  // output widths are multiples of 8
+            const float4 a = *(const float4 *)(scr + rr * kEs + c8), b = *(const float4 *)(scr + rr * kEs + c8 + 4);
+            float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            const int n = col_base + n_in;
+            if (!dual && g.epi == EPI_F32) {
+                float *yp = (float *)g.Y + ((size_t)kz * g.R + row) * g.ldy + n;
+                *(float4 *)yp = a;
+                *(float4 *)(yp + 4) = b;
+                continue;
+            }
+            if (!dual) {  // EPI_BF16_RESID
+                const uint4 rv = *(const uint4 *)(g.resid + (size_t)row * g.ldr + n);
+                const uint32_t rw[4] = {rv.x, rv.y, rv.z, rv.w};
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        int n_in = t * BN + wn * WN + j * 32 + col_l;
-        if (n_in >= g.n_seg[seg]) continue;
-        int n = col_base + n_in;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int row = row0 + wm * WM + i * 32 + 8 * (r >> 2) + row_l + (r & 3);
-                if (row >= g.R) continue;
-                float v = acc[i][j][r];
-                if (g.epi == EPI_F32) {
-                    ((float *)g.Y)[((size_t)kz * g.R + row) * g.ldy + n] = v;
-                } else {  // EPI_BF16_RESID
-                    v += bf16_to_f32(g.resid[(size_t)row * g.ldr + n]);
-                    ((bf16_t *)g.Y)[(size_t)row * g.ldy + n] = f32_to_bf16(v);
+                for (int e = 0; e < 4; ++e) {
+                    v[2 * e] += __uint_as_float(rw[e] << 16);
+                    v[2 * e + 1] += __uint_as_float(rw[e] & 0xffff0000u);
                 }
             }
+            uint4 o;
+            o.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+            o.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+            o.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
+            o.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+            *(uint4 *)((bf16_t *)g.Y + (size_t)row * g.ldy + n) = o;
+        }
     }
 }
 
@@ -375,6 +395,32 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(const float *__restrict__
         yp[2] = f32_to_bf16(v.z + bf16_to_f32(rp[2]));
         yp[3] = f32_to_bf16(v.w + bf16_to_f32(rp[3]));
     }
+}
+
+// The matrix pipe alone: 8 independent accumulators per wave, operands fixed in registers.
+__global__ void __launch_bounds__(256) k_bench_mfma(float *__restrict__ out, int iters) {
+    const int lane = threadIdx.x & 63;
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(0.001f * (float)((lane + e) % 7));
+        b[e] = (__bf16)(0.002f * (float)((lane + 2 * e) % 5));
+    }
+    f32x16 acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[t][r];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
 template <int BM, int BN, int BK, int NS, int WAVES_M, int WAVES_N>
@@ -451,7 +497,9 @@ int pick_tile(const GemmArgs &g) {
 
 bool gemm_mfma_supported(const Dims &dm, int K) {
     bool r_ok = dm.r == 0 || (dm.r >= 8 && (dm.r & (dm.r - 1)) == 0);  // adapter rank: a power of two >= 8
-    return dm.bf16 && K % kKAlign == 0 && r_ok;
+    // every output width must be a multiple of 8 (16-byte stores of the epilogue)
+    bool n_ok = dm.d % 8 == 0 && dm.F % 8 == 0 && (dm.Hq * dm.D) % 8 == 0 && (dm.Hkv * dm.D) % 8 == 0;
+    return dm.bf16 && K % kKAlign == 0 && r_ok && n_ok;
 }
 
 int gemm_mfma_tiles(const GemmArgs &g) {
@@ -483,6 +531,11 @@ hipError_t launch_splitk_reduce(const float *P, int splits, int R, int N, int ep
     if (!quads) return hipSuccess;
     hipLaunchKernelGGL(k_splitk_reduce, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st, P, splits, R, N, epi, Y, ldy,
                        (const bf16_t *)resid, ldr);
+    return hipGetLastError();
+}
+
+hipError_t launch_bench_mfma(float *out, int waves, int iters, hipStream_t st) {
+    hipLaunchKernelGGL(k_bench_mfma, dim3(waves / 4), dim3(256), 0, st, out, iters);
     return hipGetLastError();
 }
 

@@ -162,28 +162,45 @@ hipError_t launch_silu_mul(const Dims &dm, const float *gate, const float *up, v
 
 // ------------------------------------------------------------------ QK-norm + RoPE + paged append
 // One block per row.  Heads 0..Hq-1 are q; for encoder rows heads Hq..Hq+Hkv-1 are k and the
-// next Hkv are v.  Angles are computed in double: pos * theta^(-2i/D).
+// next Hkv are v.  The row arrives as `splits` fp32 slices (split-K partials of the projection
+// GEMM, `slice` floats apart) that are summed here.  Angles are computed in double, once per
+// row: pos * theta^(-2i/D).
 template <typename T>
-__global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ qkv, int ldq, const int32_t *__restrict__ row_seq,
+__global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ qkv, int ldq, int splits, size_t slice,
+                                                     const int32_t *__restrict__ row_seq,
                                                      const int32_t *__restrict__ row_model, const int32_t *__restrict__ row_pos,
                                                      const int32_t *__restrict__ bt, int max_blocks, T *__restrict__ pool,
                                                      T *__restrict__ q_out, int64_t *__restrict__ slot_out, int slot_by_row,
                                                      const T *__restrict__ q_norm, const T *__restrict__ k_norm,
                                                      int Hq, int Hkv, int D, int Bk, double log2_theta, float eps, int qk_norm) {
-    extern __shared__ float sm[];  // inv_rms per head [Hq + Hkv]
+    extern __shared__ float sm[];  // the row [n_heads * D] | cos, sin [D/2 each] | inv_rms per head [Hq + Hkv]
     int row = blockIdx.x;
     int s = row_seq[row], pos = row_pos[row];
     bool enc = row_model[row] < 0;
     const float *src = qkv + (size_t)row * ldq;
     int half = D >> 1;
-    int n_rot = Hq + (enc ? Hkv : 0);
+    int n_rot = Hq + (enc ? Hkv : 0), n_heads = Hq + (enc ? 2 * Hkv : 0);
     int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    float *xr = sm, *cs_t = sm + (size_t)(Hq + 2 * Hkv) * D, *sn_t = cs_t + half, *inv = sn_t + half;
+    for (int i = threadIdx.x; i < n_heads * D; i += 256) {
+        float v = src[i];
+        for (int z = 1; z < splits; ++z) v += src[z * slice + i];
+        xr[i] = v;
+    }
+    for (int i = threadIdx.x; i < half; i += 256) {
+        double ang = (double)pos * exp2(-(2.0 * (double)i / (double)D) * log2_theta);
+        double sn_d, cs_d;
+        sincos(ang, &sn_d, &cs_d);
+        cs_t[i] = (float)cs_d;
+        sn_t[i] = (float)sn_d;
+    }
+    __syncthreads();
     if (qk_norm) {
         for (int h = w; h < n_rot; h += 4) {
             float ss = 0.f;
-            for (int i = lane; i < D; i += 64) { float v = src[(size_t)h * D + i]; ss += v * v; }
+            for (int i = lane; i < D; i += 64) { float v = xr[(size_t)h * D + i]; ss += v * v; }
             ss = wave_sum(ss);
-            if (lane == 0) sm[h] = rsqrtf(ss / (float)D + eps);
+            if (lane == 0) inv[h] = rsqrtf(ss / (float)D + eps);
         }
         __syncthreads();
     }
@@ -200,15 +217,12 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
     }
     for (int idx = threadIdx.x; idx < n_rot * half; idx += 256) {
         int h = idx / half, i = idx % half;
-        double ang = (double)pos * exp2(-(2.0 * (double)i / (double)D) * log2_theta);
-        double sn_d, cs_d;
-        sincos(ang, &sn_d, &cs_d);
-        float cs = (float)cs_d, sn = (float)sn_d;
-        float a = src[(size_t)h * D + i], b = src[(size_t)h * D + i + half];
+        float cs = cs_t[i], sn = sn_t[i];
+        float a = xr[(size_t)h * D + i], b = xr[(size_t)h * D + i + half];
         if (qk_norm) {
             const T *nw = h < Hq ? q_norm : k_norm;
-            a = a * sm[h] * Elem<T>::ld(nw + i);
-            b = b * sm[h] * Elem<T>::ld(nw + i + half);
+            a = a * inv[h] * Elem<T>::ld(nw + i);
+            b = b * inv[h] * Elem<T>::ld(nw + i + half);
         }
         float ra = a * cs - b * sn, rb = b * cs + a * sn;
         if (h < Hq) {
@@ -222,7 +236,7 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
         }
     }
     if (enc) {
-        const float *vsrc = src + (size_t)(Hq + Hkv) * D;
+        const float *vsrc = xr + (size_t)(Hq + Hkv) * D;
         for (int idx = threadIdx.x; idx < Hkv * D; idx += 256) {
             int h = idx / D, i = idx % D;
             T *dst = vdst + ((size_t)h * 2 + 1) * Bk * D;  // V plane [D][Bk]
@@ -231,14 +245,24 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
     }
 }
 
-hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, const RowMeta &rm, const int32_t *bt,
-                              int max_blocks, void *pool, void *q_out, int64_t *slot_out, int slot_by_row,
+hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, int splits, size_t slice, const RowMeta &rm,
+                              const int32_t *bt, int max_blocks, void *pool, void *q_out, int64_t *slot_out, int slot_by_row,
                               const void *q_norm, const void *k_norm, int R, hipStream_t st) {
     if (R <= 0) return hipSuccess;
-    size_t shm = sizeof(float) * (size_t)(dm.Hq + dm.Hkv);
+    size_t shm = sizeof(float) * ((size_t)(dm.Hq + 2 * dm.Hkv) * dm.D + dm.D + dm.Hq + dm.Hkv);
     double l2t = log2(dm.theta);
-    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_rope_append<T>, dim3(R), dim3(256), shm, st, qkv, ldq, rm.row_seq, rm.row_model,
-                                           rm.row_pos, bt, max_blocks, (T *)pool, (T *)q_out, slot_out, slot_by_row,
+    if (shm > 64 * 1024) {
+        static bool attr_set[2] = {false, false};
+        if (!attr_set[dm.bf16 ? 1 : 0]) {
+            hipError_t e = dm.bf16 ? hipFuncSetAttribute((const void *)k_rope_append<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)
+                                   : hipFuncSetAttribute((const void *)k_rope_append<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            attr_set[dm.bf16 ? 1 : 0] = true;
+        }
+        if (shm > 160 * 1024) return hipErrorInvalidValue;
+    }
+    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_rope_append<T>, dim3(R), dim3(256), shm, st, qkv, ldq, splits, slice, rm.row_seq,
+                                           rm.row_model, rm.row_pos, bt, max_blocks, (T *)pool, (T *)q_out, slot_out, slot_by_row,
                                            (const T *)q_norm, (const T *)k_norm, dm.Hq, dm.Hkv, dm.D, dm.Bk, l2t, dm.eps, dm.qk_norm));
     return hipGetLastError();
 }

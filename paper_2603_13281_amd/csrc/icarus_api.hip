@@ -368,9 +368,11 @@ bool layer_mfma_supported(const icarus_ctx *ctx) {
 }
 
 // One plain ICaRusLinear GEMM.  When its grid would leave most of the chip idle (few rows and a
-// narrow output), K is split over several workgroups into fp32 partials and a second small kernel
-// sums them and applies the epilogue.
-icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, GemmArgs g, hipStream_t st) {
+// narrow output), K is split over several workgroups into fp32 partials [splits][R][N]; a second
+// small kernel sums them and applies the epilogue, unless the caller takes the slices as they are
+// (deferred_splits: set to the number of slices left in the workspace, 0 if the output is final).
+icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, GemmArgs g, hipStream_t st,
+                       int *deferred_splits = nullptr) {
     int tiles = gemm_mfma_tiles(g);
     int n_total = 0;
     for (int s = 0; s < g.nseg; ++s) n_total += g.n_seg[s];
@@ -378,6 +380,7 @@ icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, 
     int splits = 1;
     if (tiles < 160) splits = std::max(1, std::min({kGemmMaxSplits, 384 / tiles, k_ext / 256}));
     splits = (int)std::max<size_t>(1, std::min<size_t>(splits, L.gemm_part_bytes / ((size_t)g.R * n_total * 4)));
+    if (deferred_splits) *deferred_splits = 0;
     if (splits == 1) {
         g.splits = 1;
         PHASE(ctx, st, phase, launch_gemm_mfma(g, st));
@@ -386,6 +389,10 @@ icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, 
     GemmArgs p = g;
     p.epi = EPI_F32; p.Y = ws + L.gemm_part; p.ldy = n_total; p.splits = splits;
     PHASE(ctx, st, phase, launch_gemm_mfma(p, st));
+    if (deferred_splits && n_total == g.ldy) {  // the consumer sums the slices [splits][R][n_total] itself
+        *deferred_splits = splits;
+        return ICARUS_OK;
+    }
     PHASE(ctx, st, phase, launch_splitk_reduce((const float *)(ws + L.gemm_part), splits, g.R, n_total, g.epi, g.Y, g.ldy, g.resid,
                                                g.ldr, st));
     return ICARUS_OK;
@@ -410,6 +417,7 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
     // RMSNorm, with the shrink of the Q adapters on the normalised rows
     PHASE(ctx, st, ICARUS_PH_NORM, launch_norm_shrink(dm, x_in, ctx->base.norm_attn, xn, R, d, lq ? Aw(ICARUS_PROJ_Q) : nullptr, nullptr,
                                                       rm.row_model, T, nullptr, 0, st));
+    int qkv_splits = 0, o_splits = 0;
     {   // Q (ICaRusLinear) and the encoder's K, V in one GEMM over [W_q; W_k; W_v]
         GemmArgs g{};
         g.X = xn; g.ldx = d; g.R = R; g.K = d;
@@ -423,10 +431,13 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
             g.W[2] = W(ICARUS_PROJ_V); g.n_seg[2] = kvd; g.nseg = 3;
             g.Y = qkv; g.ldy = ldq;
         }
-        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_QKV, g, st));
+        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_QKV, g, st, &qkv_splits));
     }
-    PHASE(ctx, st, ICARUS_PH_ROPE_APPEND, launch_rope_append(dm, qkv, ldq, rm, bt, max_blocks, pool, q, slot_out, slot_by_row,
-                                                             ctx->base.q_norm, ctx->base.k_norm, R, st));
+    {   // split-K slices of the projection, if any were left, are summed by the RoPE kernel
+        const float *src = qkv_splits ? (const float *)(ws + L.gemm_part) : qkv;
+        PHASE(ctx, st, ICARUS_PH_ROPE_APPEND, launch_rope_append(dm, src, ldq, std::max(1, qkv_splits), (size_t)R * ldq, rm, bt, max_blocks,
+                                                                 pool, q, slot_out, slot_by_row, ctx->base.q_norm, ctx->base.k_norm, R, st));
+    }
     if (kv_only) return ICARUS_OK;
     LORA_TRY(run_decode_attention(ctx, ws, L, rm, hp, q, pool, bt, max_blocks, attn, R, st));
     {   // O projection (ICaRusLinear) + residual
@@ -439,12 +450,19 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
             g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_O);
         }
         g.Y = z; g.ldy = d; g.resid = (const bf16_raw *)x_in; g.ldr = d;
-        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_O, g, st));
+        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_O, g, st, &o_splits));
     }
     const bool lg = lo(ICARUS_PROJ_GATE), lu = lo(ICARUS_PROJ_UP);
     if (lg != lu) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "adapters on only one of gate/up need the generic kernels (set kernel mode 1)");
-    PHASE(ctx, st, ICARUS_PH_NORM, launch_norm_shrink(dm, z, ctx->base.norm_ffn, xn, R, d, lg ? Aw(ICARUS_PROJ_GATE) : nullptr,
-                                                      lg ? Aw(ICARUS_PROJ_UP) : nullptr, rm.row_model, T, nullptr, 0, st));
+    // RMSNorm with the shrink of the gate/up adapters; if the O projection left split-K slices, the
+    // same kernel first forms z = x + their sum
+    if (o_splits)
+        PHASE(ctx, st, ICARUS_PH_NORM, launch_sum_norm_shrink(dm, (const float *)(ws + L.gemm_part), o_splits, (size_t)R * d, x_in, z,
+                                                              ctx->base.norm_ffn, xn, R, d, lg ? Aw(ICARUS_PROJ_GATE) : nullptr,
+                                                              lg ? Aw(ICARUS_PROJ_UP) : nullptr, rm.row_model, T, st));
+    else
+        PHASE(ctx, st, ICARUS_PH_NORM, launch_norm_shrink(dm, z, ctx->base.norm_ffn, xn, R, d, lg ? Aw(ICARUS_PROJ_GATE) : nullptr,
+                                                          lg ? Aw(ICARUS_PROJ_UP) : nullptr, rm.row_model, T, nullptr, 0, st));
     {   // gate and up (ICaRusLinear x 2) with the SwiGLU product in the epilogue
         GemmArgs g{};
         g.X = xn; g.ldx = d; g.R = R; g.K = d;
@@ -498,7 +516,7 @@ icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowM
     }
     PHASE(ctx, st, ICARUS_PH_GEMM_QKV, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_K], R, kvd, d, qkv + qd, ldq, st));
     PHASE(ctx, st, ICARUS_PH_GEMM_QKV, launch_gemm_generic(dm, xn, d, ctx->base.w[ICARUS_PROJ_V], R, kvd, d, qkv + qd + kvd, ldq, st));
-    PHASE(ctx, st, ICARUS_PH_ROPE_APPEND, launch_rope_append(dm, qkv, ldq, rm, bt, max_blocks, pool, q, slot_out, slot_by_row,
+    PHASE(ctx, st, ICARUS_PH_ROPE_APPEND, launch_rope_append(dm, qkv, ldq, 1, 0, rm, bt, max_blocks, pool, q, slot_out, slot_by_row,
                                                              ctx->base.q_norm, ctx->base.k_norm, R, st));
     if (kv_only) return ICARUS_OK;
     LORA_TRY(run_decode_attention(ctx, ws, L, rm, hp, q, pool, bt, max_blocks, attn, R, st));
@@ -624,6 +642,11 @@ icarus_status icarus_timing_read(icarus_ctx *ctx, double *ms, int32_t *launches)
 icarus_status icarus_bench_copy(const void *src, void *dst, size_t bytes, void *stream) {
     if (!src || !dst || bytes % 16 || !aligned16(src) || !aligned16(dst)) return ICARUS_ERR_INVALID_ARG;
     return launch_bench_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? ICARUS_OK : ICARUS_ERR_HIP;
+}
+
+icarus_status icarus_bench_mfma(float *out, int32_t waves, int32_t iters, void *stream) {
+    if (!out || waves <= 0 || waves % 4 || iters <= 0) return ICARUS_ERR_INVALID_ARG;
+    return launch_bench_mfma(out, waves, iters, (hipStream_t)stream) == hipSuccess ? ICARUS_OK : ICARUS_ERR_HIP;
 }
 
 size_t icarus_workspace_bytes(const icarus_ctx *ctx, int32_t max_rows, int32_t max_seqs, int32_t max_ctx) {

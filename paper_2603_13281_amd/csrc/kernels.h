@@ -42,9 +42,10 @@ hipError_t launch_resid_store(const Dims &dm, const void *resid, const float *ac
 hipError_t launch_silu_mul(const Dims &dm, const float *gate, const float *up, void *h, int R, int n, hipStream_t st);
 // QK-RMSNorm (optional) + RoPE on q (all rows) and k (encoder rows), q -> q_out (storage, [R,Hq,D]),
 // k, v of encoder rows -> paged cache; slot_out[slot_by_row ? row : seq] = slot.
-// qkv: fp32 [R, ldq] with q at column 0, k at Hq*D, v at (Hq+Hkv)*D.
-hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, const RowMeta &rm, const int32_t *bt,
-                              int max_blocks, void *pool, void *q_out, int64_t *slot_out, int slot_by_row,
+// qkv: fp32 [R, ldq] with q at column 0, k at Hq*D, v at (Hq+Hkv)*D, given as `splits` slices that are
+// summed (`slice` floats apart; splits = 1: the plain array).
+hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, int splits, size_t slice, const RowMeta &rm,
+                              const int32_t *bt, int max_blocks, void *pool, void *q_out, int64_t *slot_out, int slot_by_row,
                               const void *q_norm, const void *k_norm, int R, hipStream_t st);
 // out[row, h, :] = softmax(q[row,h,:] K^T / sqrt(D)) V over positions 0..row_kvlen[row]-1 of row_seq[row]
 hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
@@ -52,6 +53,8 @@ hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, 
 
 // plain grid-stride copy of `bytes` bytes (multiple of 16), kernel k_bench_copy: profiler calibration
 hipError_t launch_bench_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+// register-resident MFMA loop, kernel k_bench_mfma: waves (multiple of 4) x iters x 8 MFMAs 32x32x16 bf16
+hipError_t launch_bench_mfma(float *out, int waves, int iters, hipStream_t st);
 
 // ---- matrix-core kernels (bf16 storage) ------------------------------------------------------
 // Host-built split plan of the decode attention: a sequence's cached tokens are cut into chunks
@@ -100,6 +103,11 @@ bool row_shrink_supported(int r, int targets);
 // share y; also sets zero[0..n_zero) = 0.
 hipError_t launch_norm_shrink(const Dims &dm, const void *x, const void *wn, void *y, int R, int K, const void *A0, const void *A1,
                               const int32_t *row_model, void *T, int *zero, int n_zero, hipStream_t st);
+// the same on rows that are still in pieces: xsum = resid + sum of `splits` fp32 slices [R, K] (`slice` floats
+// apart, the split-K partials of the projection before the norm) is formed, rounded, stored, and normalised
+hipError_t launch_sum_norm_shrink(const Dims &dm, const float *part, int splits, size_t slice, const void *resid, void *xsum,
+                                  const void *wn, void *y, int R, int K, const void *A0, const void *A1, const int32_t *row_model,
+                                  void *T, hipStream_t st);
 // the shrink alone, of x [R, K] (row stride ldx)
 hipError_t launch_row_shrink(const Dims &dm, const void *x, int ldx, int R, int K, const void *A0, const int32_t *row_model, void *T,
                              hipStream_t st);

@@ -34,7 +34,9 @@ template <bool NORM, int NACC>
 __global__ void __launch_bounds__(kRowThreads) k_norm_shrink(const bf16_t *__restrict__ x, int ldx, int K, const bf16_t *__restrict__ wn,
                                                      float eps, bf16_t *__restrict__ y, const bf16_t *__restrict__ A0,
                                                      const bf16_t *__restrict__ A1, int r, int M, const int32_t *__restrict__ row_model,
-                                                     float scale, bf16_t *__restrict__ T, int ldt, int *__restrict__ zero, int n_zero) {
+                                                     float scale, bf16_t *__restrict__ T, int ldt, int *__restrict__ zero, int n_zero,
+                                                     const float *__restrict__ psum, int splits, size_t slice,
+                                                     const bf16_t *__restrict__ resid, bf16_t *__restrict__ xsum) {
     __shared__ float red[16];
     __shared__ float part[kRowThreads / 64][NACC > 0 ? NACC : 1];
     __shared__ float res[NACC > 0 ? NACC : 1];
@@ -48,7 +50,24 @@ __global__ void __launch_bounds__(kRowThreads) k_norm_shrink(const bf16_t *__res
         float ss = 0.f;
         for (int c = tid; c < n_chunks; c += kRowThreads) {
             float f[8];
-            unpack8(*(const uint4 *)(xr + c * 8), f);
+            if (psum) {
+                // the row is still in pieces: residual + split-K partials of the projection before the
+                // norm.  Sum them, round to storage, keep (xsum is x): each thread re-reads below
+                // only the chunks it wrote itself.
+                unpack8(*(const uint4 *)(resid + (size_t)row * K + c * 8), f);
+                for (int z = 0; z < splits; ++z) {
+                    const float *pp = psum + z * slice + (size_t)row * K + c * 8;
+                    const float4 p0 = *(const float4 *)pp, p1 = *(const float4 *)(pp + 4);
+                    f[0] += p0.x; f[1] += p0.y; f[2] += p0.z; f[3] += p0.w;
+                    f[4] += p1.x; f[5] += p1.y; f[6] += p1.z; f[7] += p1.w;
+                }
+                uint4 o;
+                o.x = pack2(f[0], f[1]); o.y = pack2(f[2], f[3]); o.z = pack2(f[4], f[5]); o.w = pack2(f[6], f[7]);
+                *(uint4 *)(xsum + (size_t)row * K + c * 8) = o;
+                unpack8(o, f);
+            } else {
+                unpack8(*(const uint4 *)(xr + c * 8), f);
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
         }
@@ -119,10 +138,11 @@ __global__ void __launch_bounds__(kRowThreads) k_norm_shrink(const bf16_t *__res
 template <bool NORM>
 hipError_t launch_ns(int nacc, int R, hipStream_t st, const bf16_t *x, int ldx, int K, const bf16_t *wn, float eps, bf16_t *y,
                      const bf16_t *A0, const bf16_t *A1, int r, int M, const int32_t *row_model, float scale, bf16_t *T, int ldt,
-                     int *zero, int n_zero) {
+                     int *zero, int n_zero, const float *part = nullptr, int splits = 0, size_t slice = 0,
+                     const bf16_t *resid = nullptr, bf16_t *xsum = nullptr) {
 #define ICARUS_NS(N)                                                                                                          \
     hipLaunchKernelGGL((k_norm_shrink<NORM, N>), dim3(R), dim3(kRowThreads), 0, st, x, ldx, K, wn, eps, y, A0, A1, r, M, row_model, \
-                       scale, T, ldt, zero, n_zero)
+                       scale, T, ldt, zero, n_zero, part, splits, slice, resid, xsum)
     switch (nacc) {
     case 0: ICARUS_NS(0); break;
     case 8: ICARUS_NS(8); break;
@@ -148,6 +168,16 @@ hipError_t launch_norm_shrink(const Dims &dm, const void *x, const void *wn, voi
     int targets = A0 ? (A1 ? 2 : 1) : 0;
     return launch_ns<true>(targets * dm.r, R, st, (const bf16_t *)x, K, K, (const bf16_t *)wn, dm.eps, (bf16_t *)y, (const bf16_t *)A0,
                            (const bf16_t *)A1, dm.r, dm.M, row_model, dm.lora_scale, (bf16_t *)T, targets * dm.M * dm.r, zero, n_zero);
+}
+
+hipError_t launch_sum_norm_shrink(const Dims &dm, const float *part, int splits, size_t slice, const void *resid, void *xsum,
+                                  const void *wn, void *y, int R, int K, const void *A0, const void *A1, const int32_t *row_model,
+                                  void *T, hipStream_t st) {
+    if (R <= 0) return hipSuccess;
+    int targets = A0 ? (A1 ? 2 : 1) : 0;
+    return launch_ns<true>(targets * dm.r, R, st, (const bf16_t *)xsum, K, K, (const bf16_t *)wn, dm.eps, (bf16_t *)y,
+                           (const bf16_t *)A0, (const bf16_t *)A1, dm.r, dm.M, row_model, dm.lora_scale, (bf16_t *)T,
+                           targets * dm.M * dm.r, nullptr, 0, part, splits, slice, (const bf16_t *)resid, (bf16_t *)xsum);
 }
 
 hipError_t launch_row_shrink(const Dims &dm, const void *x, int ldx, int R, int K, const void *A0, const int32_t *row_model, void *T,
