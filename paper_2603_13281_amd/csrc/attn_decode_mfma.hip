@@ -412,6 +412,195 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     }
 }
 
+// compute_group for a group that sits in LDS as fragments (src[i * 64]: K fragments i = 0..7, then
+// V^T fragments): all tiles' S^T first, so that the K fragments are dead before the V^T fragments
+// are fetched -- half the operand registers of the tile-by-tile form.
+template <int NT, bool tail>
+__device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *__restrict__ src, const bf16x8 *__restrict__ qlds,
+                                                  int left, const int (&stag)[NT], float scale_log2, int lane) {
+    const int q = lane >> 4;
+    const int tbase = 16 * (q >> 1) + 8 * (q & 1);
+    float sv[NT][8];
+    {
+        bf16x8 kf[2][kKS];
+#pragma unroll
+        for (int i = 0; i < 2 * kKS; ++i) kf[i / kKS][i % kKS] = src[i * 64];
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt) {
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < kKS; ++ks) {
+                bf16x8 qv = qlds[(qt * kKS + ks) * 64 + lane];
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][ks], qv, s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][ks], qv, s1, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                sv[qt][i] = s0[i] * scale_log2;
+                sv[qt][4 + i] = s1[i] * scale_log2;
+            }
+        }
+    }
+    bf16x8 pb[NT];
+#pragma unroll
+    for (int qt = 0; qt < NT; ++qt) {
+        if (tail) {
+            const int lim = left - stag[qt];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (tbase + e >= lim) sv[qt][e] = -INFINITY;
+        }
+        float mx = sv[qt][0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[qt][e]);
+        if (__any(mx > st.m[qt] + kSlack)) {  // see compute_group: lazy softmax reference
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_old = st.m[qt];
+            const float m_new = fmaxf(m_old, mx);
+            st.m[qt] = m_new;
+            float alpha = (tail && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_old - m_new);
+            st.l[qt] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) {
+                st.o[dt][qt][0] *= alpha; st.o[dt][qt][1] *= alpha; st.o[dt][qt][2] *= alpha; st.o[dt][qt][3] *= alpha;
+            }
+        }
+        const float m_ref = st.m[qt];
+        float rs = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float p = __builtin_amdgcn_exp2f(sv[qt][e] - m_ref);
+            if (tail && m_ref == -INFINITY) p = 0.f;
+            rs += p;
+            pb[qt][e] = (__bf16)p;
+        }
+        st.l[qt] += rs;
+    }
+#pragma unroll
+    for (int dt = 0; dt < kDT; ++dt) {
+        bf16x8 vf = src[(2 * kKS + dt) * 64];
+        if (tail) {  // stale cache bytes past the end may hold anything: zero those V columns
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (tbase + e >= left) vf[e] = (__bf16)0.f;
+        }
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt) st.o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[qt], st.o[dt][qt], 0, 0, 0);
+    }
+}
+
+// Half of a group's loads: part 0 = the 8 K fragments, part 1 = the 8 V^T fragments, in the order
+// they take in a KVFrag (k[t][ks] as 4t + ks, then v[dt]).
+__device__ __forceinline__ void load_half(bf16x8 (&h)[8], int part, const bf16_t *__restrict__ pool, int blk0, int blk1, int c,
+                                          int Hkv, int lane) {
+    const int m = lane & 15, q = lane >> 4;
+    const size_t head_stride = (size_t)2 * kBk * kD;
+    if (part == 0) {
+        const bf16_t *kb = pool + ((size_t)((m >> 3) ? blk1 : blk0) * Hkv + c) * head_stride;
+        const int tok0 = 8 * ((m >> 2) & 1) + (m & 3);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int ks = 0; ks < kKS; ++ks) h[t * kKS + ks] = *(const bf16x8 *)(kb + (size_t)(tok0 + 4 * t) * kD + 32 * ks + 8 * q);
+    } else {
+        const bf16_t *vb = pool + ((size_t)((q >> 1) ? blk1 : blk0) * Hkv + c) * head_stride + (size_t)kBk * kD;
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt) h[dt] = *(const bf16x8 *)(vb + (size_t)(16 * dt + m) * kBk + 8 * (q & 1));
+    }
+}
+static_assert(2 * kKS == 8 && kDT == 8, "a half group is 8 fragments");
+
+// Prefill walk: the eight waves hold different query tiles and every wave needs every group, so a
+// group is loaded once -- in round r wave w loads half (w & 1: K or V^T) of group 4r + w/2 into
+// registers, one round ahead -- published to a one-round LDS ring as MFMA fragments in lane order,
+// and read from there by all eight.  ring: [4][16][64] x 16 B.
+template <int NT>
+__device__ __forceinline__ void prefill_walk(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
+                                             int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int c, int Hkv,
+                                             bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds, float scale_log2,
+                                             int lane) {
+    const int n_grp = (n_tok + kGrp - 1) / kGrp;  // groups, the masked ones included
+    const int n_round = (n_grp + 3) / 4;          // the same for every wave
+    const int part = w & 1, gl = w >> 1;
+    auto blk_of = [&](int grp, int which) {
+        return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
+    };
+    bf16x8 h[8];
+    if (gl < n_grp) load_half(h, part, pool, blk_of(gl, 0), blk_of(gl, 1), c, Hkv, lane);
+#pragma nounroll
+    for (int r = 0; r < n_round; ++r) {
+        const int mine = 4 * r + gl;
+        __syncthreads();  // every wave has read the previous round out of the ring
+        if (mine < n_grp) {
+            bf16x8 *dst = ring + ((size_t)gl * 16 + part * 8) * 64 + lane;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dst[i * 64] = h[i];
+        }
+        if (mine + 4 < n_grp) load_half(h, part, pool, blk_of(mine + 4, 0), blk_of(mine + 4, 1), c, Hkv, lane);
+        __syncthreads();
+#pragma nounroll
+        for (int gi = 0; gi < 4; ++gi) {
+            const int grp = 4 * r + gi;
+            if (grp >= n_grp) break;
+            const bf16x8 *src = ring + (size_t)gi * 16 * 64 + lane;
+            if (grp >= n_clean)
+                compute_group_lds<NT, true>(st, src, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
+            else
+                compute_group_lds<NT, false>(st, src, qlds, kGrp, stag, scale_log2, lane);
+        }
+    }
+}
+
+constexpr int kPrefillWaves = 8, kPrefillNT = 2;  // 8 waves x 2 tiles x 16 = 256 stacked queries per workgroup
+
+// Causal attention of a prefill chunk.  A workgroup owns one kv-head of one group of T consecutive
+// chunk tokens (T * g <= 256 stacked queries; token t attends to kv_len - (T-1-t) positions) and
+// walks the sequence's cache once for all of them; wave w holds query tiles [w NT, (w+1) NT).
+template <int NT>
+__global__ void __launch_bounds__(64 * kPrefillWaves) k_attn_prefill(const bf16_t *__restrict__ qg, const bf16_t *__restrict__ pool,
+                                                                     const int32_t *__restrict__ bt, int max_blocks, AttnPlan pl,
+                                                                     bf16_t *__restrict__ out, int Hq, int Hkv, float scale_log2) {
+    extern __shared__ float lds[];
+    const int item = blockIdx.x / Hkv, c = blockIdx.x % Hkv;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int s = pl.item_seq[item];
+    const int n_tok = pl.seq_kvlen[s];  // a causal plan never splits a sequence
+    const int row0 = pl.seq_row0[s], T = pl.seq_rows[s];
+    const int g = Hq / Hkv, G = T * g;
+    const int m = lane & 15, q = lane >> 4;
+    const int32_t *btr = bt + (size_t)pl.seq_bt[s] * max_blocks;
+    // LDS: [KV ring 64 KB] [Q fragments: wave, tile, k-step, lane] [block ids]
+    bf16x8 *ring = (bf16x8 *)lds;
+    bf16x8 *qall = ring + 4 * 16 * 64;
+    bf16x8 *qlds = qall + (size_t)w * NT * kKS * 64;
+#pragma unroll
+    for (int qt = 0; qt < NT; ++qt) {
+        int j = 16 * (w * NT + qt) + m;
+        const bf16_t *qp = qg + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD + 8 * q;
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) qlds[(qt * kKS + ks) * 64 + lane] = j < G ? *(const bf16x8 *)(qp + 32 * ks) : zero8();
+    }
+    int *blds = (int *)(qall + kPrefillWaves * NT * kKS * 64);
+    const int n_blk = (n_tok + kBk - 1) / kBk;
+    for (int i = threadIdx.x; i < n_blk; i += 64 * kPrefillWaves) blds[i] = btr[i];
+    __syncthreads();
+
+    State<NT> st;
+    int stag[NT];
+#pragma unroll
+    for (int qt = 0; qt < NT; ++qt) {
+        st.m[qt] = -INFINITY;
+        st.l[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt) st.o[dt][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        stag[qt] = T - 1 - min((16 * (w * NT + qt) + m) / g, T - 1);
+    }
+    const int n_clean = max(0, n_tok - (T - 1)) / kGrp;  // groups valid for every query
+    prefill_walk<NT>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, c, Hkv, ring, qlds, scale_log2, lane);
+    finish<NT>(st, w * NT, NT, G, g, row0, c, Hq, Hkv, 1, 0, 0, out, nullptr, nullptr, lane);
+}
+
 // Combine the partial results of sequences that were split into several chunks.
 // One block of 128 threads per (row, query head); thread d owns output element d.
 __global__ void __launch_bounds__(128) k_attn_merge(const float *__restrict__ part_o, const float *__restrict__ part_ml,
@@ -458,6 +647,30 @@ hipError_t launch_one(const void *q, const void *pool, const int32_t *bt, int ma
 
 bool attn_decode_mfma_supported(const Dims &dm, int g_max) {
     return dm.bf16 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= 80;
+}
+
+int attn_prefill_group_queries() { return kPrefillWaves * kPrefillNT * 16; }  // stacked queries one prefill workgroup holds
+
+bool attn_prefill_mfma_supported(const Dims &dm, int g_max) {
+    return dm.bf16 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= attn_prefill_group_queries();
+}
+
+hipError_t launch_attn_prefill_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
+                                    const AttnPlan &pl, void *out, hipStream_t st) {
+    if (pl.n_items <= 0) return hipSuccess;
+    if (!pl.causal || pl.chunk > kAttnMaxChunk) return hipErrorInvalidValue;
+    constexpr int NT = kPrefillNT;
+    float scale_log2 = kLog2e / sqrtf((float)dm.D);
+    size_t shm = (size_t)4 * 16 * 64 * 16 + (size_t)kPrefillWaves * NT * kKS * 64 * 16 + (size_t)(kAttnMaxChunk / kBk) * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_attn_prefill<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_attn_prefill<NT>), dim3(pl.n_items * dm.Hkv), dim3(64 * kPrefillWaves), shm, st, (const bf16_t *)q, (const bf16_t *)pool, bt,
+                       max_blocks, pl, (bf16_t *)out, dm.Hq, dm.Hkv, scale_log2);
+    return hipGetLastError();
 }
 
 hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,

@@ -283,7 +283,7 @@ void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t
         g_max = std::max(g_max, seq_rows[s] * g);
         if (seq_rows[s] > 0) total += kv_lens[s];
     }
-    if (!attn_decode_mfma_supported(ctx->dm, g_max) || g_max > kAttnGMax) return;
+    if (causal ? !attn_prefill_mfma_supported(ctx->dm, g_max) : (!attn_decode_mfma_supported(ctx->dm, g_max) || g_max > kAttnGMax)) return;
     int64_t chunk = (total * c.n_kv_heads + kAttnTargetWgs - 1) / kAttnTargetWgs;
     if (ctx->attn_chunk_override > 0) chunk = ctx->attn_chunk_override;
     chunk = std::min<int64_t>(kAttnMaxChunk, std::max<int64_t>(ctx->attn_chunk_override > 0 ? 128 : 256, (chunk + 127) / 128 * 128));
@@ -349,6 +349,10 @@ icarus_status run_decode_attention(icarus_ctx *ctx, char *ws, const WsLayout &L,
                                    hipStream_t st) {
     if (!hp || !hp->valid) {
         PHASE(ctx, st, ICARUS_PH_ATTN, launch_attn_generic(ctx->dm, q, pool, bt, max_blocks, rm, out, R, st));
+        return ICARUS_OK;
+    }
+    if (hp->pl.causal) {
+        PHASE(ctx, st, ICARUS_PH_ATTN, launch_attn_prefill_mfma(ctx->dm, q, pool, bt, max_blocks, hp->pl, out, st));
         return ICARUS_OK;
     }
     float *part_o = (float *)(ws + L.part_o), *part_ml = (float *)(ws + L.part_ml);
@@ -745,12 +749,13 @@ icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *b
             m[3 * R + r] = ctx_lens[s] + i + 1;
         }
     // Attention plan: the chunk's tokens are cut into groups of consecutive tokens whose stacked query
-    // heads fill up to three 16-query tiles; each group is one plan sequence with a causal stagger.
+    // heads fill one workgroup of the prefill attention; each group is one plan sequence with a causal
+    // stagger.
     char *ws = (char *)workspace;
     const int32_t *dmeta = (const int32_t *)(ws + L.meta);
     HostPlan hp;
     if (x_out) {
-        int g = c.n_q_heads / c.n_kv_heads, tq = std::max(1, 48 / g);
+        int g = c.n_q_heads / c.n_kv_heads, tq = std::max(1, attn_prefill_group_queries() / g);
         std::vector<int32_t> vkv, vrow0, vrows, vbt;
         int row = 0;
         for (int s = 0; s < S; ++s) {

@@ -113,6 +113,12 @@ hipError_t launch_row_shrink(const Dims &dm, const void *x, int ldx, int R, int 
                              hipStream_t st);
 
 bool attn_decode_mfma_supported(const Dims &dm, int g_max);
+// Causal attention of prefill chunks: each plan sequence is a group of consecutive chunk tokens with at
+// most attn_prefill_group_queries() stacked queries (tokens x Hq/Hkv); never split, writes `out` directly.
+int attn_prefill_group_queries();
+bool attn_prefill_mfma_supported(const Dims &dm, int g_max);
+hipError_t launch_attn_prefill_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
+                                    const AttnPlan &pl, void *out, hipStream_t st);
 // part_o: fp32 [slots, Hkv, g_max, D]; part_ml: fp32 [slots, Hkv, g_max, 2] (max in log2 units, sum)
 hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
                                    const AttnPlan &pl, void *out, float *part_o, float *part_ml, hipStream_t st);
