@@ -182,10 +182,30 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
     int n_rot = Hq + (enc ? Hkv : 0), n_heads = Hq + (enc ? 2 * Hkv : 0);
     int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     float *xr = sm, *cs_t = sm + (size_t)(Hq + 2 * Hkv) * D, *sn_t = cs_t + half, *inv = sn_t + half;
-    for (int i = threadIdx.x; i < n_heads * D; i += 256) {
-        float v = src[i];
-        for (int z = 1; z < splits; ++z) v += src[z * slice + i];
-        xr[i] = v;
+    const bool vec_ok = D % 4 == 0 && ldq % 4 == 0 && slice % 4 == 0;
+    if (!vec_ok)
+        for (int i = threadIdx.x; i < n_heads * D; i += 256) {
+            float v = src[i];
+            for (int z = 1; z < splits; ++z) v += src[z * slice + i];
+            xr[i] = v;
+        }
+    // rows and slices 16-byte aligned: 16-byte loads, four slices in flight
+    for (int i = threadIdx.x * 4; vec_ok && i < n_heads * D; i += 1024) {
+        float4 v = *(const float4 *)(src + i);
+        int z = 1;
+        for (; z + 3 < splits; z += 4) {
+            const float4 a = *(const float4 *)(src + (size_t)z * slice + i), b = *(const float4 *)(src + (size_t)(z + 1) * slice + i);
+            const float4 c4 = *(const float4 *)(src + (size_t)(z + 2) * slice + i), d4 = *(const float4 *)(src + (size_t)(z + 3) * slice + i);
+            v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+            v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+            v.x += c4.x; v.y += c4.y; v.z += c4.z; v.w += c4.w;
+            v.x += d4.x; v.y += d4.y; v.z += d4.z; v.w += d4.w;
+        }
+        for (; z < splits; ++z) {
+            const float4 a = *(const float4 *)(src + (size_t)z * slice + i);
+            v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+        }
+        *(float4 *)(xr + i) = v;
     }
     for (int i = threadIdx.x; i < half; i += 256) {
         double ang = (double)pos * exp2(-(2.0 * (double)i / (double)D) * log2_theta);
