@@ -3,7 +3,8 @@
 //
 // All stacked queries of one sequence that share a kv-head -- (1 + m_s) streams x g heads --
 // form the N dimension of the MFMA tiles, so each KV block is fetched from HBM once for all
-// of the sequence's models.  A workgroup (4 waves) owns one (sequence, kv-head, token chunk).
+// of the sequence's models.  A workgroup (4 waves) owns one kv-head of one equal share of the
+// call's cached tokens and walks the share's pieces (token ranges of one sequence each) in turn.
 // Per 32-token group a wave computes
 //     S^T[32 tok x G]  = K[32 tok x 128] . Q^T          (A = K straight from global memory)
 //     O^T[128 x G]    += V^T[128 x 32 tok] . P^T         (A = V^T straight from global memory)
@@ -323,15 +324,19 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     constexpr int NQT = NA + NB;
     constexpr int kImg = kDT * NA * 4 * 64 + 2 * NA * 64;  // floats per wave image of the merge
     extern __shared__ float lds[];
-    const int item = blockIdx.x / Hkv, c = blockIdx.x % Hkv;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int g = Hq / Hkv;
+    const int m = lane & 15, q = lane >> 4;
+  // the pieces of this workgroup's share, one after the other; the Hkv workgroups of a share (one per
+  // kv-head, on different XCDs) walk the same blocks at about the same time
+  const int share = blockIdx.x / Hkv, c = blockIdx.x % Hkv;
+  for (int item = pl.wg_first[share]; item < pl.wg_first[share + 1]; ++item) {
     const int s = pl.item_seq[item];
     const int tok_begin = pl.item_begin[item];
     const int kvlen = pl.seq_kvlen[s];
-    const int tok_end = min(tok_begin + pl.chunk, kvlen);
+    const int tok_end = tok_begin + pl.item_len[item];
     const int row0 = pl.seq_row0[s], T = pl.seq_rows[s];
-    const int g = Hq / Hkv, G = T * g;
-    const int m = lane & 15, q = lane >> 4;
+    const int G = T * g;
     const int32_t *btr = bt + (size_t)pl.seq_bt[s] * max_blocks;
 
     // Q fragments (B operands) go to LDS once, as [qt][ks][lane]; wave w stages k-step w.
@@ -364,15 +369,13 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     }
     const int direct = pl.item_direct[item];
     const int slot = pl.item_part[item];
-    // Causal stagger (prefill chunks): row t of the sequence ends T-1-t positions before its last row.
-    // Groups below n_clean are valid for every query.
-    const int max_stag = pl.causal ? T - 1 : 0;
-    const int n_clean = max(0, n_tok - (tok_end == kvlen ? max_stag : 0)) / kGrp;
+    // every stacked query of a decode step sits at the same position: all whole groups need no mask
+    const int n_clean = n_tok / kGrp;
     int stag[NA];
+#pragma unroll
+    for (int qt = 0; qt < NA; ++qt) stag[qt] = 0;
 
     if constexpr (NB == 0) {
-#pragma unroll
-        for (int qt = 0; qt < NA; ++qt) stag[qt] = pl.causal && tok_end == kvlen ? T - 1 - min((16 * qt + m) / g, T - 1) : 0;
         // the launch is sized for the largest stacked group of the call; a sequence with fewer
         // streams multiplies only the query tiles it has
         const int n_act = (G + 15) >> 4;
@@ -389,15 +392,13 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
         __syncthreads();
         if (w == 1) store_to_lds<NA>(st, lds, lane);
         __syncthreads();
-        if (w != 0) return;
-        merge_from_lds<NA>(st, lds, lane);
-        finish<NA>(st, 0, NA, G, g, row0, c, Hq, Hkv, direct, slot, pl.g_max, out, part_o, part_ml, lane);
+        if (w == 0) {
+            merge_from_lds<NA>(st, lds, lane);
+            finish<NA>(st, 0, NA, G, g, row0, c, Hq, Hkv, direct, slot, pl.g_max, out, part_o, part_ml, lane);
+        }
     } else {
         const int role = w >> 1, half = w & 1;  // role: which query tiles; half: which groups
         bf16x8 *ring = (bf16x8 *)lds;
-#pragma unroll
-        for (int qt = 0; qt < NA; ++qt)
-            stag[qt] = pl.causal && tok_end == kvlen ? T - 1 - min((16 * ((role ? NA : 0) + qt) + m) / g, T - 1) : 0;
         if (role == 0)
             shared_walk<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
         else
@@ -406,10 +407,13 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
         // each pair merges its two halves through its own LDS image
         if (half == 1) store_to_lds<NA>(st, lds + role * kImg, lane);
         __syncthreads();
-        if (half == 1) return;
-        merge_from_lds<NA>(st, lds + role * kImg, lane);
-        finish<NA>(st, role ? NA : 0, role ? NB : NA, G, g, row0, c, Hq, Hkv, direct, slot, pl.g_max, out, part_o, part_ml, lane);
+        if (half == 0) {
+            merge_from_lds<NA>(st, lds + role * kImg, lane);
+            finish<NA>(st, role ? NA : 0, role ? NB : NA, G, g, row0, c, Hq, Hkv, direct, slot, pl.g_max, out, part_o, part_ml, lane);
+        }
     }
+    __syncthreads();  // LDS (Q fragments, block ids, merge images) is reused by the next piece
+  }
 }
 
 // compute_group for a group that sits in LDS as fragments (src[i * 64]: K fragments i = 0..7, then
@@ -608,9 +612,9 @@ __global__ void __launch_bounds__(128) k_attn_merge(const float *__restrict__ pa
                                                     bf16_t *__restrict__ out, int Hq, int Hkv) {
     const int row = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
     const int s = row_seq[row];
+    const int g = Hq / Hkv, c = h / g;
     const int np = pl.seq_nparts[s];
     if (np <= 1) return;  // written directly by the attention kernel
-    const int g = Hq / Hkv, c = h / g;
     const int j = (row - pl.seq_row0[s]) * g + h % g;
     const int p0 = pl.seq_part0[s];
     float M = -INFINITY;
@@ -638,7 +642,7 @@ hipError_t launch_one(const void *q, const void *pool, const int32_t *bt, int ma
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_attn_decode<NA, NB>), dim3(pl.n_items * Hkv), dim3(256), shm, st, (const bf16_t *)q, (const bf16_t *)pool,
+    hipLaunchKernelGGL((k_attn_decode<NA, NB>), dim3(pl.n_wgs * Hkv), dim3(256), shm, st, (const bf16_t *)q, (const bf16_t *)pool,
                        bt, max_blocks, pl, (bf16_t *)out, part_o, part_ml, Hq, Hkv, scale_log2);
     return hipGetLastError();
 }
@@ -676,7 +680,7 @@ hipError_t launch_attn_prefill_mfma(const Dims &dm, const void *q, const void *p
 hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
                                    const AttnPlan &pl, void *out, float *part_o, float *part_ml, hipStream_t st) {
     if (pl.n_items <= 0) return hipSuccess;
-    if (pl.chunk > kAttnMaxChunk || pl.chunk % 128) return hipErrorInvalidValue;
+    if (pl.causal || pl.chunk > kAttnMaxChunk || pl.n_wgs <= 0) return hipErrorInvalidValue;
     float scale_log2 = kLog2e / sqrtf((float)dm.D);
     int nqt = (pl.g_max + 15) / 16;
     switch (nqt) {

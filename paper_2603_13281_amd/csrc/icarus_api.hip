@@ -55,7 +55,9 @@ struct icarus_ctx {
     icarus_lora_weights lora;
     Dims dm;
     int mode = 0;
-    int attn_chunk_override = 0;  // tokens per attention chunk; 0 = automatic (ICARUS_ATTN_CHUNK, for experiments)
+    int attn_chunk_override = 0;  // longest attention piece in tokens; 0 = automatic (ICARUS_ATTN_CHUNK, for experiments and tests)
+    int attn_wgs = 256;           // workgroups of the decode attention: Hkv per equal share of the work (ICARUS_ATTN_WGS)
+    int attn_weight_base = 128;   // per-token cost of a piece = this + stacked queries (ICARUS_ATTN_WEIGHT)
     char err[512];
     StageSlot slots[kSlots];
     int next_slot = 0;
@@ -103,15 +105,17 @@ struct WsLayout {
     size_t meta_ints, max_items, gemm_part, gemm_part_bytes;
 };
 
-constexpr int kAttnTargetWgs = 1280;  // decode attention: aim for about this many workgroups (5 per CU)
+constexpr int kAttnTargetWgs = 1280;  // decode attention: sizing bound for pieces and partial results
 constexpr int kAttnMaxChunk = 16384;  // tokens per attention chunk, at most (block ids of a chunk sit in LDS)
 constexpr int kAttnGMax = 80;         // largest stacked query group the MFMA attention covers
 constexpr int kGemmMaxSplits = 12;    // split-K slices of a narrow ICaRusLinear GEMM
 
 // Upper bounds used for sizing: chunks (= partial slots) of a call and its largest stacked group.
 size_t attn_max_items(const icarus_ctx *ctx, size_t seqs, size_t max_ctx) {
-    size_t by_target = (size_t)4 * kAttnTargetWgs / ctx->cfg.n_kv_heads, by_cap = seqs * (max_ctx / kAttnMaxChunk);
-    return std::max(by_target, by_cap) + seqs + 1;
+    // pieces of the decode plan: one per share, one more per sequence, and the cuts forced by the
+    // longest allowed piece
+    size_t cap = ctx->attn_chunk_override > 0 ? (size_t)std::max(32, ctx->attn_chunk_override / 32 * 32) : (size_t)kAttnMaxChunk;
+    return std::max<size_t>(4 * kAttnTargetWgs / ctx->cfg.n_kv_heads, (size_t)ctx->attn_wgs) + seqs * (2 + max_ctx / cap) + 1;
 }
 
 WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t max_ctx) {
@@ -122,9 +126,9 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t max_c
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     w.max_items = attn_max_items(ctx, seqs, max_ctx);
-    // metadata: 4 row arrays, the split plan (6 arrays per plan sequence, 4 per chunk); a prefill call
-    // has up to `rows` plan sequences of one chunk each
-    w.meta_ints = 4 * rows + 6 * std::max(rows, seqs) + 4 * std::max(rows, w.max_items) + 64;
+    // metadata: 4 row arrays and the attention plan (5 arrays per piece, the shares' first pieces, 6 arrays
+    // per plan sequence); a prefill call has up to `rows` plan sequences of one piece each
+    w.meta_ints = 4 * rows + 5 * std::max(rows, w.max_items) + (size_t)ctx->attn_wgs + 6 * std::max(rows, seqs) + 64;
     w.meta = take(w.meta_ints * 4);
     {
         size_t g = (size_t)c.n_q_heads / c.n_kv_heads;
@@ -252,94 +256,161 @@ icarus_status check_common_ptrs(icarus_ctx *ctx, const void *pool, const void *b
 }
 
 // ---- decode-attention split plan --------------------------------------------------------
-// Cuts every sequence's kv_len tokens into chunks of `chunk` tokens (a multiple of 128 chosen so
-// that chunks x kv-heads is about kAttnTargetWgs) and writes the plan's int32 arrays into the
-// host staging buffer `m` starting at int offset `at`; `dmeta` is the device address the buffer
-// will be copied to.  seq_row0 / seq_rows: rows of each sequence.  Returns ints used, 0 if the
-// matrix-core attention does not cover this call (then the generic kernel runs).
+// Builds the attention plan of a call into the host staging buffer `m` starting at int offset `at`;
+// `dmeta` is the device address the buffer will be copied to.  seq_row0 / seq_rows: rows of each
+// plan sequence.  hp->valid stays false if the matrix-core attention does not cover this call (then
+// the generic kernel runs).
 struct HostPlan {
     AttnPlan pl;
     bool valid = false, has_split = false;
     size_t ints = 0;
 };
 
-// seq_bt: block-table row of each plan sequence (null: sequence s reads row s).  causal: the rows of a
-// plan sequence are consecutive tokens of a prefill chunk (row t attends to kv_len - (rows-1-t) tokens);
-// such a sequence is never split, so the call is covered only if every kv_len fits one chunk.
+// Decode: the cached tokens of all sequences are laid on one line (weighted by a per-token cost that
+// grows mildly with the stacked group) and cut into equal shares, one per group of Hkv workgroups
+// (a workgroup per kv-head), so that every workgroup finishes at about the same time whatever the
+// mix of context lengths; pieces are multiples of 32 tokens and at most kAttnMaxChunk long.
+// Prefill (causal): seq_bt gives the block-table row of each plan sequence (a group of consecutive
+// chunk tokens; row t attends to kv_len - (rows-1-t) tokens); never split, so the call is covered
+// only if every kv_len fits one piece.
 void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t *dmeta, int S, const int32_t *kv_lens,
                      const int32_t *seq_row0, const int32_t *seq_rows, const int32_t *seq_bt, bool causal, size_t max_items,
                      HostPlan *hp) {
     AttnPlan *pl = &hp->pl;
+    *pl = AttnPlan{};
     hp->valid = false;
     hp->has_split = false;
     hp->ints = 0;
     const icarus_layer_config &c = ctx->cfg;
     if (ctx->mode != 0) return;
-    int g = c.n_q_heads / c.n_kv_heads, g_max = 0;
-    int64_t total = 0;
+    const int g = c.n_q_heads / c.n_kv_heads, Hkv = c.n_kv_heads;
+    int g_max = 0;
     for (int s = 0; s < S; ++s) {
         if (seq_rows[s] > 0 && kv_lens[s] <= 0) return;  // empty context: generic kernel writes zeros
         if (causal && kv_lens[s] > kAttnMaxChunk) return;
         g_max = std::max(g_max, seq_rows[s] * g);
-        if (seq_rows[s] > 0) total += kv_lens[s];
     }
     if (causal ? !attn_prefill_mfma_supported(ctx->dm, g_max) : (!attn_decode_mfma_supported(ctx->dm, g_max) || g_max > kAttnGMax)) return;
-    int64_t chunk = (total * c.n_kv_heads + kAttnTargetWgs - 1) / kAttnTargetWgs;
-    if (ctx->attn_chunk_override > 0) chunk = ctx->attn_chunk_override;
-    chunk = std::min<int64_t>(kAttnMaxChunk, std::max<int64_t>(ctx->attn_chunk_override > 0 ? 128 : 256, (chunk + 127) / 128 * 128));
-    if (causal) chunk = kAttnMaxChunk;
-    size_t n_items = 0;
+    const int32_t *d = dmeta + at;
+    if (causal) {
+        // one piece per token group (x kv-heads in the launch), longest contexts first
+        std::vector<int32_t> order;
+        for (int s = 0; s < S; ++s)
+            if (seq_rows[s] > 0) order.push_back(s);
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return kv_lens[a] > kv_lens[b]; });
+        const size_t n_items = order.size();
+        int32_t *item_seq = m + at, *seq_kvlen = item_seq + n_items, *row0 = seq_kvlen + S, *rows = row0 + S, *sbt = rows + S;
+        for (size_t i = 0; i < n_items; ++i) item_seq[i] = order[i];
+        for (int s = 0; s < S; ++s) {
+            seq_kvlen[s] = kv_lens[s];
+            row0[s] = seq_row0[s];
+            rows[s] = seq_rows[s];
+            sbt[s] = seq_bt ? seq_bt[s] : s;
+        }
+        pl->item_seq = d;
+        pl->seq_kvlen = d + n_items;
+        pl->seq_row0 = pl->seq_kvlen + S;
+        pl->seq_rows = pl->seq_row0 + S;
+        pl->seq_bt = pl->seq_rows + S;
+        pl->n_items = (int)n_items;
+        pl->chunk = kAttnMaxChunk;
+        pl->g_max = g_max;
+        pl->causal = 1;
+        hp->ints = n_items + 4 * (size_t)S;
+        hp->valid = n_items > 0;
+        return;
+    }
+    // ---- decode: equal shares of the weighted work line
+    auto weight = [&](int s) { return (int64_t)(ctx->attn_weight_base + seq_rows[s] * g); };  // cost of one cached token
+    int64_t total = 0, tokens = 0;
     for (int s = 0; s < S; ++s)
-        if (seq_rows[s] > 0) n_items += (size_t)((kv_lens[s] + chunk - 1) / chunk);
-    if (n_items > (causal ? (size_t)INT32_MAX : max_items)) return;  // partial slots (a causal plan has no splits)
-    int32_t *item_seq = m + at, *item_begin = item_seq + n_items, *item_part = item_begin + n_items,
-            *item_direct = item_part + n_items, *seq_kvlen = item_direct + n_items, *row0 = seq_kvlen + S,
-            *rows = row0 + S, *part0 = rows + S, *nparts = part0 + S, *sbt = nparts + S;
-    for (int s = 0; s < S; ++s) sbt[s] = seq_bt ? seq_bt[s] : s;
-    // Workgroups start in item order: longest chunks first, so the short tail chunks fill the gaps
-    // at the end of the launch.  Partial slots stay contiguous per sequence.
-    struct Item { int64_t cost; int32_t s, p; };
-    std::vector<Item> items;
-    items.reserve(n_items);
-    size_t slot = 0;
+        if (seq_rows[s] > 0) {
+            total += (int64_t)kv_lens[s] * weight(s);
+            tokens += kv_lens[s];
+        }
+    if (tokens == 0) return;
+    const int cap = ctx->attn_chunk_override > 0 ? std::max(32, ctx->attn_chunk_override / 32 * 32) : kAttnMaxChunk;  // longest piece
+    int n_wgs = (int)std::max<int64_t>(1, std::min<int64_t>(std::max(1, ctx->attn_wgs / Hkv), tokens / 256));
+    struct Piece { int32_t s, begin, len, wg; };
+    std::vector<Piece> pieces;
+    int wg = 0;
+    int64_t remaining = total;                          // weighted work not yet handed out
+    int64_t room = (remaining + n_wgs - 1) / n_wgs;     // ... and what the current share can still take
     for (int s = 0; s < S; ++s) {
-        int np = seq_rows[s] > 0 ? (int)((kv_lens[s] + chunk - 1) / chunk) : 0;
+        if (seq_rows[s] <= 0) continue;
+        const int64_t wt = weight(s);
+        int begin = 0;
+        while (begin < kv_lens[s]) {
+            if (wg < n_wgs - 1 && room < 64 * wt) {
+                // not worth a piece: the next share starts, with an equal part of what is left
+                ++wg;
+                room = (remaining + (n_wgs - wg) - 1) / (n_wgs - wg);
+            }
+            int left = kv_lens[s] - begin;
+            int64_t fit = wg < n_wgs - 1 ? room / wt : (int64_t)left;  // the last share takes whatever remains
+            int len = (int)std::min<int64_t>({(int64_t)left, (int64_t)cap, std::max<int64_t>(32, fit / 32 * 32)});
+            if (len < left) len = std::max(32, len / 32 * 32);  // inner boundaries on whole 32-token groups
+            pieces.push_back({s, begin, len, wg});
+            begin += len;
+            room -= (int64_t)len * wt;
+            remaining -= (int64_t)len * wt;
+        }
+    }
+    n_wgs = wg + 1;
+    const size_t n_items = pieces.size();
+    if (n_items > max_items) return;
+    int32_t *item_seq = m + at, *item_begin = item_seq + n_items, *item_len = item_begin + n_items,
+            *item_part = item_len + n_items, *item_direct = item_part + n_items, *wg_first = item_direct + n_items,
+            *seq_kvlen = wg_first + n_wgs + 1, *row0 = seq_kvlen + S, *rows = row0 + S, *sbt = rows + S, *part0 = sbt + S,
+            *nparts = part0 + S;
+    for (int s = 0; s < S; ++s) {
         seq_kvlen[s] = kv_lens[s];
         row0[s] = seq_row0[s];
         rows[s] = seq_rows[s];
-        part0[s] = (int32_t)slot;
-        nparts[s] = np;
-        slot += (size_t)np;
-        for (int p = 0; p < np; ++p) {
-            int64_t len = std::min<int64_t>(chunk, kv_lens[s] - p * chunk);
-            items.push_back({len * (8 + seq_rows[s] * g), s, p});
+        sbt[s] = seq_bt ? seq_bt[s] : s;
+        part0[s] = 0;
+        nparts[s] = 0;
+    }
+    int max_len = 0;
+    for (size_t i = 0; i < n_items; ++i) {  // pieces of one sequence are consecutive
+        const Piece &e = pieces[i];
+        if (nparts[e.s] == 0) part0[e.s] = (int32_t)i;
+        ++nparts[e.s];
+        item_seq[i] = e.s;
+        item_begin[i] = e.begin;
+        item_len[i] = e.len;
+        item_part[i] = (int32_t)i;
+        max_len = std::max(max_len, (int)e.len);
+    }
+    for (size_t i = 0; i < n_items; ++i) {
+        item_direct[i] = nparts[pieces[i].s] == 1;
+        if (nparts[pieces[i].s] > 1) hp->has_split = true;
+    }
+    {   // first piece of each share (pieces are in share order)
+        size_t i = 0;
+        for (int b = 0; b <= n_wgs; ++b) {
+            while (i < n_items && pieces[i].wg < b) ++i;
+            wg_first[b] = (int32_t)i;
         }
-        if (np > 1) hp->has_split = true;
     }
-    std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) { return a.cost > b.cost; });
-    for (size_t it = 0; it < n_items; ++it) {
-        const Item &e = items[it];
-        item_seq[it] = e.s;
-        item_begin[it] = (int32_t)(e.p * chunk);
-        item_part[it] = part0[e.s] + e.p;
-        item_direct[it] = nparts[e.s] == 1;
-    }
-    const int32_t *d = dmeta + at;
     pl->item_seq = d;
     pl->item_begin = d + n_items;
-    pl->item_part = d + 2 * n_items;
-    pl->item_direct = d + 3 * n_items;
-    pl->seq_kvlen = d + 4 * n_items;
+    pl->item_len = d + 2 * n_items;
+    pl->item_part = d + 3 * n_items;
+    pl->item_direct = d + 4 * n_items;
+    pl->wg_first = d + 5 * n_items;
+    pl->seq_kvlen = pl->wg_first + n_wgs + 1;
     pl->seq_row0 = pl->seq_kvlen + S;
     pl->seq_rows = pl->seq_row0 + S;
-    pl->seq_part0 = pl->seq_rows + S;
+    pl->seq_bt = pl->seq_rows + S;
+    pl->seq_part0 = pl->seq_bt + S;
     pl->seq_nparts = pl->seq_part0 + S;
-    pl->seq_bt = pl->seq_nparts + S;
     pl->n_items = (int)n_items;
-    pl->chunk = (int)chunk;
+    pl->n_wgs = n_wgs;
+    pl->chunk = max_len;
     pl->g_max = g_max;
-    pl->causal = causal ? 1 : 0;
-    hp->ints = 4 * n_items + 6 * (size_t)S;
+    pl->causal = 0;
+    hp->ints = 5 * n_items + (size_t)n_wgs + 1 + 6 * (size_t)S;
     hp->valid = n_items > 0;
 }
 
@@ -590,6 +661,8 @@ icarus_status icarus_create(const icarus_layer_config *cfg, const icarus_base_we
     dm.M = c.n_models; dm.r = c.lora_rank; dm.bf16 = c.dtype == ICARUS_BF16; dm.qk_norm = c.qk_norm != 0;
     dm.theta = c.rope_theta; dm.eps = (float)c.rms_eps; dm.lora_scale = (float)c.lora_scale;
     if (const char *e = getenv("ICARUS_ATTN_CHUNK")) ctx->attn_chunk_override = atoi(e);
+    if (const char *e = getenv("ICARUS_ATTN_WGS")) ctx->attn_wgs = std::max(1, atoi(e));
+    if (const char *e = getenv("ICARUS_ATTN_WEIGHT")) ctx->attn_weight_base = std::max(1, atoi(e));
     *out = ctx;
     return ICARUS_OK;
 }

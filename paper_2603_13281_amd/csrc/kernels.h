@@ -57,20 +57,27 @@ hipError_t launch_bench_copy(const void *src, void *dst, size_t bytes, hipStream
 hipError_t launch_bench_mfma(float *out, int waves, int iters, hipStream_t st);
 
 // ---- matrix-core kernels (bf16 storage) ------------------------------------------------------
-// Host-built split plan of the decode attention: a sequence's cached tokens are cut into chunks
-// of `chunk` tokens; one workgroup per (chunk, kv-head).  All arrays are device int32.
+// Host-built plan of the attention kernels.  All arrays are device int32.
+// Decode (causal = 0): the call's work -- the cached tokens of every sequence -- is laid on one line
+// and cut into n_wgs equal shares; share b is walked by Hkv workgroups (one per kv-head), each over
+// the pieces [wg_first[b], wg_first[b+1]), a piece being a token range of one sequence.  Piece
+// boundaries are multiples of 32 tokens.  A sequence cut into several pieces leaves one partial
+// result per piece and kv-head.
+// Prefill (causal = 1): one piece per token group (x kv-heads in the launch), never split.
 struct AttnPlan {
-    const int32_t *item_seq;     // [n_items] sequence of the chunk
-    const int32_t *item_begin;   // [n_items] first token of the chunk
-    const int32_t *item_part;    // [n_items] partial-result slot of the chunk
-    const int32_t *item_direct;  // [n_items] 1: the sequence has a single chunk, write the final output
+    const int32_t *item_seq;     // [n_items] plan sequence of the piece
+    const int32_t *item_begin;   // [n_items] first token of the piece (decode)
+    const int32_t *item_len;     // [n_items] tokens of the piece (decode)
+    const int32_t *item_part;    // [n_items] partial-result slot of the piece (decode)
+    const int32_t *item_direct;  // [n_items] 1: the piece is its whole sequence: write the final output (decode)
+    const int32_t *wg_first;     // [n_wgs + 1] first piece of each share (decode)
     const int32_t *seq_kvlen;    // [S] tokens to attend to
     const int32_t *seq_row0;     // [S] first row of the sequence
     const int32_t *seq_rows;     // [S] rows (stacked streams) of the sequence
-    const int32_t *seq_part0;    // [S] first partial slot
-    const int32_t *seq_nparts;   // [S] number of chunks
+    const int32_t *seq_part0;    // [S] first partial slot (decode)
+    const int32_t *seq_nparts;   // [S] number of pieces (decode)
     const int32_t *seq_bt;       // [S] row of the block table the sequence reads
-    int n_items, chunk, g_max;   // g_max: largest stacked group (rows * Hq/Hkv) in the call
+    int n_items, n_wgs, chunk, g_max;  // n_wgs: shares; chunk: longest piece; g_max: largest stacked group (rows * Hq/Hkv)
     int causal;                  // 1: row t of a sequence attends to kv_len - (rows - 1 - t) tokens (prefill)
 };
 // ICaRusLinear GEMM on matrix cores.  Y = X W^T (+ T Bcat^T), see gemm_mfma.hip.
