@@ -202,6 +202,53 @@ class Oracle:
         return out
 
 
+class OracleStack:
+    """L layers + token embedding + final norm + LM head (Alg. 3 outer loop; Alg. 1 for the prompt).
+
+    layers: list of Oracle (same shape).  embed, lm_head [vocab, d_model]; final_norm [d_model].
+    Every layer has its own pool; all share the block tables.  Only orchestration lives here: the
+    embedding lookup is an index operation, every number comes from the C file.
+    """
+
+    def __init__(self, layers, embed, final_norm, lm_head):
+        self.layers = list(layers)
+        self.cfg = self.layers[0].cfg
+        self.embed, self.final_norm, self.lm_head = _f32(embed), _f32(final_norm), _f32(lm_head)
+        self.vocab = self.lm_head.shape[0]
+
+    def new_pools(self):
+        return [l.new_pool() for l in self.layers]
+
+    def _head(self, x):
+        x = np.ascontiguousarray(x, dtype=np.float64)
+        R, d = x.shape
+        logits = np.empty((R, self.vocab), dtype=np.float64)
+        tokens = np.empty(R, dtype=np.int32)
+        lib().orc_lm_head(_p(x), C.c_int(R), C.c_int(d), _p(self.final_norm), C.c_double(self.cfg.rms_eps),
+                          _p(self.lm_head), C.c_int(self.vocab), _p(logits), _p(tokens))
+        return logits, tokens
+
+    def decode(self, pools, block_tables, ctx_lens, row_seq, row_model, seq_tokens):
+        """One token step.  Every row of sequence s embeds seq_tokens[s] (the streams differ from layer 1
+        on).  Returns (logits [R, vocab], tokens [R], slots [S])."""
+        x = self.embed[np.asarray(seq_tokens)[np.asarray(row_seq)]]
+        slots = None
+        for layer, pool in zip(self.layers, pools):
+            x, slots = layer.decode_step(pool, block_tables, ctx_lens, row_seq, row_model, x)   # rounded to storage
+        logits, tokens = self._head(x)
+        return logits, tokens, slots
+
+    def prefill(self, pools, block_tables, ctx_lens, chunk_lens, tokens):
+        """The prompt chunk through the frozen encoder of every layer.  Returns (logits [S, vocab],
+        first tokens [S]) taken at the last chunk token of each sequence: the first generated token
+        comes from the base model (Alg. 1)."""
+        x = self.embed[np.asarray(tokens)]
+        for layer, pool in zip(self.layers, pools):
+            x, _ = layer.prefill(pool, block_tables, ctx_lens, chunk_lens, x)
+        last = np.cumsum(np.asarray(chunk_lens)) - 1
+        return self._head(x[last])
+
+
 # -- primitives exposed for the pin tests ------------------------------------
 
 def round_bf16(x) -> np.ndarray:

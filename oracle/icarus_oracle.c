@@ -413,3 +413,23 @@ int orc_prefill(const orc_config *c, const orc_base *b, float *pool, const int32
     }
     return 0;
 }
+
+/* ---- layer stack: final norm, LM head, greedy token ------------------------
+ * The outer loop of Alg. 3 (and the last lines of Alg. 1): after the last layer the
+ * hidden row goes through the final RMSNorm (base weight) and the LM head; greedy
+ * sampling takes the first index of the largest logit.
+ * x [R, d] (double, already rounded to storage by the last layer), logits [R, vocab]. */
+void orc_lm_head(const double *x, int R, int d, const float *w_norm, double eps, const float *W_lm, int vocab,
+                 double *logits, int32_t *tokens) {
+    double *xn = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int r = 0; r < R; ++r) {
+        orc_rmsnorm(x + (size_t)r * d, w_norm, eps, d, xn);
+        double *lg = logits + (size_t)r * vocab;
+        orc_linear(W_lm, vocab, d, xn, lg);
+        int best = 0;
+        for (int v = 1; v < vocab; ++v)
+            if (lg[v] > lg[best]) best = v;
+        tokens[r] = best;
+    }
+    free(xn);
+}

@@ -110,6 +110,20 @@ def make_lora(shape: LayerShape, seed: int = 0, zero_b: bool = False, std: float
     return lora
 
 
+def make_stack(shape: LayerShape, n_layers: int, vocab: int, seed: int = 0, zero_b: bool = False, lora_std: float = 0.02,
+               norm_ones: bool = False) -> dict:
+    """Weights of a stack of layers with token embedding, final norm and LM head (all seeded):
+    {"bases": [...], "loras": [...], "embed" [vocab, d], "final_norm" [d], "lm_head" [vocab, d]}."""
+    bases = [make_base(shape, seed=seed * 1000 + l, norm_ones=norm_ones) for l in range(n_layers)]
+    loras = [make_lora(shape, seed=seed * 1000 + l, zero_b=zero_b, std=lora_std) for l in range(n_layers)]
+    rng = np.random.default_rng(np.random.SeedSequence([seed, 9, n_layers, vocab]))
+    embed = to_storage(rng.standard_normal((vocab, shape.d_model), dtype=np.float32), shape.bf16)
+    lm_head = to_storage(rng.standard_normal((vocab, shape.d_model), dtype=np.float32) * np.float32(0.05), shape.bf16)
+    fn = np.ones(shape.d_model, dtype=np.float32) if norm_ones else \
+        to_storage(1.0 + 0.1 * rng.standard_normal(shape.d_model, dtype=np.float32), shape.bf16)
+    return {"bases": bases, "loras": loras, "embed": embed, "final_norm": fn, "lm_head": lm_head}
+
+
 def make_hidden(shape: LayerShape, n_rows: int, seed: int = 0, tag: int = 0) -> np.ndarray:
     rng = np.random.default_rng(np.random.SeedSequence([seed, 2, tag]))
     return to_storage(rng.standard_normal((n_rows, shape.d_model), dtype=np.float32), shape.bf16)
