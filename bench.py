@@ -164,12 +164,89 @@ def main_prefill(args):
     print(json.dumps(out))
 
 
+def main_stack(args):
+    """Layer stack: one step = icarus_stack_decode of the whole batch (embedding, every layer, final norm,
+    LM head, greedy token), the sequences' next tokens fed back on the device."""
+    import numpy as np
+    import torch
+    import oracle
+    import sampled
+    from paper_2603_13281_amd import workloads
+
+    K, W = min(args.steps, 50), min(args.warmup, 5)
+    wl = workloads.build_stack_workload(args.workload, "cuda:0", headroom=K + W + 24, verbose=True)
+    b, sh = wl.batch, wl.shape
+    S, R = b.S, b.R
+    tok = wl.seq_token.clone()
+
+    def step(i, want_logits=False):
+        return wl.stack.decode(wl.pools, wl.block_tables, wl.ctx_lens(i), b.row_seq, b.row_model, tok, seq_next=tok,
+                               want_logits=want_logits)
+
+    # parity sample + CPU baseline at step 0: one sequence through every layer and the LM head in the oracle
+    base = None
+    s0 = 0
+    ctx0 = wl.ctx_lens(0)
+    if not args.no_cpu_baseline:
+        prefixes = [sampled.kv_to_host(sh, p, b.block_tables[s0], int(ctx0[s0])) for p in wl.pools]
+        tok0 = int(tok[s0].item())
+    row_next, logits = step(0, want_logits=not args.no_cpu_baseline)
+    torch.cuda.synchronize()
+    if not args.no_cpu_baseline:
+        Bk = sh.block_size
+        nb = (int(ctx0[s0]) + 1 + Bk - 1) // Bk
+        cfg = sampled.oracle_config(sh, nb)
+        layers = [oracle.Oracle(cfg, bb, ll) for bb, ll in zip(wl.weights["bases"], wl.weights["loras"])]
+        orc = oracle.OracleStack(layers, wl.weights["embed"], wl.weights["final_norm"], wl.weights["lm_head"])
+        opools = orc.new_pools()
+        bt0 = np.arange(nb, dtype=np.int32)[None]
+        from helpers import fill_pool
+        for op, (Kp, Vp) in zip(opools, prefixes):
+            fill_pool(op, bt0[0], Kp, Vp)
+        rows = np.flatnonzero(b.row_seq == s0)
+        t0 = time.perf_counter()
+        want_lg, want_tok, _ = orc.decode(opools, bt0, [int(ctx0[s0])], np.zeros(len(rows), dtype=np.int32), b.row_model[rows], [tok0])
+        dt = time.perf_counter() - t0
+        got = logits[torch.from_numpy(rows).to(logits.device)].cpu().numpy().astype(np.float64)
+        scale = np.abs(want_lg).max()
+        err = np.abs(got - want_lg).max() / scale
+        assert err <= 2e-2, f"stack sample: logits off by {err:.3g} of their range"
+        got_tok = row_next.cpu().numpy()[rows]
+        for i in range(len(rows)):
+            assert want_lg[i, got_tok[i]] >= want_lg[i].max() - 4e-2 * scale, "stack sample: token not near the best logit"
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        base = {"value": (len(rows) - 1) / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                "sample": f"sequence {s0} ({len(rows)} rows, {int(ctx0[s0])} cached tokens) through {wl.n_layers} layers and the LM head, "
+                          f"{dt:.2f} s; GPU logits of these rows within {err:.2g} of the oracle's range", "seconds": dt}
+        log(f"[bench] cpu baseline: {base['value']:.3f} tok/s; sample parity ok (max logit error {err:.2g} of range)")
+    for i in range(W):
+        step(1 + i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(1 + W + i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / K
+    n_dec = b.n_decoder_rows
+    wbytes = wl.n_layers * sum(int(np.prod(v.shape)) for k, v in wl.weights["bases"][0].items() if v.ndim == 2) * 2 + wl.vocab * sh.d_model * 2
+    kvbytes = wl.n_layers * int((wl.ctx_lens(1 + W + K // 2).astype(np.int64) + 1).sum()) * sh.n_kv_heads * sh.head_dim * 2 * 2
+    out = {"metric": "decode tokens/s through a layer stack with LM head and greedy sampling", "value": n_dec / dt, "unit": "tokens/s",
+           "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": wl.description, "rows": R, "decoder_rows": n_dec, "sequences": S, "layers": wl.n_layers, "vocab": wl.vocab},
+           "roofline": {"bound": "hbm", "achieved": (wbytes + kvbytes) / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": (wbytes + kvbytes) / dt / 1e9 / HBM_PEAK_GBS, "traffic": None, "kernel": "whole token step",
+                        "algorithmic_bytes": wbytes + kvbytes},
+           "cpu_baseline": base}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c4", "c4-small"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c4", "c4-small", "stack", "stack-small"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-private-kv-baseline", action="store_true",
                     help="skip the conventional per-model-KV run of the same traffic (same kernels, M private caches)")
@@ -199,6 +276,8 @@ def main():
         del src, dst
     if args.workload.startswith("c4"):
         return main_prefill(args)
+    if args.workload.startswith("stack"):
+        return main_stack(args)
     t_build = time.perf_counter()
     wl = workloads.build_decode_workload(args.workload, dev, headroom=2 * (K + W) + 16, verbose=True)
     wl.layer.set_kernel_mode(args.kernel_mode)

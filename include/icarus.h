@@ -193,6 +193,48 @@ icarus_status icarus_bench_copy(const void *src, void *dst, size_t bytes, void *
  * measurements only: the bf16 MFMA rate this GPU sustains, beside the published peak. */
 icarus_status icarus_bench_mfma(float *out, int32_t waves, int32_t iters, void *stream);
 
+/* ---- Layer stack: the outer loop of Alg. 3 and, for the prompt, Alg. 1 --------------------------------------
+ * n_layers layer contexts of identical configuration, each with its own KV pool (all pools share the block
+ * tables), a token embedding, the final RMSNorm and the LM head (base weights: shared by all streams).
+ * A token step embeds each sequence's current token into all of its rows (the streams differ from layer 1
+ * on), runs the rows through every layer, applies final norm + LM head to every row and takes the greedy
+ * token (first index of the largest logit).  The prompt runs through the frozen encoder of every layer; the
+ * first generated token comes from the base model (Alg. 1, y_prefill).
+ * The stack borrows the layer contexts (they must outlive it and must not be used concurrently with it) and
+ * the device arrays embed [vocab, d_model], final_norm [d_model], lm_head [vocab, d_model] (storage dtype). */
+typedef struct icarus_stack icarus_stack;
+typedef struct icarus_stack_config {
+    int32_t n_layers;            /* >= 1 */
+    int32_t vocab;               /* a multiple of 8 */
+    icarus_ctx *const *layers;   /* host array [n_layers] */
+    const void *embed, *final_norm, *lm_head; /* device */
+} icarus_stack_config;
+
+icarus_status icarus_stack_create(const icarus_stack_config *cfg, icarus_stack **out);
+void icarus_stack_destroy(icarus_stack *st);
+const char *icarus_stack_last_error(const icarus_stack *st);
+/* Workspace for calls of at most max_rows rows, max_seqs sequences, max_ctx context tokens, of which at most
+ * max_logit_rows rows go through the LM head (decode: every row; prefill: one per sequence). */
+size_t icarus_stack_workspace_bytes(const icarus_stack *st, int32_t max_rows, int32_t max_seqs, int32_t max_ctx,
+                                    int32_t max_logit_rows);
+
+/* Prompt chunks (Alg. 1): as icarus_prefill_kv on every layer, rows = embeddings of `tokens` (host, [sum of
+ * chunk_lens]); kv_pools: host array of n_layers device pools.  next_token (device int32 [S]): greedy token
+ * of the base model after each sequence's last chunk token; logits (device float [S, vocab]) optional. */
+icarus_status icarus_stack_prefill(icarus_stack *st, void *const *kv_pools, const int32_t *block_tables, int32_t max_blocks,
+                                   int32_t S, const int32_t *ctx_lens, const int32_t *chunk_lens, const int32_t *tokens,
+                                   int32_t *next_token, float *logits, void *workspace, size_t workspace_bytes, void *stream);
+
+/* One token step (Alg. 3): as icarus_decode_step on every layer.  seq_token (device int32 [S]): the token
+ * each sequence decodes now.  row_next (device int32 [R]): greedy token of every row (an encoder row gives
+ * the base model's); seq_next (device int32 [S], optional): row_next of each sequence's last row -- with one
+ * decoder per sequence, the pair of the paper, the decoder's token; logits (device float [R, vocab]) optional.
+ * seq_next may alias seq_token. */
+icarus_status icarus_stack_decode(icarus_stack *st, void *const *kv_pools, const int32_t *block_tables, int32_t max_blocks,
+                                  int32_t S, const int32_t *ctx_lens, int32_t R, const int32_t *row_seq,
+                                  const int32_t *row_model, const int32_t *seq_token, int32_t *row_next, int32_t *seq_next,
+                                  float *logits, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,8 @@ STATUS = {0: "OK", 1: "INVALID_ARG", 2: "SHAPE", 3: "ALIGNMENT", 4: "MODEL_ID", 
 
 EXPORTS = ("icarus_create", "icarus_destroy", "icarus_last_error", "icarus_workspace_bytes",
            "icarus_validate_decode", "icarus_prefill_kv", "icarus_decode_step", "icarus_attn_shared_kv",
-           "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read", "icarus_bench_copy", "icarus_bench_mfma")
+           "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read", "icarus_bench_copy", "icarus_bench_mfma", "icarus_stack_create", "icarus_stack_destroy",
+           "icarus_stack_last_error", "icarus_stack_workspace_bytes", "icarus_stack_prefill", "icarus_stack_decode")
 
 PHASES = ("norm", "lora", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gateup", "gemm_down",
           "elementwise")
@@ -52,6 +53,11 @@ class _Base(C.Structure):
 
 class _Lora(C.Structure):
     _fields_ = [("A", C.c_void_p * NPROJ), ("B", C.c_void_p * NPROJ)]
+
+
+class _StackCfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("vocab", C.c_int32), ("layers", C.POINTER(C.c_void_p)),
+                ("embed", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)]
 
 
 def _load():
@@ -86,6 +92,18 @@ def _load():
     lib.icarus_bench_copy.argtypes = [vp, vp, sz, vp]
     lib.icarus_bench_mfma.restype = C.c_int
     lib.icarus_bench_mfma.argtypes = [vp, C.c_int32, C.c_int32, vp]
+    lib.icarus_stack_create.restype = C.c_int
+    lib.icarus_stack_create.argtypes = [C.POINTER(_StackCfg), C.POINTER(vp)]
+    lib.icarus_stack_destroy.restype = None
+    lib.icarus_stack_destroy.argtypes = [vp]
+    lib.icarus_stack_last_error.restype = C.c_char_p
+    lib.icarus_stack_last_error.argtypes = [vp]
+    lib.icarus_stack_workspace_bytes.restype = sz
+    lib.icarus_stack_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.icarus_stack_prefill.restype = C.c_int
+    lib.icarus_stack_prefill.argtypes = [vp, C.POINTER(vp), vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.icarus_stack_decode.restype = C.c_int
+    lib.icarus_stack_decode.argtypes = [vp, C.POINTER(vp), vp, C.c_int32, C.c_int32, vp, C.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     return lib
 
 
@@ -299,3 +317,81 @@ class IcarusLayer:
                                                _ptr(kv_lens), R, _ptr(row_seq), _ptr(out), _ptr(ws), ws.numel(),
                                                self._stream(q.device)))
         return out
+
+
+class IcarusStack:
+    """A stack of IcarusLayer contexts with token embedding, final norm and LM head (marshalling only).
+    layers: list of IcarusLayer (kept alive); embed, final_norm, lm_head: device tensors, storage dtype."""
+
+    def __init__(self, layers, embed, final_norm, lm_head):
+        self.layers = list(layers)
+        self._t = [embed.contiguous(), final_norm.contiguous(), lm_head.contiguous()]
+        self.vocab = int(lm_head.shape[0])
+        arr = (C.c_void_p * len(self.layers))(*[l._h for l in self.layers])
+        self._arr = arr
+        cfg = _StackCfg(len(self.layers), self.vocab, C.cast(arr, C.POINTER(C.c_void_p)), self._t[0].data_ptr(),
+                        self._t[1].data_ptr(), self._t[2].data_ptr())
+        h = C.c_void_p()
+        rc = _lib.icarus_stack_create(C.byref(cfg), C.byref(h))
+        if rc != 0:
+            raise IcarusError(rc, _lib.icarus_stack_last_error(None).decode())
+        self._h = h
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.icarus_stack_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc != 0:
+            raise IcarusError(rc, _lib.icarus_stack_last_error(self._h).decode())
+
+    def workspace_bytes(self, max_rows, max_seqs, max_ctx, max_logit_rows) -> int:
+        return int(_lib.icarus_stack_workspace_bytes(self._h, max_rows, max_seqs, max_ctx, max_logit_rows))
+
+    def _workspace(self, rows, seqs, max_ctx, logit_rows, device):
+        need = self.workspace_bytes(rows, seqs, max_ctx, logit_rows)
+        if self._ws is None or self._ws.numel() < need or self._ws.device != device:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=device)
+        return self._ws
+
+    @staticmethod
+    def _pools(kv_pools):
+        return (C.c_void_p * len(kv_pools))(*[p.data_ptr() for p in kv_pools])
+
+    def prefill(self, kv_pools, block_tables, ctx_lens, chunk_lens, tokens, want_logits=False):
+        """Returns (next_token [S] int32 device, logits [S, vocab] float32 device or None)."""
+        ctx_lens, chunk_lens, tokens = _host_i32(ctx_lens), _host_i32(chunk_lens), _host_i32(tokens)
+        S, max_blocks = block_tables.shape
+        dev = block_tables.device
+        R = int(chunk_lens.sum())
+        nxt = torch.empty(S, dtype=torch.int32, device=dev)
+        logits = torch.empty((S, self.vocab), dtype=torch.float32, device=dev) if want_logits else None
+        ws = self._workspace(R, S, int((ctx_lens + chunk_lens).max()) if S else 0, S, dev)
+        stream = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+        self._check(_lib.icarus_stack_prefill(self._h, self._pools(kv_pools), _ptr(block_tables), max_blocks, S, _ptr(ctx_lens),
+                                              _ptr(chunk_lens), _ptr(tokens), _ptr(nxt), _ptr(logits), _ptr(ws), ws.numel(), stream))
+        return nxt, logits
+
+    def decode(self, kv_pools, block_tables, ctx_lens, row_seq, row_model, seq_token, seq_next=None, want_logits=False):
+        """seq_token: device int32 [S].  Returns (row_next [R] int32 device, logits [R, vocab] or None);
+        seq_next (device int32 [S], may be seq_token itself) receives each sequence's last row's token."""
+        ctx_lens, row_seq, row_model = _host_i32(ctx_lens), _host_i32(row_seq), _host_i32(row_model)
+        S, max_blocks = block_tables.shape
+        dev = block_tables.device
+        R = len(row_seq)
+        row_next = torch.empty(R, dtype=torch.int32, device=dev)
+        logits = torch.empty((R, self.vocab), dtype=torch.float32, device=dev) if want_logits else None
+        ws = self._workspace(R, S, int(ctx_lens.max()) + 1 if S else 0, R, dev)
+        stream = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+        self._check(_lib.icarus_stack_decode(self._h, self._pools(kv_pools), _ptr(block_tables), max_blocks, S, _ptr(ctx_lens), R,
+                                             _ptr(row_seq), _ptr(row_model), _ptr(seq_token), _ptr(row_next), _ptr(seq_next),
+                                             _ptr(logits), _ptr(ws), ws.numel(), stream))
+        return row_next, logits

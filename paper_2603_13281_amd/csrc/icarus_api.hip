@@ -65,6 +65,14 @@ struct icarus_ctx {
     std::mutex mu;
 };
 
+struct icarus_stack {
+    std::vector<icarus_ctx *> layers;
+    int vocab = 0;
+    const void *embed = nullptr, *final_norm = nullptr, *lm_head = nullptr;
+    char err[512];
+    std::mutex mu;
+};
+
 namespace {
 
 icarus_status fail(icarus_ctx *ctx, icarus_status st, const char *fmt, ...) {
@@ -128,7 +136,8 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t max_c
     w.max_items = attn_max_items(ctx, seqs, max_ctx);
     // metadata: 4 row arrays and the attention plan (5 arrays per piece, the shares' first pieces, 6 arrays
     // per plan sequence); a prefill call has up to `rows` plan sequences of one piece each
-    w.meta_ints = 4 * rows + 5 * std::max(rows, w.max_items) + (size_t)ctx->attn_wgs + 6 * std::max(rows, seqs) + 64;
+    w.meta_ints = 4 * rows + 5 * std::max(rows, w.max_items) + (size_t)ctx->attn_wgs + 6 * std::max(rows, seqs) + 64 +
+                  rows + seqs;  // + what a layer stack stages with the call: prompt tokens, last row of each sequence
     w.meta = take(w.meta_ints * 4);
     {
         size_t g = (size_t)c.n_q_heads / c.n_kv_heads;
@@ -610,6 +619,211 @@ icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowM
     return ICARUS_OK;
 }
 
+// What a call needs once its host metadata is validated, laid out and on its way to the device:
+// workspace layout, row arrays, attention plan; `extra` (optional caller ints staged with the same
+// copy) lands at extra_dev.
+struct Prepared {
+    WsLayout L;
+    RowMeta rm;
+    HostPlan hp;
+    const int32_t *extra_dev = nullptr;
+};
+
+icarus_status prepare_decode(icarus_ctx *ctx, const void *kv_pool, const int32_t *block_tables, int32_t max_blocks, int32_t S,
+                             const int32_t *ctx_lens, int32_t R, const int32_t *row_seq, const int32_t *row_model, void *workspace,
+                             size_t workspace_bytes, hipStream_t st, const int32_t *extra, size_t n_extra, Prepared *pr) {
+    int max_ctx = 0;
+    for (int s = 0; s < S; ++s) max_ctx = std::max(max_ctx, ctx_lens[s] + 1);
+    pr->L = ws_layout(ctx, (size_t)R, (size_t)S, (size_t)max_ctx);
+    const WsLayout &L = pr->L;
+    icarus_status rc = check_common_ptrs(ctx, kv_pool, block_tables, workspace, workspace_bytes, L.total);
+    if (rc) return rc;
+    StageSlot *slot;
+    rc = stage_acquire(ctx, L.meta_ints * 4, &slot);
+    if (rc) return rc;
+    int32_t *m = (int32_t *)slot->host;
+    std::vector<int32_t> kvl((size_t)S), row0((size_t)S, 0), rows((size_t)S, 0);
+    for (int r = 0; r < R; ++r) {
+        int s = row_seq[r];
+        m[r] = s;
+        m[R + r] = row_model[r];
+        m[2 * R + r] = ctx_lens[s];
+        m[3 * R + r] = ctx_lens[s] + 1;
+        if (rows[s]++ == 0) row0[s] = r;
+    }
+    for (int s = 0; s < S; ++s) kvl[s] = ctx_lens[s] + 1;
+    char *ws = (char *)workspace;
+    const int32_t *dmeta = (const int32_t *)(ws + L.meta);
+    build_attn_plan(ctx, m, (size_t)4 * R, dmeta, S, kvl.data(), row0.data(), rows.data(), nullptr, false, L.max_items, &pr->hp);
+    size_t used = (size_t)4 * R + pr->hp.ints;
+    if (n_extra) {
+        memcpy(m + used, extra, n_extra * 4);
+        pr->extra_dev = dmeta + used;
+        used += n_extra;
+    }
+    rc = stage_commit(ctx, slot, ws + L.meta, used * 4, st);
+    if (rc) return rc;
+    pr->rm = RowMeta{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
+    return ICARUS_OK;
+}
+
+// Validates a prefill call's host metadata; *rows = total chunk tokens.
+icarus_status check_prefill(icarus_ctx *ctx, int32_t max_blocks, int32_t S, const int32_t *ctx_lens, const int32_t *chunk_lens, int *rows) {
+    const icarus_layer_config &c = ctx->cfg;
+    *rows = 0;
+    if (S < 0 || max_blocks < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "negative size");
+    if (S == 0) return ICARUS_OK;
+    if (!ctx_lens || !chunk_lens) return fail(ctx, ICARUS_ERR_INVALID_ARG, "null metadata array");
+    int64_t total = 0;
+    for (int s = 0; s < S; ++s) {
+        if (ctx_lens[s] < 0 || chunk_lens[s] < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "sequence %d: negative length", s);
+        int64_t end = (int64_t)ctx_lens[s] + chunk_lens[s];
+        if (end > c.max_position) return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: %lld tokens exceed max_position %d", s, (long long)end, c.max_position);
+        if ((end + c.block_size - 1) / c.block_size > max_blocks)
+            return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: %lld tokens need %lld blocks, table has %d", s, (long long)end,
+                        (long long)((end + c.block_size - 1) / c.block_size), max_blocks);
+        total += chunk_lens[s];
+    }
+    if (total > 65535) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "at most 65535 rows per call (got %lld)", (long long)total);
+    *rows = (int)total;
+    return ICARUS_OK;
+}
+
+icarus_status prepare_prefill(icarus_ctx *ctx, const void *kv_pool, const int32_t *block_tables, int32_t max_blocks, int32_t S,
+                              const int32_t *ctx_lens, const int32_t *chunk_lens, int R, bool want_attention, void *workspace,
+                              size_t workspace_bytes, hipStream_t st, const int32_t *extra, size_t n_extra, Prepared *pr) {
+    const icarus_layer_config &c = ctx->cfg;
+    int max_ctx = 0;
+    for (int s = 0; s < S; ++s) max_ctx = std::max(max_ctx, ctx_lens[s] + chunk_lens[s]);
+    pr->L = ws_layout(ctx, (size_t)R, (size_t)S, (size_t)max_ctx);
+    const WsLayout &L = pr->L;
+    icarus_status rc = check_common_ptrs(ctx, kv_pool, block_tables, workspace, workspace_bytes, L.total);
+    if (rc) return rc;
+    StageSlot *slot;
+    rc = stage_acquire(ctx, L.meta_ints * 4, &slot);
+    if (rc) return rc;
+    int32_t *m = (int32_t *)slot->host;
+    int r = 0;
+    for (int s = 0; s < S; ++s)
+        for (int i = 0; i < chunk_lens[s]; ++i, ++r) {
+            m[r] = s;
+            m[R + r] = -1;
+            m[2 * R + r] = ctx_lens[s] + i;
+            m[3 * R + r] = ctx_lens[s] + i + 1;
+        }
+    // Attention plan: the chunk's tokens are cut into groups of consecutive tokens whose stacked query
+    // heads fill one workgroup of the prefill attention; each group is one plan sequence with a causal
+    // stagger.
+    char *ws = (char *)workspace;
+    const int32_t *dmeta = (const int32_t *)(ws + L.meta);
+    if (want_attention) {
+        int g = c.n_q_heads / c.n_kv_heads, tq = std::max(1, attn_prefill_group_queries() / g);
+        std::vector<int32_t> vkv, vrow0, vrows, vbt;
+        int row = 0;
+        for (int s = 0; s < S; ++s) {
+            for (int t0 = 0; t0 < chunk_lens[s]; t0 += tq) {
+                int n = std::min(tq, chunk_lens[s] - t0);
+                vkv.push_back(ctx_lens[s] + t0 + n);
+                vrow0.push_back(row + t0);
+                vrows.push_back(n);
+                vbt.push_back(s);
+            }
+            row += chunk_lens[s];
+        }
+        build_attn_plan(ctx, m, (size_t)4 * R, dmeta, (int)vkv.size(), vkv.data(), vrow0.data(), vrows.data(), vbt.data(), true,
+                        L.max_items, &pr->hp);
+    }
+    size_t used = (size_t)4 * R + pr->hp.ints;
+    if (n_extra) {
+        memcpy(m + used, extra, n_extra * 4);
+        pr->extra_dev = dmeta + used;
+        used += n_extra;
+    }
+    rc = stage_commit(ctx, slot, ws + L.meta, used * 4, st);
+    if (rc) return rc;
+    pr->rm = RowMeta{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
+    return ICARUS_OK;
+}
+
+// ---- layer stack: workspace after the layer workspace, and the launch sequence ------------------------
+struct StackLayout {
+    size_t xa, xb, xn, logits, tok, total;
+};
+
+StackLayout stack_layout_from(const icarus_stack *st, const WsLayout &L, size_t rows, size_t logit_rows) {
+    const icarus_layer_config &c = st->layers[0]->cfg;
+    size_t es = c.dtype == ICARUS_BF16 ? 2 : 4;
+    StackLayout s{};
+    size_t off = align_up(L.total, 256);
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    s.xa = take(rows * c.d_model * es);
+    s.xb = take(rows * c.d_model * es);
+    s.xn = take(logit_rows * c.d_model * es * 2);  // gathered rows, then their normalised form
+    s.logits = take(logit_rows * (size_t)st->vocab * 4);
+    s.tok = take(logit_rows * 4);
+    s.total = off;
+    return s;
+}
+
+StackLayout stack_layout(const icarus_stack *st, size_t rows, size_t seqs, size_t max_ctx, size_t logit_rows) {
+    return stack_layout_from(st, ws_layout(st->layers[0], rows, seqs, max_ctx), rows, logit_rows);
+}
+
+icarus_status stack_fail(icarus_stack *st, icarus_status rc, const char *msg) {
+    snprintf(st->err, sizeof st->err, "%s", msg);
+    return rc;
+}
+
+#define STACK_TRY(call) do { hipError_t e__ = (call); if (e__ != hipSuccess) return stack_fail(st, ICARUS_ERR_HIP, hipGetErrorString(e__)); } while (0)
+
+// tok / tok_idx: the token of row r is tok[tok_idx ? tok_idx[r] : r].  head_rows: rows that go through
+// the LM head (null: all R rows, n_head = R).  next_out [n_head]; pick [n_pick] / seq_next: optional
+// seq_next[s] = next_out[pick[s]].
+icarus_status run_stack(icarus_stack *st, char *ws, const StackLayout &SL, const Prepared &pr, void *const *kv_pools,
+                        const int32_t *bt, int max_blocks, int R, bool decode, const int32_t *tok, const int32_t *tok_idx,
+                        const int32_t *head_rows, int n_head, int32_t *next_out, const int32_t *pick, int n_pick, int32_t *seq_next,
+                        float *logits, hipStream_t s) {
+    icarus_ctx *c0 = st->layers[0];
+    const Dims &dm = c0->dm;
+    const size_t es = dm.bf16 ? 2 : 4;
+    const int row_bytes = (int)(dm.d * es);
+    void *xa = ws + SL.xa, *xb = ws + SL.xb;
+    for (size_t l = 0; l < st->layers.size(); ++l) {
+        icarus_status rc = check_common_ptrs(st->layers[l], kv_pools[l], bt, ws, SL.total, 0);
+        if (rc) return stack_fail(st, rc, st->layers[l]->err);
+    }
+    STACK_TRY(launch_embed_rows(st->embed, tok, tok_idx, xa, R, row_bytes, s));
+    for (size_t l = 0; l < st->layers.size(); ++l) {
+        icarus_status rc = run_layer(st->layers[l], ws, pr.L, pr.rm, &pr.hp, R, decode, false, decode ? 0 : 1, kv_pools[l], bt, max_blocks,
+                                     xa, xb, nullptr, s);
+        if (rc) return stack_fail(st, rc, st->layers[l]->err);
+        std::swap(xa, xb);
+    }
+    // final norm + LM head on the chosen rows, greedy token
+    char *xg = ws + SL.xn, *xn = xg + (size_t)n_head * row_bytes;
+    const void *xh = xa;
+    if (head_rows) {
+        STACK_TRY(launch_gather_rows(xa, head_rows, xg, n_head, row_bytes, s));
+        xh = xg;
+    }
+    float *lg = logits ? logits : (float *)(ws + SL.logits);
+    if (layer_mfma_supported(c0) && gemm_mfma_supported(dm, dm.d)) {
+        STACK_TRY(launch_norm_shrink(dm, xh, st->final_norm, xn, n_head, dm.d, nullptr, nullptr, nullptr, nullptr, nullptr, 0, s));
+        GemmArgs g{};
+        g.X = (const bf16_raw *)xn; g.ldx = dm.d; g.R = n_head; g.K = dm.d;
+        g.W[0] = (const bf16_raw *)st->lm_head; g.n_seg[0] = st->vocab; g.nseg = 1;
+        g.mode = GEMM_PLAIN; g.epi = EPI_F32; g.splits = 1;
+        g.Y = lg; g.ldy = st->vocab;
+        STACK_TRY(launch_gemm_mfma(g, s));
+    } else {
+        STACK_TRY(launch_rmsnorm(dm, xh, st->final_norm, xn, n_head, dm.d, s));
+        STACK_TRY(launch_gemm_generic(dm, xn, dm.d, st->lm_head, n_head, st->vocab, dm.d, lg, st->vocab, s));
+    }
+    STACK_TRY(launch_argmax(lg, n_head, st->vocab, next_out, s));
+    if (seq_next && pick) STACK_TRY(launch_pick_rows(next_out, pick, seq_next, n_pick, s));
+    return ICARUS_OK;
+}
+
 }  // namespace
 
 // =====================================================================================
@@ -749,34 +963,12 @@ icarus_status icarus_decode_step(icarus_ctx *ctx, void *kv_pool, const int32_t *
     if (R == 0) return ICARUS_OK;
     if (!x_in || !x_out) return fail(ctx, ICARUS_ERR_INVALID_ARG, "x_in / x_out is null");
     if (!aligned16(x_in) || !aligned16(x_out) || (slot_out && !aligned16(slot_out))) return fail(ctx, ICARUS_ERR_ALIGNMENT, "x_in, x_out and slot_out must be 16-byte aligned");
-    int max_ctx = 0;
-    for (int s = 0; s < S; ++s) max_ctx = std::max(max_ctx, ctx_lens[s] + 1);
-    WsLayout L = ws_layout(ctx, (size_t)R, (size_t)S, (size_t)max_ctx);
-    rc = check_common_ptrs(ctx, kv_pool, block_tables, workspace, workspace_bytes, L.total);
+    Prepared pr;
+    rc = prepare_decode(ctx, kv_pool, block_tables, max_blocks, S, ctx_lens, R, row_seq, row_model, workspace, workspace_bytes,
+                        (hipStream_t)stream, nullptr, 0, &pr);
     if (rc) return rc;
-    hipStream_t st = (hipStream_t)stream;
-    StageSlot *slot;
-    rc = stage_acquire(ctx, L.meta_ints * 4, &slot);
-    if (rc) return rc;
-    int32_t *m = (int32_t *)slot->host;
-    std::vector<int32_t> kvl((size_t)S), row0((size_t)S, 0), rows((size_t)S, 0);
-    for (int r = 0; r < R; ++r) {
-        int s = row_seq[r];
-        m[r] = s;
-        m[R + r] = row_model[r];
-        m[2 * R + r] = ctx_lens[s];
-        m[3 * R + r] = ctx_lens[s] + 1;
-        if (rows[s]++ == 0) row0[s] = r;
-    }
-    for (int s = 0; s < S; ++s) kvl[s] = ctx_lens[s] + 1;
-    char *ws = (char *)workspace;
-    const int32_t *dmeta = (const int32_t *)(ws + L.meta);
-    HostPlan hp;
-    build_attn_plan(ctx, m, (size_t)4 * R, dmeta, S, kvl.data(), row0.data(), rows.data(), nullptr, false, L.max_items, &hp);
-    rc = stage_commit(ctx, slot, ws + L.meta, ((size_t)4 * R + hp.ints) * 4, st);
-    if (rc) return rc;
-    RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
-    return run_layer(ctx, ws, L, rm, &hp, R, true, false, 0, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
+    return run_layer(ctx, (char *)workspace, pr.L, pr.rm, &pr.hp, R, true, false, 0, kv_pool, block_tables, max_blocks, x_in, x_out,
+                     slot_out, (hipStream_t)stream);
 }
 
 icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *block_tables, int32_t max_blocks, int32_t S,
@@ -784,70 +976,18 @@ icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *b
                                 int64_t *slot_out, void *workspace, size_t workspace_bytes, void *stream) {
     if (!ctx) return ICARUS_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> lk(ctx->mu);
-    const icarus_layer_config &c = ctx->cfg;
-    if (S < 0 || max_blocks < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "negative size");
-    if (S == 0) return ICARUS_OK;
-    if (!ctx_lens || !chunk_lens) return fail(ctx, ICARUS_ERR_INVALID_ARG, "null metadata array");
-    int64_t total = 0;
-    int max_ctx = 0;
-    for (int s = 0; s < S; ++s) {
-        if (ctx_lens[s] < 0 || chunk_lens[s] < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "sequence %d: negative length", s);
-        int64_t end = (int64_t)ctx_lens[s] + chunk_lens[s];
-        if (end > c.max_position) return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: %lld tokens exceed max_position %d", s, (long long)end, c.max_position);
-        if ((end + c.block_size - 1) / c.block_size > max_blocks)
-            return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: %lld tokens need %lld blocks, table has %d", s, (long long)end,
-                        (long long)((end + c.block_size - 1) / c.block_size), max_blocks);
-        total += chunk_lens[s];
-        max_ctx = std::max<int>(max_ctx, (int)end);
-    }
-    if (total == 0) return ICARUS_OK;
-    if (total > 65535) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "at most 65535 rows per call (got %lld)", (long long)total);
+    int R = 0;
+    icarus_status rc = check_prefill(ctx, max_blocks, S, ctx_lens, chunk_lens, &R);
+    if (rc) return rc;
+    if (R == 0) return ICARUS_OK;
     if (!x_in) return fail(ctx, ICARUS_ERR_INVALID_ARG, "x_in is null");
     if (!aligned16(x_in) || (x_out && !aligned16(x_out)) || (slot_out && !aligned16(slot_out))) return fail(ctx, ICARUS_ERR_ALIGNMENT, "x_in, x_out and slot_out must be 16-byte aligned");
-    int R = (int)total;
-    WsLayout L = ws_layout(ctx, (size_t)R, (size_t)S, (size_t)max_ctx);
-    icarus_status rc = check_common_ptrs(ctx, kv_pool, block_tables, workspace, workspace_bytes, L.total);
+    Prepared pr;
+    rc = prepare_prefill(ctx, kv_pool, block_tables, max_blocks, S, ctx_lens, chunk_lens, R, x_out != nullptr, workspace,
+                         workspace_bytes, (hipStream_t)stream, nullptr, 0, &pr);
     if (rc) return rc;
-    hipStream_t st = (hipStream_t)stream;
-    StageSlot *slot;
-    rc = stage_acquire(ctx, L.meta_ints * 4, &slot);
-    if (rc) return rc;
-    int32_t *m = (int32_t *)slot->host;
-    int r = 0;
-    for (int s = 0; s < S; ++s)
-        for (int i = 0; i < chunk_lens[s]; ++i, ++r) {
-            m[r] = s;
-            m[R + r] = -1;
-            m[2 * R + r] = ctx_lens[s] + i;
-            m[3 * R + r] = ctx_lens[s] + i + 1;
-        }
-    // Attention plan: the chunk's tokens are cut into groups of consecutive tokens whose stacked query
-    // heads fill one workgroup of the prefill attention; each group is one plan sequence with a causal
-    // stagger.
-    char *ws = (char *)workspace;
-    const int32_t *dmeta = (const int32_t *)(ws + L.meta);
-    HostPlan hp;
-    if (x_out) {
-        int g = c.n_q_heads / c.n_kv_heads, tq = std::max(1, attn_prefill_group_queries() / g);
-        std::vector<int32_t> vkv, vrow0, vrows, vbt;
-        int row = 0;
-        for (int s = 0; s < S; ++s) {
-            for (int t0 = 0; t0 < chunk_lens[s]; t0 += tq) {
-                int n = std::min(tq, chunk_lens[s] - t0);
-                vkv.push_back(ctx_lens[s] + t0 + n);
-                vrow0.push_back(row + t0);
-                vrows.push_back(n);
-                vbt.push_back(s);
-            }
-            row += chunk_lens[s];
-        }
-        build_attn_plan(ctx, m, (size_t)4 * R, dmeta, (int)vkv.size(), vkv.data(), vrow0.data(), vrows.data(), vbt.data(), true,
-                        L.max_items, &hp);
-    }
-    rc = stage_commit(ctx, slot, ws + L.meta, ((size_t)4 * R + hp.ints) * 4, st);
-    if (rc) return rc;
-    RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
-    return run_layer(ctx, ws, L, rm, &hp, R, false, x_out == nullptr, 1, kv_pool, block_tables, max_blocks, x_in, x_out, slot_out, st);
+    return run_layer(ctx, (char *)workspace, pr.L, pr.rm, &pr.hp, R, false, x_out == nullptr, 1, kv_pool, block_tables, max_blocks, x_in,
+                     x_out, slot_out, (hipStream_t)stream);
 }
 
 icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *kv_pool, const int32_t *block_tables,
@@ -899,6 +1039,106 @@ icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *
     if (rc) return rc;
     RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
     return run_decode_attention(ctx, ws, L, rm, &hp, q, kv_pool, block_tables, max_blocks, out, R, st);
+}
+
+// ---- layer stack -----------------------------------------------------------------------------------------
+
+icarus_status icarus_stack_create(const icarus_stack_config *cfg, icarus_stack **out) {
+    if (!cfg || !out) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "null argument");
+    *out = nullptr;
+    if (cfg->n_layers < 1 || !cfg->layers) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "a stack needs at least one layer");
+    if (cfg->vocab < 8 || cfg->vocab % 8) return fail(nullptr, ICARUS_ERR_SHAPE, "vocab %d must be a positive multiple of 8", cfg->vocab);
+    if (!cfg->embed || !cfg->final_norm || !cfg->lm_head) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "null embed / final_norm / lm_head");
+    if (!aligned16(cfg->embed) || !aligned16(cfg->final_norm) || !aligned16(cfg->lm_head))
+        return fail(nullptr, ICARUS_ERR_ALIGNMENT, "embed, final_norm and lm_head must be 16-byte aligned");
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        if (!cfg->layers[l]) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "layer %d is null", l);
+        if (memcmp(&cfg->layers[l]->cfg, &cfg->layers[0]->cfg, sizeof(icarus_layer_config)) != 0)
+            return fail(nullptr, ICARUS_ERR_SHAPE, "layer %d differs in configuration from layer 0", l);
+    }
+    const icarus_layer_config &c = cfg->layers[0]->cfg;
+    if ((c.d_model * (c.dtype == ICARUS_BF16 ? 2 : 4)) % 16) return fail(nullptr, ICARUS_ERR_SHAPE, "d_model rows must be a multiple of 16 bytes");
+    icarus_stack *st = new (std::nothrow) icarus_stack();
+    if (!st) return fail(nullptr, ICARUS_ERR_HIP, "out of host memory");
+    st->layers.assign(cfg->layers, cfg->layers + cfg->n_layers);
+    st->vocab = cfg->vocab;
+    st->embed = cfg->embed;
+    st->final_norm = cfg->final_norm;
+    st->lm_head = cfg->lm_head;
+    st->err[0] = 0;
+    *out = st;
+    return ICARUS_OK;
+}
+
+void icarus_stack_destroy(icarus_stack *st) { delete st; }
+
+const char *icarus_stack_last_error(const icarus_stack *st) { return st ? st->err : g_create_err; }
+
+size_t icarus_stack_workspace_bytes(const icarus_stack *st, int32_t max_rows, int32_t max_seqs, int32_t max_ctx,
+                                    int32_t max_logit_rows) {
+    if (!st || max_rows < 0 || max_seqs < 0 || max_ctx < 0 || max_logit_rows < 0) return 0;
+    return stack_layout(st, (size_t)std::max(1, max_rows), (size_t)std::max(1, max_seqs), (size_t)max_ctx,
+                        (size_t)std::max(1, max_logit_rows)).total;
+}
+
+icarus_status icarus_stack_prefill(icarus_stack *st, void *const *kv_pools, const int32_t *block_tables, int32_t max_blocks,
+                                   int32_t S, const int32_t *ctx_lens, const int32_t *chunk_lens, const int32_t *tokens,
+                                   int32_t *next_token, float *logits, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!st) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(st->mu);
+    icarus_ctx *c0 = st->layers[0];
+    int R = 0;
+    icarus_status rc = check_prefill(c0, max_blocks, S, ctx_lens, chunk_lens, &R);
+    if (rc) return stack_fail(st, rc, c0->err);
+    if (R == 0) return ICARUS_OK;
+    if (!kv_pools || !tokens || !next_token) return stack_fail(st, ICARUS_ERR_INVALID_ARG, "null kv_pools / tokens / next_token");
+    std::vector<int32_t> extra((size_t)R + S);  // prompt tokens, then each sequence's last chunk row (-1: empty chunk)
+    int n_logit = 0;
+    {
+        int row = 0;
+        for (int s = 0; s < S; ++s) {
+            for (int i = 0; i < chunk_lens[s]; ++i, ++row) {
+                if (tokens[row] < 0 || tokens[row] >= st->vocab) return stack_fail(st, ICARUS_ERR_INVALID_ARG, "token out of range");
+                extra[row] = tokens[row];
+            }
+            if (chunk_lens[s] == 0) return stack_fail(st, ICARUS_ERR_INVALID_ARG, "every sequence of a stack prefill needs at least one token");
+            extra[(size_t)R + n_logit++] = row - 1;
+        }
+    }
+    Prepared pr;
+    // the layer workspace sits at the start of the stack workspace
+    rc = prepare_prefill(c0, kv_pools[0], block_tables, max_blocks, S, ctx_lens, chunk_lens, R, true, workspace, workspace_bytes,
+                         (hipStream_t)stream, extra.data(), extra.size(), &pr);
+    if (rc) return stack_fail(st, rc, c0->err);
+    StackLayout SL = stack_layout_from(st, pr.L, (size_t)R, (size_t)S);
+    if (workspace_bytes < SL.total) return stack_fail(st, ICARUS_ERR_CAPACITY, "workspace too small");
+    return run_stack(st, (char *)workspace, SL, pr, kv_pools, block_tables, max_blocks, R, false, pr.extra_dev, nullptr,
+                     pr.extra_dev + R, S, next_token, nullptr, 0, nullptr, logits, (hipStream_t)stream);
+}
+
+icarus_status icarus_stack_decode(icarus_stack *st, void *const *kv_pools, const int32_t *block_tables, int32_t max_blocks,
+                                  int32_t S, const int32_t *ctx_lens, int32_t R, const int32_t *row_seq,
+                                  const int32_t *row_model, const int32_t *seq_token, int32_t *row_next, int32_t *seq_next,
+                                  float *logits, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!st) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(st->mu);
+    icarus_ctx *c0 = st->layers[0];
+    icarus_status rc = check_decode_rows(c0, max_blocks, S, ctx_lens, R, row_seq, row_model);
+    if (rc) return stack_fail(st, rc, c0->err);
+    if (R == 0) return ICARUS_OK;
+    if (!kv_pools || !seq_token || !row_next) return stack_fail(st, ICARUS_ERR_INVALID_ARG, "null kv_pools / seq_token / row_next");
+    std::vector<int32_t> extra((size_t)S, -1);  // last row of each sequence
+    for (int r = 0; r < R; ++r) extra[row_seq[r]] = r;
+    for (int s = 0; s < S; ++s)
+        if (extra[s] < 0) extra[s] = 0;  // a sequence without rows: its seq_next entry is meaningless
+    Prepared pr;
+    rc = prepare_decode(c0, kv_pools[0], block_tables, max_blocks, S, ctx_lens, R, row_seq, row_model, workspace, workspace_bytes,
+                        (hipStream_t)stream, extra.data(), extra.size(), &pr);
+    if (rc) return stack_fail(st, rc, c0->err);
+    StackLayout SL = stack_layout_from(st, pr.L, (size_t)R, (size_t)R);
+    if (workspace_bytes < SL.total) return stack_fail(st, ICARUS_ERR_CAPACITY, "workspace too small");
+    return run_stack(st, (char *)workspace, SL, pr, kv_pools, block_tables, max_blocks, R, true, seq_token, pr.rm.row_seq, nullptr, R,
+                     row_next, pr.extra_dev, S, seq_next, logits, (hipStream_t)stream);
 }
 
 }  // extern "C"

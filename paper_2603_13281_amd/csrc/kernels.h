@@ -132,4 +132,14 @@ hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *po
 hipError_t launch_attn_merge(const Dims &dm, const float *part_o, const float *part_ml, const AttnPlan &pl,
                              const int32_t *row_seq, void *out, int R, hipStream_t st);
 
+// ---- layer stack helpers (index work) ----------------------------------------------------------
+// x[row, :] = embed[tok[idx ? idx[row] : row], :]   (rows of row_bytes bytes, a multiple of 16)
+hipError_t launch_embed_rows(const void *embed, const int32_t *tok, const int32_t *idx, void *x, int R, int row_bytes, hipStream_t st);
+// out[i, :] = x[rows[i], :]
+hipError_t launch_gather_rows(const void *x, const int32_t *rows, void *out, int n, int row_bytes, hipStream_t st);
+// token[row] = first index of the largest of logits[row, 0..V)
+hipError_t launch_argmax(const float *logits, int R, int V, int32_t *token, hipStream_t st);
+// seq_next[s] = row_next[last_row[s]]
+hipError_t launch_pick_rows(const int32_t *row_next, const int32_t *last_row, int32_t *seq_next, int S, hipStream_t st);
+
 }  // namespace icarus

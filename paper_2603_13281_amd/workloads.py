@@ -191,3 +191,64 @@ def build_prefill_workload(name: str, device="cuda:0", seed: int = 0, verbose: b
     x_host = synth.make_hidden(shape, int(chunk_lens.sum()), seed=seed, tag=20)
     x = upload(x_host, shape.bf16, device)
     return PrefillWorkload(name, desc, shape, batch, chunk_lens, base, layer, pool, bt, x, x_host)
+
+
+@dataclass
+class StackWorkload:
+    name: str
+    description: str
+    shape: synth.LayerShape
+    n_layers: int
+    vocab: int
+    batch: synth.Batch
+    weights: dict            # host float32 (storage-representable): the oracle reads these
+    stack: binding.IcarusStack
+    pools: list              # per layer, device, library layout
+    block_tables: torch.Tensor
+    seq_token: torch.Tensor  # device int32 [S]
+    headroom: int
+
+    def ctx_lens(self, step: int) -> np.ndarray:
+        return (self.batch.ctx_lens + step).astype(np.int32)
+
+
+STACK_SPECS = {
+    # name: (shape, layers, vocab, S, (len_lo, len_hi), description)
+    "stack": (synth.LLAMA8B, 8, 128256, 32, (1024, 8192),
+              "layer stack: 8 Llama-3-8B-shaped layers, vocabulary 128256, 32 sequences with shared contexts U[1024,8192], "
+              "one encoder row and one decoder row (its own adapter of 8) per sequence, greedy token fed back on the device"),
+    "stack-small": (synth.LLAMA_SMALL.replace(n_models=8), 3, 2048, 6, (40, 600), "reduced layer stack"),
+}
+
+
+def build_stack_workload(name: str, device="cuda:0", headroom: int = 128, seed: int = 0, verbose: bool = False) -> StackWorkload:
+    import sys
+    shape, n_layers, vocab, S, (lo, hi), desc = STACK_SPECS[name]
+    say = (lambda *a: print(*a, file=sys.stderr, flush=True)) if verbose else (lambda *a: None)
+    say(f"[workload {name}] weights of {n_layers} layers")
+    wts = synth.make_stack(shape, n_layers, vocab, seed=seed, norm_ones=True)
+    lens = synth.draw_lens(seed, S, lo, hi)
+    batch = synth.make_batch(shape, lens, np.ones(S, dtype=np.int32), seed=seed, headroom=headroom)
+    cfg = layer_config(shape, batch.num_blocks, int(lens.max()) + headroom + 1)
+    layers = []
+    for b, l in zip(wts["bases"], wts["loras"]):
+        dbase = {k: upload(v, shape.bf16, device) for k, v in b.items()}
+        dlora = {p: (upload(A, shape.bf16, device), upload(B, shape.bf16, device)) for p, (A, B) in l.items()}
+        layers.append(binding.IcarusLayer(cfg, dbase, dlora))
+    stack = binding.IcarusStack(layers, upload(wts["embed"], shape.bf16, device), upload(wts["final_norm"], shape.bf16, device),
+                                upload(wts["lm_head"], shape.bf16, device))
+    say(f"[workload {name}] {n_layers} pools of {batch.num_blocks} blocks")
+    gen = torch.Generator(device=device)
+    gen.manual_seed(4000 + seed)
+    pools = []
+    for _ in range(n_layers):
+        pool = torch.empty(cfg.pool_shape(), dtype=cfg.torch_dtype, device=device)
+        step_blocks = max(1, (1 << 28) // (pool[0].numel()))
+        for b0 in range(0, batch.num_blocks, step_blocks):
+            sl = pool[b0:b0 + step_blocks]
+            sl.copy_(torch.randn(sl.shape, generator=gen, device=device, dtype=torch.float32))
+        pools.append(pool)
+    bt = torch.from_numpy(batch.block_tables).to(device)
+    rng = np.random.default_rng(np.random.SeedSequence([seed, 77]))
+    seq_token = torch.from_numpy(rng.integers(0, vocab, size=S).astype(np.int32)).to(device)
+    return StackWorkload(name, desc, shape, n_layers, vocab, batch, wts, stack, pools, bt, seq_token, headroom)

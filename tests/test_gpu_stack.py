@@ -1,0 +1,101 @@
+"""Layer stack on the GPU against the stack oracle: prompt through prefill (first token from the base
+model), then greedy token steps with one encoder row and decoder rows per sequence.
+
+Floating point decides an integer here (the greedy token).  Logits are compared to tolerance; a
+token must equal the oracle's wherever the oracle's two best logits are further apart than twice the
+logit tolerance, and must in any case be a logit within that margin of the oracle's best."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+def _build(shape, n_layers, vocab, num_blocks, seed, lora_std=0.05):
+    import oracle
+    from gpu_util import dev, make_layer
+    from helpers import oracle_config
+    from paper_2603_13281_amd import binding, synth
+    wts = synth.make_stack(shape, n_layers, vocab, seed=seed, lora_std=lora_std)
+    cfg = oracle_config(shape, num_blocks)
+    orc = oracle.OracleStack([oracle.Oracle(cfg, b, l) for b, l in zip(wts["bases"], wts["loras"])],
+                             wts["embed"], wts["final_norm"], wts["lm_head"])
+    layers = [make_layer(shape, b, l, num_blocks) for b, l in zip(wts["bases"], wts["loras"])]
+    stack = binding.IcarusStack(layers, dev(wts["embed"], shape.bf16), dev(wts["final_norm"], shape.bf16), dev(wts["lm_head"], shape.bf16))
+    pools = [torch.zeros(layers[0].cfg.pool_shape(), dtype=layers[0].cfg.torch_dtype, device="cuda:0") for _ in layers]
+    return wts, orc, stack, pools
+
+
+def _check_tokens(got_tok, got_logits, want_logits, tol, what):
+    scale = np.abs(want_logits).max()
+    err = np.abs(got_logits - want_logits).max()
+    assert err <= tol * scale, f"{what}: logits off by {err / scale:.3g} of their range (tolerance {tol})"
+    for r in range(want_logits.shape[0]):
+        order = np.argsort(-want_logits[r], kind="stable")
+        best, second = want_logits[r, order[0]], want_logits[r, order[1]]
+        assert want_logits[r, got_tok[r]] >= best - 2 * tol * scale, f"{what}: row {r} took a token that is not near the best"
+        if best - second > 2 * tol * scale:
+            assert got_tok[r] == order[0], f"{what}: row {r} token {got_tok[r]} != {order[0]}"
+
+
+@pytest.mark.parametrize("kind", ["tiny-fp32", "llama-small-bf16", "qwen-small-bf16"])
+def test_stack_prefill_then_greedy_decode(kind):
+    from paper_2603_13281_amd import synth
+    shape, n_layers, vocab, tol = {
+        "tiny-fp32": (synth.TINY, 3, 264, 1e-4),
+        "llama-small-bf16": (synth.LLAMA_SMALL, 3, 1024, 2e-2),
+        "qwen-small-bf16": (synth.QWEN_SMALL, 2, 512, 2e-2),
+    }[kind]
+    S, steps = 3, 4
+    rng = np.random.default_rng(4)
+    prompt_lens = np.array([37, 5, 64], dtype=np.int32)
+    Bk = shape.block_size
+    max_blocks = int((prompt_lens.max() + steps + Bk) // Bk) + 1
+    num_blocks = S * max_blocks + 2
+    wts, orc, stack, pools = _build(shape, n_layers, vocab, num_blocks, seed=11)
+    opools = orc.new_pools()
+    bt = rng.permutation(num_blocks)[:S * max_blocks].reshape(S, max_blocks).astype(np.int32)
+    dbt = torch.from_numpy(bt).to("cuda:0")
+    tokens = rng.integers(0, vocab, size=int(prompt_lens.sum())).astype(np.int32)
+    zeros = np.zeros(S, dtype=np.int32)
+
+    # prompt: first token from the base model
+    nxt, lg = stack.prefill(pools, dbt, zeros, prompt_lens, tokens, want_logits=True)
+    want_lg, want_tok = orc.prefill(opools, bt, zeros, prompt_lens, tokens)
+    torch.cuda.synchronize()
+    _check_tokens(nxt.cpu().numpy(), lg.cpu().numpy().astype(np.float64), want_lg, tol, f"{kind} prefill")
+
+    # greedy steps: sequence s runs 1 + m_s rows; the sequence's last row decides its next token.
+    # Both sides are fed the ORACLE's token each step, so that a legitimate near-tie cannot fork them.
+    row_seq = np.int32([0, 0, 1, 1, 1, 2])
+    row_model = np.int32([-1, 1, -1, 0, 1, -1])
+    last_row = np.array([1, 4, 5])
+    ctx = prompt_lens.copy()
+    cur = want_tok.astype(np.int32)
+    for t in range(steps):
+        seq_tok = torch.from_numpy(cur).to("cuda:0")
+        seq_next = torch.empty(S, dtype=torch.int32, device="cuda:0")
+        row_next, lg = stack.decode(pools, dbt, ctx, row_seq, row_model, seq_tok, seq_next=seq_next, want_logits=True)
+        want_lg, want_row_tok, _ = orc.decode(opools, bt, ctx, row_seq, row_model, cur)
+        torch.cuda.synchronize()
+        got_rows = row_next.cpu().numpy()
+        _check_tokens(got_rows, lg.cpu().numpy().astype(np.float64), want_lg, tol, f"{kind} step {t}")
+        np.testing.assert_array_equal(seq_next.cpu().numpy(), got_rows[last_row])
+        cur = want_row_tok[last_row].astype(np.int32)
+        ctx = ctx + 1
+
+
+def test_stack_rejects_bad_arguments():
+    from paper_2603_13281_amd import binding, synth
+    shape = synth.TINY
+    wts, orc, stack, pools = _build(shape, 2, 64, 8, seed=1)
+    dbt = torch.arange(4, dtype=torch.int32, device="cuda:0").reshape(1, 4)
+    with pytest.raises(binding.IcarusError) as e:       # token outside the vocabulary
+        stack.prefill(pools, dbt, [0], [3], [1, 2, 64])
+    assert e.value.status_name == "INVALID_ARG"
+    with pytest.raises(binding.IcarusError) as e:       # context beyond the block table
+        stack.prefill(pools, dbt, [0], [4 * shape.block_size + 1], np.zeros(4 * shape.block_size + 1, dtype=np.int32))
+    assert e.value.status_name == "CAPACITY"
+    with pytest.raises(binding.IcarusError) as e:       # two encoder rows in one sequence
+        stack.decode(pools, dbt, [3], [0, 0], [-1, -1], torch.zeros(1, dtype=torch.int32, device="cuda:0"))
+    assert e.value.status_name == "ROW_ORDER"
