@@ -461,9 +461,11 @@ hipError_t launch_cfg(GemmArgs g, hipStream_t st) {
 // one workgroup); the narrow GEMMs take 128 x 128 tiles with narrow K slabs (two workgroups per CU)
 // and split K.
 enum TileKind { TILE_AUTO = 0, TILE_128, TILE_128_NARROW, TILE_256x128, TILE_384x128, TILE_384x128_W8, TILE_256x256,
-                TILE_KINDS };
+                TILE_128_K128, TILE_128x64_K128, TILE_256x256_K64, TILE_384x128_K64, TILE_256x128_K64, TILE_192x128_K64, TILE_192x128_K64_N3, TILE_192x128_K64_N2, TILE_64x128_K64_N3, TILE_64x128_K64_N5, TILE_KINDS };
 struct TileShape { int bm, bn; };
-constexpr TileShape kTileShape[TILE_KINDS] = {{0, 0}, {128, 128}, {128, 128}, {256, 128}, {384, 128}, {384, 128}, {256, 256}};
+constexpr TileShape kTileShape[TILE_KINDS] = {{0, 0}, {128, 128}, {128, 128}, {256, 128}, {384, 128}, {384, 128}, {256, 256},
+                                              {128, 128}, {128, 64}, {256, 256}, {384, 128}, {256, 128}, {192, 128}, {192, 128}, {192, 128}, {64, 128}, {64, 128}};
+constexpr int kTileBK[TILE_KINDS] = {0, 64, 32, 32, 32, 32, 32, 128, 128, 64, 64, 64, 64, 64, 64, 64, 64};
 
 // ICARUS_GEMM_CFG = "<tile kind>" forces one tile shape for every GEMM (experiments, tests).
 int forced_tile() {
@@ -485,12 +487,20 @@ int n_tiles_for(const GemmArgs &g, int bm, int bn) {
     return m_tiles * n_tiles;
 }
 
-int pick_tile(const GemmArgs &g) {
+int pick_tile_unchecked(const GemmArgs &g) {
+    if (g.tile > 0 && g.tile < TILE_KINDS) return g.tile;
     if (int f = forced_tile()) return f;
-    if (g.R >= 1024 && n_tiles_for(g, 256, 256) >= 192) return TILE_256x256;  // enough large tiles for 256 CUs
-    if (g.mode == GEMM_DUAL && g.R > 128 && g.R <= 256) return TILE_256x128;
-    if (g.mode == GEMM_DUAL && g.R > 256 && g.R <= 384) return TILE_384x128_W8;
-    return g.R <= 384 ? TILE_128_NARROW : TILE_128;
+    if (g.R >= 1024 && n_tiles_for(g, 256, 256) >= 192) return TILE_256x256_K64;  // enough large tiles for 256 CUs
+    if (g.R <= 64) return TILE_64x128_K64_N3;
+    if (g.R <= 128) return TILE_128;
+    if (g.mode == GEMM_DUAL && g.R > 192 && g.R <= 256) return TILE_256x128;
+    if (g.R <= 384) return g.mode == GEMM_DUAL ? TILE_192x128_K64_N2 : TILE_192x128_K64_N3;
+    return TILE_128;
+}
+
+int pick_tile(const GemmArgs &g) {
+    int kind = pick_tile_unchecked(g);
+    return g.K % kTileBK[kind] ? TILE_128 : kind;  // K is a multiple of 64 at least
 }
 
 }  // namespace
@@ -514,13 +524,25 @@ hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st) {
     else
         g.K_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
     if (g.splits < 1) g.splits = 1;
-    g.k_per_split = ((g.K_ext + g.splits - 1) / g.splits + kKAlign - 1) / kKAlign * kKAlign;
-    switch (pick_tile(g)) {
+    const int kind = pick_tile(g), bk = kTileBK[kind];
+    if (g.K % bk) return hipErrorInvalidValue;
+    g.k_per_split = ((g.K_ext + g.splits - 1) / g.splits + bk - 1) / bk * bk;
+    switch (kind) {
     case TILE_128_NARROW: return launch_cfg<128, 128, 32, 4, 2, 2>(g, st);
     case TILE_256x128: return launch_cfg<256, 128, 32, 4, 2, 2>(g, st);
     case TILE_384x128: return launch_cfg<384, 128, 32, 4, 4, 1>(g, st);
     case TILE_384x128_W8: return launch_cfg<384, 128, 32, 4, 4, 2>(g, st);
     case TILE_256x256: return launch_cfg<256, 256, 32, 4, 2, 4>(g, st);
+    case TILE_128_K128: return launch_cfg<128, 128, 128, 2, 2, 2>(g, st);
+    case TILE_128x64_K128: return launch_cfg<128, 64, 128, 3, 2, 2>(g, st);
+    case TILE_256x256_K64: return launch_cfg<256, 256, 64, 2, 2, 4>(g, st);
+    case TILE_384x128_K64: return launch_cfg<384, 128, 64, 2, 4, 2>(g, st);
+    case TILE_256x128_K64: return launch_cfg<256, 128, 64, 3, 2, 2>(g, st);
+    case TILE_192x128_K64: return launch_cfg<192, 128, 64, 4, 2, 2>(g, st);
+    case TILE_192x128_K64_N3: return launch_cfg<192, 128, 64, 3, 2, 2>(g, st);
+    case TILE_192x128_K64_N2: return launch_cfg<192, 128, 64, 2, 2, 2>(g, st);
+    case TILE_64x128_K64_N3: return launch_cfg<64, 128, 64, 3, 2, 2>(g, st);
+    case TILE_64x128_K64_N5: return launch_cfg<64, 128, 64, 5, 2, 2>(g, st);
     default: return launch_cfg<128, 128, 64, 4, 2, 2>(g, st);
     }
 }

@@ -426,7 +426,8 @@ void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t
 // Attention of decode rows: matrix-core kernel + merge when a plan exists, else the generic kernel.
 icarus_status run_decode_attention(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp,
                                    const void *q, const void *pool, const int32_t *bt, int max_blocks, void *out, int R,
-                                   hipStream_t st) {
+                                   hipStream_t st, bool *merge_left = nullptr) {
+    if (merge_left) *merge_left = false;
     if (!hp || !hp->valid) {
         PHASE(ctx, st, ICARUS_PH_ATTN, launch_attn_generic(ctx->dm, q, pool, bt, max_blocks, rm, out, R, st));
         return ICARUS_OK;
@@ -437,6 +438,10 @@ icarus_status run_decode_attention(icarus_ctx *ctx, char *ws, const WsLayout &L,
     }
     float *part_o = (float *)(ws + L.part_o), *part_ml = (float *)(ws + L.part_ml);
     PHASE(ctx, st, ICARUS_PH_ATTN, launch_attn_decode_mfma(ctx->dm, q, pool, bt, max_blocks, hp->pl, out, part_o, part_ml, st));
+    if (hp->has_split && merge_left) {  // the caller merges the partials in its next row kernel
+        *merge_left = true;
+        return ICARUS_OK;
+    }
     if (hp->has_split) PHASE(ctx, st, ICARUS_PH_ATTN_MERGE, launch_attn_merge(ctx->dm, part_o, part_ml, hp->pl, rm.row_seq, out, R, st));
     return ICARUS_OK;
 }
@@ -451,18 +456,35 @@ bool layer_mfma_supported(const icarus_ctx *ctx) {
            gemm_mfma_supported(ctx->dm, c.d_ffn) && shrink_ok;
 }
 
+// Experiments: ICARUS_GEMM_PLAN = "tile,splits" pairs for the QKV, O, gate/up and down GEMMs (0 = automatic).
+const int *gemm_plan() {
+    static int plan[16] = {-1};
+    if (plan[0] < 0) {
+        for (int &v : plan) v = 0;
+        if (const char *e = getenv("ICARUS_GEMM_PLAN")) {
+            int i = 0;
+            for (const char *q = e; *q && i < 16; ++i) { plan[i] = atoi(q); while (*q && *q != ',') ++q; if (*q) ++q; }
+        }
+    }
+    return plan;
+}
+
 // One plain ICaRusLinear GEMM.  When its grid would leave most of the chip idle (few rows and a
 // narrow output), K is split over several workgroups into fp32 partials [splits][R][N]; a second
 // small kernel sums them and applies the epilogue, unless the caller takes the slices as they are
 // (deferred_splits: set to the number of slices left in the workspace, 0 if the output is final).
 icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, GemmArgs g, hipStream_t st,
                        int *deferred_splits = nullptr) {
+    const int *plan = gemm_plan();
+    int pi = phase == ICARUS_PH_GEMM_QKV ? 0 : phase == ICARUS_PH_GEMM_O ? 2 : phase == ICARUS_PH_GEMM_DOWN ? 6 : 4;
+    g.tile = plan[pi];
     int tiles = gemm_mfma_tiles(g);
     int n_total = 0;
     for (int s = 0; s < g.nseg; ++s) n_total += g.n_seg[s];
     int k_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
     int splits = 1;
-    if (tiles < 160) splits = std::max(1, std::min({kGemmMaxSplits, 384 / tiles, k_ext / 256}));
+    if (tiles < 160) splits = std::max(1, std::min({kGemmMaxSplits, 256 / tiles, k_ext / 256}));
+    if (plan[pi + 1] > 0) splits = plan[pi + 1];
     splits = (int)std::max<size_t>(1, std::min<size_t>(splits, L.gemm_part_bytes / ((size_t)g.R * n_total * 4)));
     if (deferred_splits) *deferred_splits = 0;
     if (splits == 1) {
@@ -523,16 +545,21 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
                                                                  pool, q, slot_out, slot_by_row, ctx->base.q_norm, ctx->base.k_norm, R, st));
     }
     if (kv_only) return ICARUS_OK;
-    LORA_TRY(run_decode_attention(ctx, ws, L, rm, hp, q, pool, bt, max_blocks, attn, R, st));
-    {   // O projection (ICaRusLinear) + residual
+    bool merge_left = false;
+    LORA_TRY(run_decode_attention(ctx, ws, L, rm, hp, q, pool, bt, max_blocks, attn, R, st, &merge_left));
+    {   // O projection (ICaRusLinear) + residual; its shrink also merges the attention partials of cut sequences
         GemmArgs g{};
         g.X = attn; g.ldx = qd; g.R = R; g.K = qd;
         g.W[0] = W(ICARUS_PROJ_O); g.n_seg[0] = d; g.nseg = 1;
         g.mode = GEMM_PLAIN; g.epi = EPI_BF16_RESID; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
-        if (lo(ICARUS_PROJ_O)) {
+        const bool l_o = lo(ICARUS_PROJ_O);
+        if (merge_left)
+            PHASE(ctx, st, ICARUS_PH_ATTN_MERGE,
+                  launch_merge_shrink(dm, (const float *)(ws + L.part_o), (const float *)(ws + L.part_ml), hp->pl, rm.row_seq, attn, R,
+                                      l_o ? Aw(ICARUS_PROJ_O) : nullptr, rm.row_model, T, st));
+        else if (l_o)
             PHASE(ctx, st, ICARUS_PH_LORA, launch_row_shrink(dm, attn, qd, R, qd, Aw(ICARUS_PROJ_O), rm.row_model, T, st));
-            g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_O);
-        }
+        if (l_o) { g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_O); }
         g.Y = z; g.ldy = d; g.resid = (const bf16_raw *)x_in; g.ldr = d;
         LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_O, g, st, &o_splits));
     }
@@ -554,6 +581,7 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
         g.mode = GEMM_DUAL; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
         if (lg) { g.T = T; g.ldt = 2 * mr; g.B[0] = Bw(ICARUS_PROJ_GATE); g.B[1] = Bw(ICARUS_PROJ_UP); }
         g.Y = h; g.ldy = F;
+        g.tile = gemm_plan()[4];
         PHASE(ctx, st, ICARUS_PH_GEMM_GATEUP, launch_gemm_mfma(g, st));
     }
     {   // down projection (ICaRusLinear) + residual

@@ -92,6 +92,7 @@ struct GemmArgs {
     void *Y; int ldy;                            // EPI_F32: float [splits][R][ldy]; else bf16 [R][ldy]
     const bf16_raw *resid; int ldr;              // EPI_BF16_RESID: added to the result
     int splits;                                  // split-K slices (EPI_F32 without adapters only)
+    int tile;                                    // tile kind, 0 = chosen by the launcher
     // filled by the launcher
     int tiles_seg[3]; int m_tiles, n_tiles, K_ext, k_per_split;
     int run, panel_m, panel_n, panels_m, n_panels;  // tile order: panels of panel_m x panel_n <= run tiles
@@ -120,6 +121,11 @@ hipError_t launch_row_shrink(const Dims &dm, const void *x, int ldx, int R, int 
                              hipStream_t st);
 
 bool attn_decode_mfma_supported(const Dims &dm, int g_max);
+// Merge of the attention partials of cut sequences (as launch_attn_merge) and, with A0, the shrink of the O projection
+// on the merged rows, in one kernel: attn [R][Hq*D] is completed in place, T as for launch_row_shrink.
+hipError_t launch_merge_shrink(const Dims &dm, const float *part_o, const float *part_ml, const struct AttnPlan &pl,
+                               const int32_t *row_pseq, void *attn, int R, const void *A0, const int32_t *row_model, void *T,
+                               hipStream_t st);
 // Causal attention of prefill chunks: each plan sequence is a group of consecutive chunk tokens with at
 // most attn_prefill_group_queries() stacked queries (tokens x Hq/Hkv); never split, writes `out` directly.
 int attn_prefill_group_queries();

@@ -10,6 +10,8 @@
 #include "device_util.h"
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace icarus {
 
 namespace {
@@ -27,132 +29,242 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
     return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
 
-// NORM: y[row] = rmsnorm(x[row]) * wn (bf16), and the shrink reads y; else the shrink reads x.
-// NACC = targets * r accumulators per row (0: no shrink).  A0/A1: adapter A of the one or two
-// targets that share this input, each [M][r][K].  T: [R][ldt], ldt = targets * M * r.
-template <bool NORM, int NACC>
-__global__ void __launch_bounds__(kRowThreads) k_norm_shrink(const bf16_t *__restrict__ x, int ldx, int K, const bf16_t *__restrict__ wn,
-                                                     float eps, bf16_t *__restrict__ y, const bf16_t *__restrict__ A0,
-                                                     const bf16_t *__restrict__ A1, int r, int M, const int32_t *__restrict__ row_model,
-                                                     float scale, bf16_t *__restrict__ T, int ldt, int *__restrict__ zero, int n_zero,
-                                                     const float *__restrict__ psum, int splits, size_t slice,
-                                                     const bf16_t *__restrict__ resid, bf16_t *__restrict__ xsum) {
+// Where a row comes from.
+//   SRC_PLAIN:  it is stored (x).
+//   SRC_SLICES: it is still in pieces, residual + split-K partials (fp32) of the projection before it.
+//   SRC_ATTN:   it is the attention output of a sequence whose cached tokens were cut into several
+//               pieces: per (piece, kv-head, stacked query) an unnormalised partial output with its
+//               running maximum and denominator, merged here (rows of uncut sequences are stored).
+// Rows that are formed here are rounded to bf16 and stored at x, and everything downstream sees them
+// as stored.
+enum { SRC_PLAIN = 0, SRC_SLICES = 1, SRC_ATTN = 2 };
+
+struct RowArgs {
+    bf16_t *x; int ldx; int K;                       // the rows [R][ldx], K used columns
+    const bf16_t *wn; float eps; bf16_t *y;          // NORM: y = rmsnorm(x) * wn, [R][K]
+    const bf16_t *A0, *A1; int r, M;                 // adapter A of the one or two targets reading this input, [M][r][K]
+    const int32_t *row_model; float scale; bf16_t *T; int ldt;  // T [R][ldt], ldt = targets * M * r
+    int *zero; int n_zero;                           // small per-call counters cleared by row 0
+    const float *psum; int splits; size_t slice; const bf16_t *resid;  // SRC_SLICES
+    const float *part_o, *part_ml;                   // SRC_ATTN: partials [(piece, kv-head, query)][D] and [..][2]
+    const int32_t *row_pseq, *seq_nparts, *seq_part0, *seq_row0; int Hq, Hkv, g_max;
+};
+
+constexpr int kHeadChunks = 16;  // 16-byte chunks per attention head (head_dim 128)
+
+// One workgroup per row.  NACC = targets * r accumulators (0: no shrink).  The row's mat-vecs are a
+// chain of dependent memory round trips if written naively (row model -> row -> norm -> adapter
+// rows), so the adapter rows, which depend on the row's model only, are requested first and stay
+// one group of loads ahead of the arithmetic throughout.
+template <int SRC, bool NORM, int NACC>
+__global__ void __launch_bounds__(kRowThreads) k_row(RowArgs a) {
+    constexpr int NA = NACC > 0 ? NACC : 1;
+    constexpr int GRP = NA == 32 ? 4 : (NA >= 8 ? 8 : NA);  // adapter rows per group of loads (two groups in flight); 128 registers at 32
+    constexpr int NG = NA / GRP;              // groups per chunk: 1, 2, 4 or 8
+    constexpr int U = NG < 2 ? 2 : NG;        // steps per unrolled round (two load buffers)
+    constexpr bool FIRST_PASS = NORM || SRC != SRC_PLAIN;
     __shared__ float red[16];
-    __shared__ float part[kRowThreads / 64][NACC > 0 ? NACC : 1];
-    __shared__ float res[NACC > 0 ? NACC : 1];
+    __shared__ float part[kRowThreads / 64][NA];
+    __shared__ float res[NA];
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int n_chunks = K >> 3;
-    const bf16_t *xr = x + (size_t)row * ldx;
-    if (row == 0)  // the layer's first kernel also clears small per-call counters
-        for (int i = tid; i < n_zero; i += kRowThreads) zero[i] = 0;
-    float inv = 1.f;
-    if (NORM) {
+    const int K = a.K, n_chunks = K >> 3;
+    const int j = NACC > 0 ? a.row_model[row] : -1;
+    const bool shrink = NACC > 0 && j >= 0;  // uniform over the workgroup
+    if (row == 0)
+        for (int i = tid; i < a.n_zero; i += kRowThreads) a.zero[i] = 0;
+    bf16_t *xr = a.x + (size_t)row * a.ldx;
+    const bf16_t *pA0 = a.A0 + (size_t)(shrink ? j : 0) * a.r * K;
+    const bf16_t *pA1 = a.A1 ? a.A1 + (size_t)(shrink ? j : 0) * a.r * K : pA0;
+    const int my_chunks = tid < n_chunks ? (n_chunks - tid + kRowThreads - 1) / kRowThreads : 0;
+    const int n_steps = my_chunks * NG;  // step t: chunk t / NG of this thread, adapter rows (t % NG) * GRP ...
+
+    uint4 av[2][GRP], xb[2], wb[2];
+    auto issue = [&](int t, int gi, int b) {
+        const int c = tid + (t / NG) * kRowThreads;
+        if (gi == 0) {
+            if (t > 0 || !FIRST_PASS) xb[b] = *(const uint4 *)(xr + c * 8);  // chunk 0 stays in registers after the first pass
+            if (NORM) wb[b] = *(const uint4 *)(a.wn + c * 8);
+        }
+        if (shrink) {
+#pragma unroll
+            for (int q = 0; q < GRP; ++q) {
+                const int ai = gi * GRP + q;
+                av[b][q] = *(const uint4 *)((ai < a.r ? pA0 + (size_t)ai * K : pA1 + (size_t)(ai - a.r) * K) + c * 8);
+            }
+        }
+    };
+    if (n_steps > 0) issue(0, 0, 0);
+
+    // first pass: form the row (and store it), sum of squares
+    float f0[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, inv = 1.f;
+    if (FIRST_PASS) {
         float ss = 0.f;
-        for (int c = tid; c < n_chunks; c += kRowThreads) {
+        int np = 1, p0 = 0, jq0 = 0, g = 1;
+        if (SRC == SRC_ATTN) {
+            const int s = a.row_pseq[row];
+            np = a.seq_nparts[s]; p0 = a.seq_part0[s]; g = a.Hq / a.Hkv;
+            jq0 = (row - a.seq_row0[s]) * g;
+        }
+        for (int ci = 0; ci < my_chunks; ++ci) {
+            const int c = tid + ci * kRowThreads;
             float f[8];
-            if (psum) {
-                // the row is still in pieces: residual + split-K partials of the projection before the
-                // norm.  Sum them, round to storage, keep (xsum is x): each thread re-reads below
-                // only the chunks it wrote itself.
-                unpack8(*(const uint4 *)(resid + (size_t)row * K + c * 8), f);
-                for (int z = 0; z < splits; ++z) {
-                    const float *pp = psum + z * slice + (size_t)row * K + c * 8;
-                    const float4 p0 = *(const float4 *)pp, p1 = *(const float4 *)(pp + 4);
-                    f[0] += p0.x; f[1] += p0.y; f[2] += p0.z; f[3] += p0.w;
-                    f[4] += p1.x; f[5] += p1.y; f[6] += p1.z; f[7] += p1.w;
+            bool formed = false;
+            if (SRC == SRC_SLICES) {
+                unpack8(*(const uint4 *)(a.resid + (size_t)row * K + c * 8), f);
+                const float *pp = a.psum + (size_t)row * K + c * 8;
+                int z = 0;
+                for (; z + 4 <= a.splits; z += 4) {  // four slices in flight
+                    float4 v[8];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        v[2 * q] = *(const float4 *)(pp + (z + q) * a.slice);
+                        v[2 * q + 1] = *(const float4 *)(pp + (z + q) * a.slice + 4);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        f[0] += v[2 * q].x; f[1] += v[2 * q].y; f[2] += v[2 * q].z; f[3] += v[2 * q].w;
+                        f[4] += v[2 * q + 1].x; f[5] += v[2 * q + 1].y; f[6] += v[2 * q + 1].z; f[7] += v[2 * q + 1].w;
+                    }
                 }
+                for (; z < a.splits; ++z) {
+                    const float4 v0 = *(const float4 *)(pp + z * a.slice), v1 = *(const float4 *)(pp + z * a.slice + 4);
+                    f[0] += v0.x; f[1] += v0.y; f[2] += v0.z; f[3] += v0.w;
+                    f[4] += v1.x; f[5] += v1.y; f[6] += v1.z; f[7] += v1.w;
+                }
+                formed = true;
+            } else if (SRC == SRC_ATTN && np > 1) {
+                const int h = c / kHeadChunks, d0 = (c % kHeadChunks) * 8;
+                const size_t pj0 = ((size_t)p0 * a.Hkv + h / g) * a.g_max + jq0 + h % g;
+                const size_t pstep = (size_t)a.Hkv * a.g_max;  // between consecutive pieces
+                float mx = -INFINITY;
+                for (int p = 0; p < np; ++p) mx = fmaxf(mx, a.part_ml[(pj0 + p * pstep) * 2]);
+                float den = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] = 0.f;
+                for (int p = 0; p < np; ++p) {
+                    const size_t pj = pj0 + p * pstep;
+                    const float wgt = __builtin_amdgcn_exp2f(a.part_ml[pj * 2] - mx);
+                    den += wgt * a.part_ml[pj * 2 + 1];
+                    const float4 v0 = *(const float4 *)(a.part_o + pj * (kHeadChunks * 8) + d0);
+                    const float4 v1 = *(const float4 *)(a.part_o + pj * (kHeadChunks * 8) + d0 + 4);
+                    f[0] += wgt * v0.x; f[1] += wgt * v0.y; f[2] += wgt * v0.z; f[3] += wgt * v0.w;
+                    f[4] += wgt * v1.x; f[5] += wgt * v1.y; f[6] += wgt * v1.z; f[7] += wgt * v1.w;
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] = f[e] / den;
+                formed = true;
+            }
+            if (formed) {
                 uint4 o;
                 o.x = pack2(f[0], f[1]); o.y = pack2(f[2], f[3]); o.z = pack2(f[4], f[5]); o.w = pack2(f[6], f[7]);
-                *(uint4 *)(xsum + (size_t)row * K + c * 8) = o;
+                *(uint4 *)(xr + c * 8) = o;
                 unpack8(o, f);
             } else {
                 unpack8(*(const uint4 *)(xr + c * 8), f);
             }
+            if (NORM) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+                for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+            }
+            if (ci == 0) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f0[e] = f[e];
+            }
         }
-        ss = block_sum(ss, red);
-        inv = rsqrtf(ss / (float)K + eps);
-    }
-    const int j = NACC > 0 ? row_model[row] : -1;
-    float acc[NACC > 0 ? NACC : 1];
-#pragma unroll
-    for (int a = 0; a < (NACC > 0 ? NACC : 1); ++a) acc[a] = 0.f;
-    for (int c = tid; c < n_chunks; c += kRowThreads) {
-        float f[8];
-        unpack8(*(const uint4 *)(xr + c * 8), f);
         if (NORM) {
-            float wf[8];
-            unpack8(*(const uint4 *)(wn + c * 8), wf);
-            uint4 o;
-            o.x = pack2(f[0] * inv * wf[0], f[1] * inv * wf[1]);
-            o.y = pack2(f[2] * inv * wf[2], f[3] * inv * wf[3]);
-            o.z = pack2(f[4] * inv * wf[4], f[5] * inv * wf[5]);
-            o.w = pack2(f[6] * inv * wf[6], f[7] * inv * wf[7]);
-            *(uint4 *)(y + (size_t)row * K + c * 8) = o;
-            unpack8(o, f);  // the shrink sees the row as stored
+            ss = block_sum(ss, red);
+            inv = rsqrtf(ss / (float)K + a.eps);
         }
-        if (NACC > 0 && j >= 0) {
-            const bf16_t *p0 = A0 + ((size_t)j * r) * K + c * 8;
-            const bf16_t *p1 = A1 ? A1 + ((size_t)j * r) * K + c * 8 : p0;
-            constexpr int GRP = NACC < 16 ? (NACC > 0 ? NACC : 1) : 16;  // loads in flight per thread
+    }
+    if (!NORM && NACC == 0) return;
+
+    // second pass: normalise and store, multiply with the adapter rows
+    float acc[NA];
 #pragma unroll
-            for (int a0 = 0; a0 < NACC; a0 += GRP) {
-                uint4 av[GRP];
+    for (int q = 0; q < NA; ++q) acc[q] = 0.f;
+    float f[8];
+    for (int t0 = 0; t0 < n_steps; t0 += U) {
 #pragma unroll
-                for (int a = 0; a < GRP; ++a)
-                    av[a] = *(const uint4 *)(a0 + a < r ? p0 + (size_t)(a0 + a) * K : p1 + (size_t)(a0 + a - r) * K);
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u, gi = u % NG, b = u & 1;
+            if (t < n_steps) {
+                if (t + 1 < n_steps) issue(t + 1, (u + 1) % NG, (u + 1) & 1);
+                if (gi == 0) {
+                    const int c = tid + (t / NG) * kRowThreads;
+                    if (FIRST_PASS && t == 0) {
 #pragma unroll
-                for (int a = 0; a < GRP; ++a) {
-                    float af[8];
-                    unpack8(av[a], af);
+                        for (int e = 0; e < 8; ++e) f[e] = f0[e];
+                    } else {
+                        unpack8(xb[b], f);
+                    }
+                    if (NORM) {
+                        float wf[8];
+                        unpack8(wb[b], wf);
+                        uint4 o;
+                        o.x = pack2(f[0] * inv * wf[0], f[1] * inv * wf[1]);
+                        o.y = pack2(f[2] * inv * wf[2], f[3] * inv * wf[3]);
+                        o.z = pack2(f[4] * inv * wf[4], f[5] * inv * wf[5]);
+                        o.w = pack2(f[6] * inv * wf[6], f[7] * inv * wf[7]);
+                        *(uint4 *)(a.y + (size_t)row * K + c * 8) = o;
+                        unpack8(o, f);  // the shrink sees the row as stored
+                    }
+                }
+                if (shrink) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[a0 + a] += f[e] * af[e];
+                    for (int q = 0; q < GRP; ++q) {
+                        float af[8];
+                        unpack8(av[b][q], af);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[gi * GRP + q] += f[e] * af[e];
+                    }
                 }
             }
         }
     }
     if (NACC == 0) return;
-    if (j >= 0) {  // uniform over the workgroup
+    if (shrink) {
 #pragma unroll
-        for (int a = 0; a < NACC; ++a) {
-            float s = wave_sum(acc[a]);
-            if (lane == 0) part[wv][a] = s;
+        for (int q = 0; q < NA; ++q) {
+            float s = wave_sum(acc[q]);
+            if (lane == 0) part[wv][q] = s;
         }
         __syncthreads();
-        if (tid < NACC) {
+        if (tid < NA) {
             float v = 0.f;
 #pragma unroll
             for (int q = 0; q < kRowThreads / 64; ++q) v += part[q][tid];
-            res[tid] = v * scale;
+            res[tid] = v * a.scale;
         }
         __syncthreads();
     }
-    const int mr = M * r;
-    for (int c = tid; c < ldt; c += kRowThreads) {
-        int t = c / mr, jj = (c % mr) / r, i = c % r;
-        T[(size_t)row * ldt + c] = f32_to_bf16(jj == j ? res[t * r + i] : 0.f);
+    const int mr = a.M * a.r;
+    for (int c = tid; c < a.ldt; c += kRowThreads) {
+        int t = c / mr, jj = (c % mr) / a.r, i = c % a.r;
+        a.T[(size_t)row * a.ldt + c] = f32_to_bf16(jj == j ? res[t * a.r + i] : 0.f);
     }
 }
 
-template <bool NORM>
-hipError_t launch_ns(int nacc, int R, hipStream_t st, const bf16_t *x, int ldx, int K, const bf16_t *wn, float eps, bf16_t *y,
-                     const bf16_t *A0, const bf16_t *A1, int r, int M, const int32_t *row_model, float scale, bf16_t *T, int ldt,
-                     int *zero, int n_zero, const float *part = nullptr, int splits = 0, size_t slice = 0,
-                     const bf16_t *resid = nullptr, bf16_t *xsum = nullptr) {
-#define ICARUS_NS(N)                                                                                                          \
-    hipLaunchKernelGGL((k_norm_shrink<NORM, N>), dim3(R), dim3(kRowThreads), 0, st, x, ldx, K, wn, eps, y, A0, A1, r, M, row_model, \
-                       scale, T, ldt, zero, n_zero, part, splits, slice, resid, xsum)
+template <int SRC, bool NORM>
+hipError_t launch_row(int nacc, int R, hipStream_t st, const RowArgs &a) {
+#define ICARUS_ROW(N) hipLaunchKernelGGL((k_row<SRC, NORM, N>), dim3(R), dim3(kRowThreads), 0, st, a)
     switch (nacc) {
-    case 0: ICARUS_NS(0); break;
-    case 8: ICARUS_NS(8); break;
-    case 16: ICARUS_NS(16); break;
-    case 32: ICARUS_NS(32); break;
-    case 64: ICARUS_NS(64); break;
+    case 0: ICARUS_ROW(0); break;
+    case 8: ICARUS_ROW(8); break;
+    case 16: ICARUS_ROW(16); break;
+    case 32: ICARUS_ROW(32); break;
+    case 64: ICARUS_ROW(64); break;
     default: return hipErrorInvalidValue;
     }
-#undef ICARUS_NS
+#undef ICARUS_ROW
     return hipGetLastError();
+}
+
+RowArgs shrink_args(const Dims &dm, const void *A0, const void *A1, const int32_t *row_model, void *T) {
+    RowArgs a{};
+    int targets = A0 ? (A1 ? 2 : 1) : 0;
+    a.A0 = (const bf16_t *)A0; a.A1 = (const bf16_t *)A1; a.r = dm.r; a.M = dm.M; a.row_model = row_model;
+    a.scale = dm.lora_scale; a.T = (bf16_t *)T; a.ldt = targets * dm.M * dm.r;
+    return a;
 }
 
 }  // namespace
@@ -165,26 +277,39 @@ bool row_shrink_supported(int r, int targets) {
 hipError_t launch_norm_shrink(const Dims &dm, const void *x, const void *wn, void *y, int R, int K, const void *A0, const void *A1,
                               const int32_t *row_model, void *T, int *zero, int n_zero, hipStream_t st) {
     if (R <= 0) return hipSuccess;
-    int targets = A0 ? (A1 ? 2 : 1) : 0;
-    return launch_ns<true>(targets * dm.r, R, st, (const bf16_t *)x, K, K, (const bf16_t *)wn, dm.eps, (bf16_t *)y, (const bf16_t *)A0,
-                           (const bf16_t *)A1, dm.r, dm.M, row_model, dm.lora_scale, (bf16_t *)T, targets * dm.M * dm.r, zero, n_zero);
+    RowArgs a = shrink_args(dm, A0, A1, row_model, T);
+    a.x = (bf16_t *)x; a.ldx = K; a.K = K; a.wn = (const bf16_t *)wn; a.eps = dm.eps; a.y = (bf16_t *)y;
+    a.zero = zero; a.n_zero = n_zero;
+    return launch_row<SRC_PLAIN, true>(a.ldt / std::max(1, dm.M), R, st, a);
 }
 
 hipError_t launch_sum_norm_shrink(const Dims &dm, const float *part, int splits, size_t slice, const void *resid, void *xsum,
                                   const void *wn, void *y, int R, int K, const void *A0, const void *A1, const int32_t *row_model,
                                   void *T, hipStream_t st) {
     if (R <= 0) return hipSuccess;
-    int targets = A0 ? (A1 ? 2 : 1) : 0;
-    return launch_ns<true>(targets * dm.r, R, st, (const bf16_t *)xsum, K, K, (const bf16_t *)wn, dm.eps, (bf16_t *)y,
-                           (const bf16_t *)A0, (const bf16_t *)A1, dm.r, dm.M, row_model, dm.lora_scale, (bf16_t *)T,
-                           targets * dm.M * dm.r, nullptr, 0, part, splits, slice, (const bf16_t *)resid, (bf16_t *)xsum);
+    RowArgs a = shrink_args(dm, A0, A1, row_model, T);
+    a.x = (bf16_t *)xsum; a.ldx = K; a.K = K; a.wn = (const bf16_t *)wn; a.eps = dm.eps; a.y = (bf16_t *)y;
+    a.psum = part; a.splits = splits; a.slice = slice; a.resid = (const bf16_t *)resid;
+    return launch_row<SRC_SLICES, true>(a.ldt / std::max(1, dm.M), R, st, a);
 }
 
 hipError_t launch_row_shrink(const Dims &dm, const void *x, int ldx, int R, int K, const void *A0, const int32_t *row_model, void *T,
                              hipStream_t st) {
     if (R <= 0) return hipSuccess;
-    return launch_ns<false>(dm.r, R, st, (const bf16_t *)x, ldx, K, nullptr, 0.f, nullptr, (const bf16_t *)A0, nullptr, dm.r, dm.M,
-                            row_model, dm.lora_scale, (bf16_t *)T, dm.M * dm.r, nullptr, 0);
+    RowArgs a = shrink_args(dm, A0, nullptr, row_model, T);
+    a.x = (bf16_t *)x; a.ldx = ldx; a.K = K;
+    return launch_row<SRC_PLAIN, false>(dm.r, R, st, a);
+}
+
+hipError_t launch_merge_shrink(const Dims &dm, const float *part_o, const float *part_ml, const AttnPlan &pl, const int32_t *row_pseq,
+                               void *attn, int R, const void *A0, const int32_t *row_model, void *T, hipStream_t st) {
+    if (R <= 0) return hipSuccess;
+    if (dm.D != kHeadChunks * 8) return hipErrorInvalidValue;
+    RowArgs a = shrink_args(dm, A0, nullptr, row_model, T);
+    a.x = (bf16_t *)attn; a.ldx = dm.Hq * dm.D; a.K = dm.Hq * dm.D;
+    a.part_o = part_o; a.part_ml = part_ml; a.row_pseq = row_pseq; a.seq_nparts = pl.seq_nparts; a.seq_part0 = pl.seq_part0;
+    a.seq_row0 = pl.seq_row0; a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.g_max = pl.g_max;
+    return launch_row<SRC_ATTN, false>(A0 ? dm.r : 0, R, st, a);
 }
 
 }  // namespace icarus
