@@ -455,17 +455,17 @@ hipError_t launch_cfg(GemmArgs g, hipStream_t st) {
 
 // Tile shapes (rows x weight rows x K slab, ring stages, waves).  What bounds a tile is the bytes it
 // pulls through the CU's vector memory path per MFMA cycle, 4096 (1/BM + 1/BN): 64 for 128 x 128
-// (the path's peak), 32 for 256 x 256.  Many rows (prefill): 256 x 256.  Few rows (decode): the
-// grid must still fill 256 CUs, so tiles stay 128 wide in N; the fused gate/up GEMM, which cannot
-// split K, takes one row tile that covers all stacked rows (every weight is then fetched by exactly
-// one workgroup); the narrow GEMMs take 128 x 128 tiles with narrow K slabs (two workgroups per CU)
-// and split K.
-enum TileKind { TILE_AUTO = 0, TILE_128, TILE_128_NARROW, TILE_256x128, TILE_384x128, TILE_384x128_W8, TILE_256x256,
-                TILE_128_K128, TILE_128x64_K128, TILE_256x256_K64, TILE_384x128_K64, TILE_256x128_K64, TILE_192x128_K64, TILE_192x128_K64_N3, TILE_192x128_K64_N2, TILE_64x128_K64_N3, TILE_64x128_K64_N5, TILE_KINDS };
-struct TileShape { int bm, bn; };
-constexpr TileShape kTileShape[TILE_KINDS] = {{0, 0}, {128, 128}, {128, 128}, {256, 128}, {384, 128}, {384, 128}, {256, 256},
-                                              {128, 128}, {128, 64}, {256, 256}, {384, 128}, {256, 128}, {192, 128}, {192, 128}, {192, 128}, {64, 128}, {64, 128}};
-constexpr int kTileBK[TILE_KINDS] = {0, 64, 32, 32, 32, 32, 32, 128, 128, 64, 64, 64, 64, 64, 64, 64, 64};
+// (the path's peak), 32 for 256 x 256.  Many rows (prefill): 256 x 256.  Few rows (decode): every
+// weight is used once, straight from HBM, and what counts is how the weight rows are fetched: 64-wide
+// K slabs ask for whole 128-byte lines (32-wide slabs ask for every line twice, half each time, and
+// stream at about 60% of the rate), the grid must fill 256 CUs, so tiles stay 128 wide in N and K is
+// split, and the row tile is the smallest that covers the stacked rows in one or two tiles (64, 128,
+// 192 rows), which keeps the activation re-reads and the ring small enough for two workgroups per CU.
+enum TileKind { TILE_AUTO = 0, TILE_128, TILE_128_NARROW, TILE_256x128, TILE_384x128_W8, TILE_256x256, TILE_256x256_K64,
+                TILE_192x128_N3, TILE_192x128_N2, TILE_64x128, TILE_KINDS };
+struct TileShape { int bm, bn, bk; };
+constexpr TileShape kTileShape[TILE_KINDS] = {{0, 0, 0},      {128, 128, 64}, {128, 128, 32}, {256, 128, 32}, {384, 128, 32},
+                                              {256, 256, 32}, {256, 256, 64}, {192, 128, 64}, {192, 128, 64}, {64, 128, 64}};
 
 // ICARUS_GEMM_CFG = "<tile kind>" forces one tile shape for every GEMM (experiments, tests).
 int forced_tile() {
@@ -491,16 +491,16 @@ int pick_tile_unchecked(const GemmArgs &g) {
     if (g.tile > 0 && g.tile < TILE_KINDS) return g.tile;
     if (int f = forced_tile()) return f;
     if (g.R >= 1024 && n_tiles_for(g, 256, 256) >= 192) return TILE_256x256_K64;  // enough large tiles for 256 CUs
-    if (g.R <= 64) return TILE_64x128_K64_N3;
+    if (g.R <= 64) return TILE_64x128;
     if (g.R <= 128) return TILE_128;
     if (g.mode == GEMM_DUAL && g.R > 192 && g.R <= 256) return TILE_256x128;
-    if (g.R <= 384) return g.mode == GEMM_DUAL ? TILE_192x128_K64_N2 : TILE_192x128_K64_N3;
+    if (g.R <= 384) return g.mode == GEMM_DUAL ? TILE_192x128_N2 : TILE_192x128_N3;  // DUAL cannot split K: two workgroups per CU
     return TILE_128;
 }
 
 int pick_tile(const GemmArgs &g) {
     int kind = pick_tile_unchecked(g);
-    return g.K % kTileBK[kind] ? TILE_128 : kind;  // K is a multiple of 64 at least
+    return g.K % kTileShape[kind].bk ? TILE_128 : kind;  // K is a multiple of 64 at least
 }
 
 }  // namespace
@@ -524,25 +524,18 @@ hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st) {
     else
         g.K_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
     if (g.splits < 1) g.splits = 1;
-    const int kind = pick_tile(g), bk = kTileBK[kind];
+    const int kind = pick_tile(g), bk = kTileShape[kind].bk;
     if (g.K % bk) return hipErrorInvalidValue;
     g.k_per_split = ((g.K_ext + g.splits - 1) / g.splits + bk - 1) / bk * bk;
     switch (kind) {
     case TILE_128_NARROW: return launch_cfg<128, 128, 32, 4, 2, 2>(g, st);
     case TILE_256x128: return launch_cfg<256, 128, 32, 4, 2, 2>(g, st);
-    case TILE_384x128: return launch_cfg<384, 128, 32, 4, 4, 1>(g, st);
     case TILE_384x128_W8: return launch_cfg<384, 128, 32, 4, 4, 2>(g, st);
     case TILE_256x256: return launch_cfg<256, 256, 32, 4, 2, 4>(g, st);
-    case TILE_128_K128: return launch_cfg<128, 128, 128, 2, 2, 2>(g, st);
-    case TILE_128x64_K128: return launch_cfg<128, 64, 128, 3, 2, 2>(g, st);
     case TILE_256x256_K64: return launch_cfg<256, 256, 64, 2, 2, 4>(g, st);
-    case TILE_384x128_K64: return launch_cfg<384, 128, 64, 2, 4, 2>(g, st);
-    case TILE_256x128_K64: return launch_cfg<256, 128, 64, 3, 2, 2>(g, st);
-    case TILE_192x128_K64: return launch_cfg<192, 128, 64, 4, 2, 2>(g, st);
-    case TILE_192x128_K64_N3: return launch_cfg<192, 128, 64, 3, 2, 2>(g, st);
-    case TILE_192x128_K64_N2: return launch_cfg<192, 128, 64, 2, 2, 2>(g, st);
-    case TILE_64x128_K64_N3: return launch_cfg<64, 128, 64, 3, 2, 2>(g, st);
-    case TILE_64x128_K64_N5: return launch_cfg<64, 128, 64, 5, 2, 2>(g, st);
+    case TILE_192x128_N3: return launch_cfg<192, 128, 64, 3, 2, 2>(g, st);
+    case TILE_192x128_N2: return launch_cfg<192, 128, 64, 2, 2, 2>(g, st);
+    case TILE_64x128: return launch_cfg<64, 128, 64, 3, 2, 2>(g, st);
     default: return launch_cfg<128, 128, 64, 4, 2, 2>(g, st);
     }
 }
