@@ -204,3 +204,54 @@ def make_kv_tokens(shape: LayerShape, n_tokens: int, seed: int = 0, tag: int = 0
     K = rng.standard_normal((n_tokens, shape.n_kv_heads, shape.head_dim), dtype=np.float32)
     V = rng.standard_normal((n_tokens, shape.n_kv_heads, shape.head_dim), dtype=np.float32)
     return to_storage(K, shape.bf16), to_storage(V, shape.bf16)
+
+
+# ---- multi-agent conversations for the prefix-cache manager -----------------------------------
+@dataclass
+class AgentTurn:
+    conversation: int
+    model: int
+    context: np.ndarray      # int32: every token the agent sees when it is invoked (prompt + all earlier turns)
+    new_tokens: np.ndarray   # int32: what this turn appends (the agent's output, then the tool observation)
+    n_generated: int         # how many of new_tokens the agent generates itself (the rest is observation text)
+
+
+def make_agent_schedule(n_conversations: int, n_models: int, turns: int, seed: int = 0, pattern: str = "round_robin",
+                        prompt_len=(600, 1400), out_len=(40, 160), obs_len=(60, 400), shared_system_prompt: int = 256,
+                        concurrency: int = 4, vocab: int = 32000):
+    """Seeded stand-in for the paper's agentic workload (Sec. 4.3, App. A.2: a ReAct-style loop in which a
+    controller hands one shared, growing context to one of N task agents per turn; App. F: `skewed` = one
+    agent is chosen with probability 1/2, the others share the rest at random; `round_robin` = fixed order).
+    Conversations start with a system prompt common to all of them, then their own question; every turn
+    appends the agent's output and an observation.  `concurrency` conversations are in progress at a time and
+    take turns in rotation.  Returns the list of AgentTurn in service order."""
+    rng = np.random.default_rng(np.random.SeedSequence([seed, 1009, n_conversations, n_models, turns, 0 if pattern == "round_robin" else 1]))
+    system = rng.integers(0, vocab, size=shared_system_prompt, dtype=np.int32)
+    ctx, done, model_next = {}, {}, {}
+    for c in range(n_conversations):
+        n = int(rng.integers(prompt_len[0], prompt_len[1] + 1))
+        ctx[c] = np.concatenate([system, rng.integers(0, vocab, size=max(1, n - shared_system_prompt), dtype=np.int32)])
+        done[c] = 0
+        model_next[c] = int(rng.integers(0, n_models))
+    out = []
+    active, waiting = [], list(range(n_conversations))
+    while active or waiting:
+        while waiting and len(active) < concurrency:
+            active.append(waiting.pop(0))
+        c = active.pop(0)
+        if pattern == "round_robin":
+            m = model_next[c]
+            model_next[c] = (m + 1) % n_models
+        elif pattern == "skewed":
+            m = 0 if (n_models == 1 or rng.random() < 0.5) else int(rng.integers(1, n_models))
+        else:
+            raise ValueError(pattern)
+        n_out = int(rng.integers(out_len[0], out_len[1] + 1))
+        n_obs = int(rng.integers(obs_len[0], obs_len[1] + 1))
+        new = rng.integers(0, vocab, size=n_out + n_obs, dtype=np.int32)
+        out.append(AgentTurn(c, m, ctx[c].copy(), new, n_out))
+        ctx[c] = np.concatenate([ctx[c], new])
+        done[c] += 1
+        if done[c] < turns:
+            active.append(c)
+    return out
