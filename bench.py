@@ -164,6 +164,60 @@ def main_prefill(args):
     print(json.dumps(out))
 
 
+def main_prefix_cache(args):
+    """Host-side prefix-cache manager under the synthetic multi-agent schedules: the memory and prefill
+    arguments of Table 1 as measured counts, shared keys (ICaRus) against per-adapter keys (baseline)."""
+    from paper_2603_13281_amd import binding, cache_sim, synth
+
+    B = 16
+    rows = []
+    t_lib = n_ops = 0
+    for pattern in ("round_robin", "skewed"):
+        for n_models in (2, 4, 8):
+            sched = synth.make_agent_schedule(64, n_models, 2 * n_models, seed=0, pattern=pattern)
+            final_tokens = {}
+            for t in sched:
+                final_tokens[t.conversation] = len(t.context) + len(t.new_tokens)
+            shared_need = sum(-(-n // B) for n in final_tokens.values())
+            tight = int(1.5 * 4 * (max(final_tokens.values()) // B + 1))   # 4 conversations are in progress at a time
+            r = {"pattern": pattern, "models": n_models, "turns": len(sched), "context_blocks": shared_need, "tight_pool_blocks": tight}
+            for name, per_model in (("shared", False), ("per_model", True)):
+                big = binding.PrefixCache(1 << 22, B, per_model)        # never full: what would like to stay resident
+                t0 = time.perf_counter()
+                out = cache_sim.run_schedule(big, sched)
+                t_lib += time.perf_counter() - t0
+                n_ops += 4 * len(sched)
+                big.close()
+                small = binding.PrefixCache(tight, B, per_model)   # room for 1.5 x the contexts in progress, kept once
+                out_s = cache_sim.run_schedule(small, sched)
+                small.close()
+                r[name] = {"resident_blocks": out["cached"], "prefill_tokens": out["prefill_tokens"],
+                           "tight_pool_prefill_tokens": out_s["prefill_tokens"], "tight_pool_evictions": out_s["evictions"]}
+            r["resident_ratio"] = r["per_model"]["resident_blocks"] / r["shared"]["resident_blocks"]
+            r["prefill_ratio"] = r["per_model"]["prefill_tokens"] / r["shared"]["prefill_tokens"]
+            r["tight_pool_prefill_ratio"] = r["per_model"]["tight_pool_prefill_tokens"] / r["shared"]["tight_pool_prefill_tokens"]
+            rows.append(r)
+            log(f"[bench] {pattern:11s} N={n_models}: resident blocks x{r['resident_ratio']:.2f}, prefill tokens x{r['prefill_ratio']:.2f}, "
+                f"in a pool of {tight} blocks x{r['tight_pool_prefill_ratio']:.2f}")
+    base = None
+    if not args.no_cpu_baseline:
+        import oracle.prefix_cache as opc
+        sched = synth.make_agent_schedule(16, 4, 8, seed=0, pattern="round_robin")
+        t0 = time.perf_counter()
+        cache_sim.run_schedule(opc.OraclePrefixCache(1 << 20, B, False), sched)
+        dt = time.perf_counter() - t0
+        base = {"value": 4 * len(sched) / dt, "unit": "manager calls/s", "cores": 1, "kind": "oracle",
+                "sample": f"{len(sched)} turns of 16 conversations, 4 adapters, {dt:.2f} s", "seconds": dt}
+    head = next(r for r in rows if r["pattern"] == "round_robin" and r["models"] == 8)
+    print(json.dumps({"metric": "KV blocks kept resident by per-adapter prefix keys / by shared (ICaRus) keys, 8 adapters, round robin",
+                      "value": head["resident_ratio"], "unit": "x", "n_gpus": 0, "steps": len(rows), "warmup": 0,
+                      "ms_per_step": 1e3 * t_lib / max(n_ops, 1), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                      "dtype": "int32", "data": "synthetic",
+                      "config": {"workload": "prefix-cache manager (host): 64 conversations, 2N turns each, system prompt shared, "
+                                             "contexts 0.6-1.4 k tokens growing by 0.1-0.56 k per turn, block 16"},
+                      "manager_calls_per_s": n_ops / t_lib, "roofline": None, "cpu_baseline": base, "results": rows}))
+
+
 def main_stack(args):
     """Layer stack: one step = icarus_stack_decode of the whole batch (embedding, every layer, final norm,
     LM head, greedy token), the sequences' next tokens fed back on the device."""
@@ -246,7 +300,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c4", "c4-small", "stack", "stack-small"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c4", "c4-small", "stack", "stack-small", "prefix-cache"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-private-kv-baseline", action="store_true",
                     help="skip the conventional per-model-KV run of the same traffic (same kernels, M private caches)")
@@ -257,6 +311,8 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "prefix-cache":      # host-side bookkeeping only
+        return main_prefix_cache(args)
 
     import numpy as np
     import torch

@@ -26,7 +26,9 @@ STATUS = {0: "OK", 1: "INVALID_ARG", 2: "SHAPE", 3: "ALIGNMENT", 4: "MODEL_ID", 
 EXPORTS = ("icarus_create", "icarus_destroy", "icarus_last_error", "icarus_workspace_bytes",
            "icarus_validate_decode", "icarus_prefill_kv", "icarus_decode_step", "icarus_attn_shared_kv",
            "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read", "icarus_bench_copy", "icarus_bench_mfma", "icarus_stack_create", "icarus_stack_destroy",
-           "icarus_stack_last_error", "icarus_stack_workspace_bytes", "icarus_stack_prefill", "icarus_stack_decode")
+           "icarus_stack_last_error", "icarus_stack_workspace_bytes", "icarus_stack_prefill", "icarus_stack_decode",
+           "icarus_cache_create", "icarus_cache_destroy", "icarus_cache_last_error", "icarus_cache_acquire", "icarus_cache_extend",
+           "icarus_cache_commit", "icarus_cache_release", "icarus_cache_get_stats")
 
 PHASES = ("norm", "lora", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gateup", "gemm_down",
           "elementwise")
@@ -58,6 +60,15 @@ class _Lora(C.Structure):
 class _StackCfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("vocab", C.c_int32), ("layers", C.POINTER(C.c_void_p)),
                 ("embed", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+class _CacheCfg(C.Structure):
+    _fields_ = [("num_blocks", C.c_int32), ("block_size", C.c_int32), ("key_by_model", C.c_int32)]
+
+
+class _CacheStats(C.Structure):
+    _fields_ = [("lookups", C.c_int64), ("hit_tokens", C.c_int64), ("miss_tokens", C.c_int64), ("evictions", C.c_int64),
+                ("live", C.c_int32), ("cached", C.c_int32), ("free_blocks", C.c_int32), ("peak_live", C.c_int32)]
 
 
 def _load():
@@ -104,6 +115,23 @@ def _load():
     lib.icarus_stack_prefill.argtypes = [vp, C.POINTER(vp), vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.icarus_stack_decode.restype = C.c_int
     lib.icarus_stack_decode.argtypes = [vp, C.POINTER(vp), vp, C.c_int32, C.c_int32, vp, C.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    i32, pi32 = C.c_int32, C.POINTER(C.c_int32)
+    lib.icarus_cache_create.restype = C.c_int
+    lib.icarus_cache_create.argtypes = [C.POINTER(_CacheCfg), C.POINTER(vp)]
+    lib.icarus_cache_destroy.restype = None
+    lib.icarus_cache_destroy.argtypes = [vp]
+    lib.icarus_cache_last_error.restype = C.c_char_p
+    lib.icarus_cache_last_error.argtypes = [vp]
+    lib.icarus_cache_acquire.restype = C.c_int
+    lib.icarus_cache_acquire.argtypes = [vp, vp, i32, i32, i32, vp, i32, pi32, pi32]
+    lib.icarus_cache_extend.restype = C.c_int
+    lib.icarus_cache_extend.argtypes = [vp, vp, i32, pi32, i32]
+    lib.icarus_cache_commit.restype = C.c_int
+    lib.icarus_cache_commit.argtypes = [vp, vp, i32, i32, vp, i32]
+    lib.icarus_cache_release.restype = C.c_int
+    lib.icarus_cache_release.argtypes = [vp, vp, i32]
+    lib.icarus_cache_get_stats.restype = C.c_int
+    lib.icarus_cache_get_stats.argtypes = [vp, C.POINTER(_CacheStats)]
     return lib
 
 
@@ -395,3 +423,62 @@ class IcarusStack:
                                              _ptr(row_seq), _ptr(row_model), _ptr(seq_token), _ptr(row_next), _ptr(seq_next),
                                              _ptr(logits), _ptr(ws), ws.numel(), stream))
         return row_next, logits
+
+
+class PrefixCache:
+    """icarus_cache_*: the cross-model prefix-cache manager (host side).  Marshalling only."""
+
+    def __init__(self, num_blocks: int, block_size: int, key_by_model: bool):
+        self.num_blocks, self.block_size, self.key_by_model = int(num_blocks), int(block_size), bool(key_by_model)
+        self._h = C.c_void_p()
+        cfg = _CacheCfg(self.num_blocks, self.block_size, int(self.key_by_model))
+        rc = _lib.icarus_cache_create(C.byref(cfg), C.byref(self._h))
+        if rc != 0:
+            raise IcarusError(rc, (_lib.icarus_cache_last_error(None) or b"").decode())
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.icarus_cache_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def _check(self, rc):
+        if rc != 0:
+            raise IcarusError(rc, (_lib.icarus_cache_last_error(self._h) or b"").decode())
+
+    @staticmethod
+    def _i32(a):
+        return np.ascontiguousarray(a, dtype=np.int32)
+
+    def acquire(self, tokens, model: int, reserve: int = 0):
+        """-> (block ids of the sequence, number of leading tokens whose K/V is already cached)"""
+        t = self._i32(tokens)
+        cap = (len(t) + reserve + self.block_size - 1) // self.block_size
+        out = np.empty(max(cap, 1), dtype=np.int32)
+        nb, nc = C.c_int32(0), C.c_int32(0)
+        self._check(_lib.icarus_cache_acquire(self._h, t.ctypes.data, len(t), int(model), int(reserve), out.ctypes.data, cap,
+                                              C.byref(nb), C.byref(nc)))
+        return out[: nb.value].tolist(), nc.value
+
+    def extend(self, blocks, n_tokens_total: int):
+        cap = max(len(blocks), (int(n_tokens_total) + self.block_size - 1) // self.block_size, 1)
+        buf = np.empty(cap, dtype=np.int32)
+        buf[: len(blocks)] = blocks
+        nb = C.c_int32(len(blocks))
+        self._check(_lib.icarus_cache_extend(self._h, buf.ctypes.data, cap, C.byref(nb), int(n_tokens_total)))
+        return buf[: nb.value].tolist()
+
+    def commit(self, tokens, model: int, blocks):
+        t, b = self._i32(tokens), self._i32(blocks)
+        self._check(_lib.icarus_cache_commit(self._h, t.ctypes.data, len(t), int(model), b.ctypes.data, len(b)))
+
+    def release(self, blocks):
+        b = self._i32(blocks)
+        self._check(_lib.icarus_cache_release(self._h, b.ctypes.data, len(b)))
+
+    def counts(self) -> dict:
+        st = _CacheStats()
+        self._check(_lib.icarus_cache_get_stats(self._h, C.byref(st)))
+        return dict(lookups=st.lookups, hit_tokens=st.hit_tokens, miss_tokens=st.miss_tokens, evictions=st.evictions,
+                    peak_live=st.peak_live, live=st.live, cached=st.cached, free=st.free_blocks)

@@ -29,7 +29,8 @@ def _weights(addr=FAKE):
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "icarus.h")).read()
+    import glob
+    hdr = "".join(open(h).read() for h in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(icarus_[a-z_0-9]+)\s*\(", hdr))
     assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
