@@ -38,7 +38,8 @@ class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "block_size", "num_blocks",
         "n_models", "lora_rank", "lora_target_mask", "qk_norm", "bf16")] + [
-        ("rope_theta", C.c_double), ("rms_eps", C.c_double), ("lora_scale", C.c_double)]
+        ("rope_theta", C.c_double), ("rms_eps", C.c_double), ("lora_scale", C.c_double),
+        ("kv_fp8", C.c_int32), ("k_scale", C.c_double), ("v_scale", C.c_double)]
 
 
 class _Base(C.Structure):
@@ -59,6 +60,8 @@ def lib():
         _lib = C.CDLL(build())
         _lib.orc_round_bf16.restype = C.c_double
         _lib.orc_round_bf16.argtypes = [C.c_double]
+        _lib.orc_round_e4m3.restype = C.c_double
+        _lib.orc_round_e4m3.argtypes = [C.c_double]
         _lib.orc_slot.restype = C.c_int64
         _lib.orc_slot.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         _lib.orc_decode_step.restype = C.c_int
@@ -96,6 +99,9 @@ class LayerConfig:
     rope_theta: float = 1e4
     rms_eps: float = 1e-5
     lora_scale: float = 2.0
+    kv_fp8: bool = False        # the cache holds FP8 E4M3 codes: value = code * k_scale (K) or v_scale (V)
+    k_scale: float = 1.0
+    v_scale: float = 1.0
 
     def proj_in(self, p: str) -> int:
         return {"q": self.d_model, "k": self.d_model, "v": self.d_model, "gate": self.d_model,
@@ -110,7 +116,8 @@ class LayerConfig:
         return _Cfg(self.d_model, self.n_q_heads, self.n_kv_heads, self.head_dim, self.d_ffn,
                     self.block_size, self.num_blocks, self.n_models, self.lora_rank,
                     self.lora_target_mask, int(self.qk_norm), int(self.bf16),
-                    float(self.rope_theta), float(self.rms_eps), float(self.lora_scale))
+                    float(self.rope_theta), float(self.rms_eps), float(self.lora_scale),
+                    int(self.kv_fp8), float(self.k_scale), float(self.v_scale))
 
 
 class Oracle:
@@ -250,6 +257,11 @@ class OracleStack:
 
 
 # -- primitives exposed for the pin tests ------------------------------------
+
+def round_e4m3(x) -> np.ndarray:
+    f = np.vectorize(lambda v: lib().orc_round_e4m3(float(v)), otypes=[np.float64])
+    return f(np.asarray(x, dtype=np.float64))
+
 
 def round_bf16(x) -> np.ndarray:
     f = np.vectorize(lambda v: lib().orc_round_bf16(float(v)), otypes=[np.float64])

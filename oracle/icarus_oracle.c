@@ -47,6 +47,8 @@ typedef struct {
     int32_t qk_norm;          /* per-head RMSNorm on q and k before RoPE */
     int32_t bf16;             /* 1: cache and x_out hold bf16 values; 0: float32 */
     double rope_theta, rms_eps, lora_scale;
+    int32_t kv_fp8;           /* 1: the cache holds FP8 E4M3 codes with one scale for all K and one for all V */
+    double k_scale, v_scale;  /* value = code * scale (kv_fp8 only) */
 } orc_config;
 
 typedef struct {
@@ -88,6 +90,30 @@ double orc_round_bf16(double x) {
     if (q < -133) q = -133;       /* bf16 subnormal quantum 2^-133 */
     double r = ldexp(nearbyint(ldexp(x, -q)), q); /* nearbyint: ties-to-even */
     return r;
+}
+/* Round a double to the nearest FP8 E4M3 value of the OCP 8-bit floating point
+ * specification (4 exponent bits, bias 7, 3 mantissa bits, no infinities, largest
+ * finite value 448, subnormals down to 2^-9), ties to even; magnitudes beyond 448
+ * saturate to +-448.  The quantised KV cache is this paper's "orthogonal" prior
+ * work (Sec. 1); the format is that of the hardware's FP8 conversions. */
+double orc_round_e4m3(double x) {
+    if (x == 0.0 || isnan(x)) return x;
+    double a = fabs(x);
+    if (a >= 448.0) return copysign(448.0, x);
+    int e;
+    (void)frexp(a, &e);           /* a = m * 2^e, m in [0.5,1) */
+    int q = e - 4;                /* quantum exponent for 4 significant bits */
+    if (q < -9) q = -9;           /* subnormal quantum 2^-9 (smallest normal 2^-6) */
+    double r = ldexp(nearbyint(ldexp(a, -q)), q);
+    if (r > 448.0) r = 448.0;
+    return copysign(r, x);
+}
+
+/* What the cache holds for a K (kv = 0) or V (kv = 1) element x. */
+static double round_cache(const orc_config *c, double x, int kv) {
+    if (!c->kv_fp8) return c->bf16 ? orc_round_bf16(x) : (double)(float)x;
+    double s = kv ? c->v_scale : c->k_scale;
+    return orc_round_e4m3(x / s) * s;
 }
 static double round_store(const orc_config *c, double x) {
     return c->bf16 ? orc_round_bf16(x) : (double)(float)x;
@@ -191,8 +217,8 @@ static int64_t cache_append(const orc_config *c, float *pool, const int32_t *bt_
     for (int h = 0; h < c->n_kv_heads; ++h) {
         float *kd = pool_at(c, pool, slot, 0, h), *vd = pool_at(c, pool, slot, 1, h);
         for (int i = 0; i < c->head_dim; ++i) {
-            kd[i] = (float)round_store(c, k[(size_t)h * c->head_dim + i]);
-            vd[i] = (float)round_store(c, v[(size_t)h * c->head_dim + i]);
+            kd[i] = (float)round_cache(c, k[(size_t)h * c->head_dim + i], 0);
+            vd[i] = (float)round_cache(c, v[(size_t)h * c->head_dim + i], 1);
         }
     }
     return slot;
