@@ -94,7 +94,8 @@ def cpu_baseline(wl, step, x_dev_out, prefixes):
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     tol = 2e-2 if sh.bf16 else 1e-4
     info = sampled.decode_sample_check(sh, wl.base, wl.lora, prefixes, ctx, b.row_seq, b.row_model,
-                                       wl.x_host[step % len(wl.x_host)], x_dev_out, tol, "bench sample vs oracle")
+                                       wl.x_host[step % len(wl.x_host)], x_dev_out, tol, "bench sample vs oracle",
+                                       kv_scales=wl.kv_scales)
     dt, n_dec = info["seconds"], info["decoder_rows"]
     return {"value": n_dec / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"sequences {info['sample']} of the workload at step {step}: {info['rows']} rows ({n_dec} decoder rows), "
@@ -300,7 +301,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c4", "c4-small", "stack", "stack-small", "prefix-cache"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c3-fp8", "c3-small-fp8", "c4", "c4-small", "stack", "stack-small", "prefix-cache"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-private-kv-baseline", action="store_true",
                     help="skip the conventional per-model-KV run of the same traffic (same kernels, M private caches)")
@@ -338,7 +339,7 @@ def main():
     wl = workloads.build_decode_workload(args.workload, dev, headroom=2 * (K + W) + 16, verbose=True)
     wl.layer.set_kernel_mode(args.kernel_mode)
     log(f"[bench] workload built in {time.perf_counter() - t_build:.1f} s: R={wl.batch.R} rows "
-        f"({wl.batch.n_decoder_rows} decoder), S={wl.batch.S}, pool {wl.pool.numel() * 2 / 2**30:.2f} GiB")
+        f"({wl.batch.n_decoder_rows} decoder), S={wl.batch.S}, pool {wl.pool.numel() * wl.pool.element_size() / 2**30:.2f} GiB")
     x_out = torch.empty_like(wl.x[0])
 
     # parity sample + CPU baseline at step 0 (before the timed steps append to the cache)
@@ -347,10 +348,10 @@ def main():
     torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         import sampled
-        nseq = {"c2": 1, "c3": 32, "c5": 4, "c3-small": 8}[args.workload]
+        nseq = {"c2": 1, "c3": 32, "c3-fp8": 32, "c5": 4, "c3-small": 8, "c3-small-fp8": 8}[args.workload]
         sample = [int(s) for s in np.random.default_rng(12345).permutation(wl.batch.S)[:nseq]]
         # positions 0..L_s-1 of the cache are what the step read; the step itself appended position L_s
-        prefixes = sampled.snapshot_prefixes(wl.shape, wl.pool, wl.batch.block_tables, wl.ctx_lens(0), sample)
+        prefixes = sampled.snapshot_prefixes(wl.shape, wl.pool, wl.batch.block_tables, wl.ctx_lens(0), sample, wl.kv_scales)
         base = cpu_baseline(wl, 0, x_out, prefixes)
         log(f"[bench] cpu baseline: {base['value']:.2f} tok/s on {base['cores']} threads; sample parity ok")
 
@@ -401,7 +402,7 @@ def main():
 
     # the conventional alternative on the same GPU and kernels: a private KV cache per (sequence, model)
     private = None
-    if not args.no_private_kv_baseline:
+    if not args.no_private_kv_baseline and wl.kv_scales is None:
         kb = min(K, 20)
         pw = workloads.build_private_kv_baseline(wl, dev)
         py = torch.empty_like(pw.x[0])

@@ -78,11 +78,20 @@ typedef struct icarus_layer_config {
     int32_t dtype;            /* ICARUS_F32 or ICARUS_BF16 */
     int32_t qk_norm;          /* 1: per-head RMSNorm on q and k before RoPE */
     int32_t max_position;     /* largest position + 1 any call may touch */
-    int32_t reserved;
+    int32_t kv_dtype;         /* ICARUS_KV_SAME: cache elements have `dtype`; ICARUS_KV_FP8_E4M3: 1-byte codes */
     double rope_theta;        /* RoPE base; rotate-half pairing (i, i + head_dim/2) */
     double rms_eps;
     double lora_scale;        /* s = alpha / r */
+    double k_scale, v_scale;  /* ICARUS_KV_FP8_E4M3 only, > 0: cached value = code * k_scale (K) or * v_scale (V) */
 } icarus_layer_config;
+
+/* Quantised shared cache (the paper names KV quantisation as orthogonal prior work, Sec. 1; the scheme is that of
+ * the serving stacks it builds on: one static scale for all K and one for all V of a layer, calibrated by the
+ * caller).  Codes are OCP FP8 E4M3 (bias 7, largest finite value 448, no infinities): on append
+ * code = round-to-nearest-even(clamp(x / scale, -448, 448)); on read value = code * scale.  The pool has the same
+ * shape with 1-byte elements: pool[num_blocks][n_kv_heads][2][block_size * head_dim] bytes.  K is quantised after
+ * RoPE.  Activations and weights keep `dtype`. */
+enum { ICARUS_KV_SAME = 0, ICARUS_KV_FP8_E4M3 = 1 };
 
 typedef struct icarus_base_weights { /* all DEVICE, dtype elements */
     const void *w[ICARUS_NPROJ];       /* W_q [Hq*D, d], W_k, W_v [Hkv*D, d], W_o [d, Hq*D],

@@ -44,8 +44,9 @@ class IcarusError(RuntimeError):
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "block_size", "num_blocks", "n_models",
-        "lora_rank", "lora_target_mask", "dtype", "qk_norm", "max_position", "reserved")] + [
-        ("rope_theta", C.c_double), ("rms_eps", C.c_double), ("lora_scale", C.c_double)]
+        "lora_rank", "lora_target_mask", "dtype", "qk_norm", "max_position", "kv_dtype")] + [
+        ("rope_theta", C.c_double), ("rms_eps", C.c_double), ("lora_scale", C.c_double),
+        ("k_scale", C.c_double), ("v_scale", C.c_double)]
 
 
 class _Base(C.Structure):
@@ -160,16 +161,24 @@ class LayerConfig:
     rope_theta: float = 5e5
     rms_eps: float = 1e-5
     lora_scale: float = 2.0
+    kv_fp8: bool = False      # the KV pool holds FP8 E4M3 codes: value = code * k_scale (K) or v_scale (V)
+    k_scale: float = 1.0
+    v_scale: float = 1.0
 
     def _c(self) -> _Cfg:
         return _Cfg(self.d_model, self.n_q_heads, self.n_kv_heads, self.head_dim, self.d_ffn, self.block_size,
                     self.num_blocks, self.n_models, self.lora_rank, self.lora_target_mask,
-                    BF16 if self.bf16 else F32, int(self.qk_norm), self.max_position, 0,
-                    float(self.rope_theta), float(self.rms_eps), float(self.lora_scale))
+                    BF16 if self.bf16 else F32, int(self.qk_norm), self.max_position, 1 if self.kv_fp8 else 0,
+                    float(self.rope_theta), float(self.rms_eps), float(self.lora_scale), float(self.k_scale), float(self.v_scale))
 
     @property
     def torch_dtype(self):
         return torch.bfloat16 if self.bf16 else torch.float32
+
+    @property
+    def pool_dtype(self):
+        """Element type of the KV pool tensor (FP8 codes are handed over as raw bytes)."""
+        return torch.uint8 if self.kv_fp8 else self.torch_dtype
 
     def pool_shape(self):
         """[num_blocks, n_kv_heads, 2, block_size*head_dim]: plane 0 = K [Bk, D], plane 1 = V^T [D, Bk]."""

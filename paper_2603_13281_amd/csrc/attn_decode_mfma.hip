@@ -242,6 +242,150 @@ __device__ __forceinline__ void shared_walk(State<NT> &st, const bf16_t *__restr
     __syncthreads();  // the ring may be reused now
 }
 
+// ---- FP8 (E4M3) cache: 1-byte codes, value = code * scale (one scale for K, one for V) ----------------
+// The codes are exact in bf16, so they go through the same bf16 MFMAs after a register conversion; the
+// scales are folded into the softmax scale (K) and the final normalisation (V).  Loads stay 16 bytes
+// per lane for K: a lane's 16 codes are 16 consecutive d of one token, i.e. the lane's operand
+// elements of TWO k-steps, so the contraction index is laid out differently from the bf16 path
+//   k-step 2s + h, lane quarter q  <->  d = 64 s + 16 q + 8 h .. + 7
+// and the Q fragments are staged in the same order (a dot product does not care).  V^T rows hold 16
+// tokens in 16 bytes; a lane needs the 8 of its quarter: 8-byte loads, 16 rows x 16 bytes of a block
+// fully used by each wave-wide load.
+struct KVRaw8 {
+    uint4 k[2][2];  // k[t][s]: tile t, d slab s (64 codes per row, 16 per lane)
+    uint2 v[kDT];   // v[dt]: 8 tokens of row d = 16 dt + l%16
+};
+
+__device__ __forceinline__ void load_group8(KVRaw8 &f, const uint8_t *__restrict__ pool, int blk0, int blk1, int c, int Hkv,
+                                            int lane) {
+    const int m = lane & 15, q = lane >> 4;
+    const size_t head_stride = (size_t)2 * kBk * kD;  // bytes
+    const uint8_t *kb = pool + ((size_t)((m >> 3) ? blk1 : blk0) * Hkv + c) * head_stride;
+    const int tok0 = 8 * ((m >> 2) & 1) + (m & 3);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) f.k[t][sl] = *(const uint4 *)(kb + (size_t)(tok0 + 4 * t) * kD + 64 * sl + 16 * q);
+    const uint8_t *vb = pool + ((size_t)((q >> 1) ? blk1 : blk0) * Hkv + c) * head_stride + (size_t)kBk * kD;
+#pragma unroll
+    for (int dt = 0; dt < kDT; ++dt) f.v[dt] = *(const uint2 *)(vb + (size_t)(16 * dt + m) * kBk + 8 * (q & 1));
+}
+
+// 8 FP8 codes (two dwords) -> 8 bf16, exactly.
+__device__ __forceinline__ bf16x8 cvt8(uint32_t lo, uint32_t hi) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    uint4 r;
+    r.x = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false));
+    r.y = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true));
+    r.z = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false));
+    r.w = __builtin_bit_cast(uint32_t, (bf16x2)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true));
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// compute_group for raw FP8 fragments: the scores of all N tiles first (K codes are converted one
+// k-step at a time and die at once), then the softmax of every tile, then PV with V^T codes converted
+// one d tile at a time.  scale_log2 includes the K scale; the V scale is applied when the piece ends.
+template <int NT, int N, bool tail>
+__device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, const bf16x8 *__restrict__ qlds, int left,
+                                               const int (&stag)[NT], float scale_log2, int lane) {
+    const int q = lane >> 4;
+    const int tbase = 16 * (q >> 1) + 8 * (q & 1);
+    f32x4 s0[N], s1[N];
+#pragma unroll
+    for (int qt = 0; qt < N; ++qt) { s0[qt] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[qt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+    for (int ks = 0; ks < kKS; ++ks) {
+        const uint4 r0 = f.k[0][ks >> 1], r1 = f.k[1][ks >> 1];
+        const bf16x8 a0 = (ks & 1) ? cvt8(r0.z, r0.w) : cvt8(r0.x, r0.y);
+        const bf16x8 a1 = (ks & 1) ? cvt8(r1.z, r1.w) : cvt8(r1.x, r1.y);
+#pragma unroll
+        for (int qt = 0; qt < N; ++qt) {
+            bf16x8 qv = qlds[(qt * kKS + ks) * 64 + lane];
+            s0[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qv, s0[qt], 0, 0, 0);
+            s1[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qv, s1[qt], 0, 0, 0);
+        }
+    }
+    bf16x8 pb[N];
+#pragma unroll
+    for (int qt = 0; qt < N; ++qt) {
+        float sv[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sv[i] = s0[qt][i] * scale_log2;
+            sv[4 + i] = s1[qt][i] * scale_log2;
+        }
+        if (tail) {
+            const int lim = left - stag[qt];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (tbase + e >= lim) sv[e] = -INFINITY;  // also replaces whatever stale codes produced
+        }
+        float mx = sv[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+        if (__any(mx > st.m[qt] + kSlack)) {  // see compute_group: lazy softmax reference
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_old = st.m[qt];
+            const float m_new = fmaxf(m_old, mx);
+            st.m[qt] = m_new;
+            float alpha = (tail && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_old - m_new);
+            st.l[qt] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) {
+                st.o[dt][qt][0] *= alpha; st.o[dt][qt][1] *= alpha; st.o[dt][qt][2] *= alpha; st.o[dt][qt][3] *= alpha;
+            }
+        }
+        const float m_ref = st.m[qt];
+        float rs = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float p = __builtin_amdgcn_exp2f(sv[e] - m_ref);
+            if (tail && m_ref == -INFINITY) p = 0.f;
+            rs += p;
+            pb[qt][e] = (__bf16)p;
+        }
+        st.l[qt] += rs;
+    }
+#pragma unroll
+    for (int dt = 0; dt < kDT; ++dt) {
+        bf16x8 av = cvt8(f.v[dt].x, f.v[dt].y);
+        if (tail) {  // stale codes past the end may decode to anything, NaN included
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (tbase + e >= left) av[e] = (__bf16)0.f;
+        }
+#pragma unroll
+        for (int qt = 0; qt < N; ++qt) st.o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[qt], st.o[dt][qt], 0, 0, 0);
+    }
+}
+
+// wave_walk over an FP8 cache: the two register buffers hold raw codes (48 registers each).
+template <int NT, int N>
+__device__ __forceinline__ void wave_walk8(State<NT> &st, const uint8_t *__restrict__ pool, const int *__restrict__ blds,
+                                           int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int first, int stride,
+                                           int c, int Hkv, const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
+    const int n_grp = (n_tok + kGrp - 1) / kGrp;
+    auto blk_of = [&](int grp, int which) {
+        return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
+    };
+    KVRaw8 f0, f1;
+    if (first < n_clean) load_group8(f0, pool, blk_of(first, 0), blk_of(first, 1), c, Hkv, lane);
+#pragma nounroll
+    for (int grp = first; grp < n_clean; grp += 2 * stride) {
+        if (grp + stride < n_clean) load_group8(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
+        compute_group8<NT, N, false>(st, f0, qlds, kGrp, stag, scale_log2, lane);
+        if (grp + 2 * stride < n_clean) load_group8(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
+        if (grp + stride < n_clean) compute_group8<NT, N, false>(st, f1, qlds, kGrp, stag, scale_log2, lane);
+    }
+#pragma nounroll
+    for (int grp = n_clean; grp < n_grp; ++grp) {
+        if (grp % stride != first) continue;
+        load_group8(f0, pool, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
+        compute_group8<NT, N, true>(st, f0, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
+    }
+}
+
 // LDS image of a state: o as [dt][qt][i][lane], then m[qt][lane], l[qt][lane].
 template <int NT>
 __device__ __forceinline__ void merge_from_lds(State<NT> &st, const float *__restrict__ lds, int lane) {
@@ -316,11 +460,15 @@ __device__ __forceinline__ void finish(State<NT> &st, int qt0, int n, int G, int
 }
 
 // NA: query tiles of waves 0,1 (of all four waves when NB == 0); NB: query tiles of waves 2,3.
-template <int NA, int NB>
-__global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ qg, const bf16_t *__restrict__ pool,
+// KV8: the pool holds FP8 codes (scale_log2 then includes the K scale, v_scale multiplies the output).
+template <int NA, int NB, bool KV8 = false>
+__global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ qg, const void *__restrict__ pool_v,
                                                      const int32_t *__restrict__ bt, int max_blocks, AttnPlan pl,
                                                      bf16_t *__restrict__ out, float *__restrict__ part_o,
-                                                     float *__restrict__ part_ml, int Hq, int Hkv, float scale_log2) {
+                                                     float *__restrict__ part_ml, int Hq, int Hkv, float scale_log2,
+                                                     float v_scale) {
+    static_assert(!KV8 || NB == 0, "the FP8 cache path covers up to three query tiles");
+    const bf16_t *pool = (const bf16_t *)pool_v;
     constexpr int NQT = NA + NB;
     constexpr int kImg = kDT * NA * 4 * 64 + 2 * NA * 64;  // floats per wave image of the merge
     extern __shared__ float lds[];
@@ -348,7 +496,9 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
         int j = 16 * qt + m;
-        const bf16_t *qp = qg + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD + 8 * q + 32 * w;
+        // k-step w of this lane: d = 32 w + 8 q (bf16 cache), d = 64 (w / 2) + 16 q + 8 (w % 2) (FP8 cache, see KVRaw8)
+        const int d0 = KV8 ? 64 * (w >> 1) + 16 * q + 8 * (w & 1) : 8 * q + 32 * w;
+        const bf16_t *qp = qg + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD + d0;
         qlds[(qt * kKS + w) * 64 + lane] = j < G ? *(const bf16x8 *)qp : zero8();
     }
     // The chunk's block ids go to LDS too: a lookup in the loop is then an LDS read, not a global
@@ -379,7 +529,21 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
         // the launch is sized for the largest stacked group of the call; a sequence with fewer
         // streams multiplies only the query tiles it has
         const int n_act = (G + 15) >> 4;
-        if (NA >= 3 && n_act >= 3)
+        if constexpr (KV8) {
+            const uint8_t *pool8 = (const uint8_t *)pool_v;
+            if (NA >= 3 && n_act >= 3)
+                wave_walk8<NA, NA>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+            else if (NA >= 2 && n_act == 2)
+                wave_walk8<NA, (NA >= 2 ? 2 : 1)>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+            else
+                wave_walk8<NA, 1>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+#pragma unroll
+            for (int qt = 0; qt < NA; ++qt)
+#pragma unroll
+                for (int dt = 0; dt < kDT; ++dt) {
+                    st.o[dt][qt][0] *= v_scale; st.o[dt][qt][1] *= v_scale; st.o[dt][qt][2] *= v_scale; st.o[dt][qt][3] *= v_scale;
+                }
+        } else if (NA >= 3 && n_act >= 3)
             wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
         else if (NA >= 2 && n_act == 2)
             wave_walk<NA, (NA >= 2 ? 2 : 1)>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
@@ -629,34 +793,34 @@ __global__ void __launch_bounds__(128) k_attn_merge(const float *__restrict__ pa
     out[((size_t)row * Hq + h) * kD + d] = f32_to_bf16(num / den);
 }
 
-template <int NA, int NB>
+template <int NA, int NB, bool KV8 = false>
 hipError_t launch_one(const void *q, const void *pool, const int32_t *bt, int max_blocks, const AttnPlan &pl, void *out,
-                      float *part_o, float *part_ml, int Hq, int Hkv, float scale_log2, hipStream_t st) {
+                      float *part_o, float *part_ml, int Hq, int Hkv, float scale_log2, float v_scale, hipStream_t st) {
     constexpr int kImg = kDT * NA * 4 * 64 + 2 * NA * 64;
     // merge images + Q fragments + the chunk's block ids (chunk <= kAttnMaxChunk tokens)
     size_t shm = (NB ? kRingBytes : (size_t)2 * kImg * sizeof(float)) + (size_t)(NA + NB) * kKS * 64 * 16 +
                  (size_t)(kAttnMaxChunk / kBk) * 4;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_attn_decode<NA, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+        hipError_t e = hipFuncSetAttribute((const void *)k_attn_decode<NA, NB, KV8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_attn_decode<NA, NB>), dim3(pl.n_wgs * Hkv), dim3(256), shm, st, (const bf16_t *)q, (const bf16_t *)pool,
-                       bt, max_blocks, pl, (bf16_t *)out, part_o, part_ml, Hq, Hkv, scale_log2);
+    hipLaunchKernelGGL((k_attn_decode<NA, NB, KV8>), dim3(pl.n_wgs * Hkv), dim3(256), shm, st, (const bf16_t *)q, pool, bt, max_blocks, pl,
+                       (bf16_t *)out, part_o, part_ml, Hq, Hkv, scale_log2, v_scale);
     return hipGetLastError();
 }
 
 }  // namespace
 
 bool attn_decode_mfma_supported(const Dims &dm, int g_max) {
-    return dm.bf16 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= 80;
+    return dm.bf16 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= (dm.kv8 ? 48 : 80);
 }
 
 int attn_prefill_group_queries() { return kPrefillWaves * kPrefillNT * 16; }  // stacked queries one prefill workgroup holds
 
 bool attn_prefill_mfma_supported(const Dims &dm, int g_max) {
-    return dm.bf16 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= attn_prefill_group_queries();
+    return dm.bf16 && !dm.kv8 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= attn_prefill_group_queries();
 }
 
 hipError_t launch_attn_prefill_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
@@ -683,12 +847,21 @@ hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *po
     if (pl.causal || pl.chunk > kAttnMaxChunk || pl.n_wgs <= 0) return hipErrorInvalidValue;
     float scale_log2 = kLog2e / sqrtf((float)dm.D);
     int nqt = (pl.g_max + 15) / 16;
+    if (dm.kv8) {  // FP8 codes: the K scale joins the softmax scale, the V scale the output
+        scale_log2 *= dm.k_scale;
+        switch (nqt) {
+        case 1: return launch_one<1, 0, true>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, dm.v_scale, st);
+        case 2: return launch_one<2, 0, true>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, dm.v_scale, st);
+        case 3: return launch_one<3, 0, true>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, dm.v_scale, st);
+        default: return hipErrorInvalidValue;
+        }
+    }
     switch (nqt) {
-    case 1: return launch_one<1, 0>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
-    case 2: return launch_one<2, 0>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
-    case 3: return launch_one<3, 0>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
-    case 4: return launch_one<2, 2>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
-    case 5: return launch_one<3, 2>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, st);
+    case 1: return launch_one<1, 0>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, 1.f, st);
+    case 2: return launch_one<2, 0>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, 1.f, st);
+    case 3: return launch_one<3, 0>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, 1.f, st);
+    case 4: return launch_one<2, 2>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, 1.f, st);
+    case 5: return launch_one<3, 2>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, 1.f, st);
     default: return hipErrorInvalidValue;
     }
 }

@@ -30,6 +30,28 @@ template <> struct Elem<bf16_t> {
     static __device__ __forceinline__ void st(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 };
 
+// FP8 E4M3 (OCP: largest finite value 448, no infinities) cache element.  gfx950's conversion instructions
+// implement this format: decode is exact, encode rounds to nearest even and turns magnitudes of 480 and
+// more into NaN, so values are clamped to +-448 first.
+struct fp8_t { uint8_t v; };
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float fp8_to_f32(uint32_t code) { return __builtin_amdgcn_cvt_pk_f32_fp8(code, false)[0]; }
+__device__ __forceinline__ uint32_t f32_to_fp8(float x) {
+    if (!(x == x)) return 0x7fu;
+    x = fminf(fmaxf(x, -448.f), 448.f);
+    return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(x, 0.f, 0, false) & 0xffu;
+}
+
+// Cache element access: value = stored element (x scale for FP8 codes).
+template <typename KT> struct KVElem {
+    static __device__ __forceinline__ float ld(const KT *p, float) { return Elem<KT>::ld(p); }
+    static __device__ __forceinline__ void st(KT *p, float v, float) { Elem<KT>::st(p, v); }
+};
+template <> struct KVElem<fp8_t> {
+    static __device__ __forceinline__ float ld(const fp8_t *p, float scale) { return fp8_to_f32(p->v) * scale; }
+    static __device__ __forceinline__ void st(fp8_t *p, float v, float scale) { p->v = (uint8_t)f32_to_fp8(v / scale); }
+};
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -13,6 +13,13 @@ namespace icarus {
         if (bf16) { typedef bf16_t T; __VA_ARGS__; }  \
         else      { typedef float T;  __VA_ARGS__; }  \
     } while (0)
+// T as above; KT: element type of the KV pool (T, or FP8 codes)
+#define DISPATCH_TK(bf16, kv8, ...)                                   \
+    do {                                                              \
+        if (kv8) { typedef fp8_t KT; DISPATCH_T(bf16, __VA_ARGS__); } \
+        else if (bf16) { typedef bf16_t T; typedef bf16_t KT; __VA_ARGS__; } \
+        else { typedef float T; typedef float KT; __VA_ARGS__; }      \
+    } while (0)
 
 // ------------------------------------------------------------------ RMSNorm
 template <typename T>
@@ -165,14 +172,15 @@ hipError_t launch_silu_mul(const Dims &dm, const float *gate, const float *up, v
 // next Hkv are v.  The row arrives as `splits` fp32 slices (split-K partials of the projection
 // GEMM, `slice` floats apart) that are summed here.  Angles are computed in double, once per
 // row: pos * theta^(-2i/D).
-template <typename T>
+template <typename T, typename KT>
 __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ qkv, int ldq, int splits, size_t slice,
                                                      const int32_t *__restrict__ row_seq,
                                                      const int32_t *__restrict__ row_model, const int32_t *__restrict__ row_pos,
-                                                     const int32_t *__restrict__ bt, int max_blocks, T *__restrict__ pool,
+                                                     const int32_t *__restrict__ bt, int max_blocks, KT *__restrict__ pool,
                                                      T *__restrict__ q_out, int64_t *__restrict__ slot_out, int slot_by_row,
                                                      const T *__restrict__ q_norm, const T *__restrict__ k_norm,
-                                                     int Hq, int Hkv, int D, int Bk, double log2_theta, float eps, int qk_norm) {
+                                                     int Hq, int Hkv, int D, int Bk, double log2_theta, float eps, int qk_norm,
+                                                     float k_scale, float v_scale) {
     extern __shared__ float sm[];  // the row [n_heads * D] | cos, sin [D/2 each] | inv_rms per head [Hq + Hkv]
     int row = blockIdx.x;
     int s = row_seq[row], pos = row_pos[row];
@@ -225,7 +233,7 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
         __syncthreads();
     }
     int64_t slot = 0;
-    T *kdst = nullptr, *vdst = nullptr;
+    KT *kdst = nullptr, *vdst = nullptr;
     int off = 0;
     if (enc) {
         int blk = bt[(size_t)s * max_blocks + pos / Bk];
@@ -250,17 +258,17 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
             Elem<T>::st(dst + i, ra);
             Elem<T>::st(dst + i + half, rb);
         } else {
-            T *dst = kdst + ((size_t)(h - Hq) * 2 + 0) * Bk * D + (size_t)off * D;  // K plane [Bk][D]
-            Elem<T>::st(dst + i, ra);
-            Elem<T>::st(dst + i + half, rb);
+            KT *dst = kdst + ((size_t)(h - Hq) * 2 + 0) * Bk * D + (size_t)off * D;  // K plane [Bk][D]
+            KVElem<KT>::st(dst + i, ra, k_scale);
+            KVElem<KT>::st(dst + i + half, rb, k_scale);
         }
     }
     if (enc) {
         const float *vsrc = xr + (size_t)(Hq + Hkv) * D;
         for (int idx = threadIdx.x; idx < Hkv * D; idx += 256) {
             int h = idx / D, i = idx % D;
-            T *dst = vdst + ((size_t)h * 2 + 1) * Bk * D;  // V plane [D][Bk]
-            Elem<T>::st(dst + (size_t)i * Bk + off, vsrc[idx]);
+            KT *dst = vdst + ((size_t)h * 2 + 1) * Bk * D;  // V plane [D][Bk]
+            KVElem<KT>::st(dst + (size_t)i * Bk + off, vsrc[idx], v_scale);
         }
     }
 }
@@ -271,29 +279,31 @@ hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, int spl
     if (R <= 0) return hipSuccess;
     size_t shm = sizeof(float) * ((size_t)(dm.Hq + 2 * dm.Hkv) * dm.D + dm.D + dm.Hq + dm.Hkv);
     double l2t = log2(dm.theta);
-    if (shm > 64 * 1024) {
-        static bool attr_set[2] = {false, false};
-        if (!attr_set[dm.bf16 ? 1 : 0]) {
-            hipError_t e = dm.bf16 ? hipFuncSetAttribute((const void *)k_rope_append<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)
-                                   : hipFuncSetAttribute((const void *)k_rope_append<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return e;
-            attr_set[dm.bf16 ? 1 : 0] = true;
+    if (shm > 160 * 1024) return hipErrorInvalidValue;
+    DISPATCH_TK(dm.bf16, dm.kv8, {
+        if (shm > 64 * 1024) {
+            static bool attr_set = false;  // per instantiation
+            if (!attr_set) {
+                hipError_t e = hipFuncSetAttribute((const void *)k_rope_append<T, KT>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                if (e != hipSuccess) return e;
+                attr_set = true;
+            }
         }
-        if (shm > 160 * 1024) return hipErrorInvalidValue;
-    }
-    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_rope_append<T>, dim3(R), dim3(256), shm, st, qkv, ldq, splits, slice, rm.row_seq,
-                                           rm.row_model, rm.row_pos, bt, max_blocks, (T *)pool, (T *)q_out, slot_out, slot_by_row,
-                                           (const T *)q_norm, (const T *)k_norm, dm.Hq, dm.Hkv, dm.D, dm.Bk, l2t, dm.eps, dm.qk_norm));
+        hipLaunchKernelGGL((k_rope_append<T, KT>), dim3(R), dim3(256), shm, st, qkv, ldq, splits, slice, rm.row_seq, rm.row_model,
+                           rm.row_pos, bt, max_blocks, (KT *)pool, (T *)q_out, slot_out, slot_by_row, (const T *)q_norm,
+                           (const T *)k_norm, dm.Hq, dm.Hkv, dm.D, dm.Bk, l2t, dm.eps, dm.qk_norm, dm.k_scale, dm.v_scale);
+    });
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ attention (one block per row and query head)
 // Online softmax over chunks of 1024 cached positions; thread d < D owns output element d.
-template <typename T>
-__global__ void __launch_bounds__(256) k_attn_generic(const T *__restrict__ q, const T *__restrict__ pool,
+template <typename T, typename KT>
+__global__ void __launch_bounds__(256) k_attn_generic(const T *__restrict__ q, const KT *__restrict__ pool,
                                                       const int32_t *__restrict__ bt, int max_blocks,
                                                       const int32_t *__restrict__ row_seq, const int32_t *__restrict__ row_kvlen,
-                                                      T *__restrict__ out, int Hq, int Hkv, int D, int Bk, float scale) {
+                                                      T *__restrict__ out, int Hq, int Hkv, int D, int Bk, float scale,
+                                                      float k_scale, float v_scale) {
     __shared__ float sc[1024];
     __shared__ float red[16];
     extern __shared__ float qs[];  // [D]
@@ -310,9 +320,9 @@ __global__ void __launch_bounds__(256) k_attn_generic(const T *__restrict__ q, c
         float lmax = -INFINITY;
         for (int t = threadIdx.x; t < cnt; t += 256) {
             int tok = c0 + t;
-            const T *kr = pool + (size_t)btr[tok / Bk] * blk_stride + (size_t)c * head_stride + (size_t)(tok % Bk) * D;
+            const KT *kr = pool + (size_t)btr[tok / Bk] * blk_stride + (size_t)c * head_stride + (size_t)(tok % Bk) * D;
             float dot = 0.f;
-            for (int i = 0; i < D; ++i) dot += qs[i] * Elem<T>::ld(kr + i);
+            for (int i = 0; i < D; ++i) dot += qs[i] * KVElem<KT>::ld(kr + i, k_scale);
             dot *= scale;
             sc[t] = dot;
             lmax = fmaxf(lmax, dot);
@@ -333,8 +343,8 @@ __global__ void __launch_bounds__(256) k_attn_generic(const T *__restrict__ q, c
             int d = threadIdx.x;
             for (int t = 0; t < cnt; ++t) {
                 int tok = c0 + t;
-                const T *vr = pool + (size_t)btr[tok / Bk] * blk_stride + (size_t)c * head_stride + (size_t)Bk * D;
-                a += sc[t] * Elem<T>::ld(vr + (size_t)d * Bk + (tok % Bk));
+                const KT *vr = pool + (size_t)btr[tok / Bk] * blk_stride + (size_t)c * head_stride + (size_t)Bk * D;
+                a += sc[t] * KVElem<KT>::ld(vr + (size_t)d * Bk + (tok % Bk), v_scale);
             }
             acc = a;
         }
@@ -350,8 +360,9 @@ hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, 
     if (R <= 0) return hipSuccess;
     float scale = 1.0f / sqrtf((float)dm.D);
     dim3 grid(dm.Hq, R);
-    DISPATCH_T(dm.bf16, hipLaunchKernelGGL(k_attn_generic<T>, grid, dim3(256), sizeof(float) * dm.D, st, (const T *)q, (const T *)pool, bt,
-                                           max_blocks, rm.row_seq, rm.row_kvlen, (T *)out, dm.Hq, dm.Hkv, dm.D, dm.Bk, scale));
+    DISPATCH_TK(dm.bf16, dm.kv8, hipLaunchKernelGGL((k_attn_generic<T, KT>), grid, dim3(256), sizeof(float) * dm.D, st, (const T *)q,
+                                                    (const KT *)pool, bt, max_blocks, rm.row_seq, rm.row_kvlen, (T *)out, dm.Hq, dm.Hkv,
+                                                    dm.D, dm.Bk, scale, dm.k_scale, dm.v_scale));
     return hipGetLastError();
 }
 

@@ -865,6 +865,9 @@ icarus_status icarus_create(const icarus_layer_config *cfg, const icarus_base_we
     if (!cfg || !base || !out) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "cfg, base and out must not be null");
     const icarus_layer_config &c = *cfg;
     if (c.dtype != ICARUS_F32 && c.dtype != ICARUS_BF16) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "dtype %d is neither ICARUS_F32 nor ICARUS_BF16", c.dtype);
+    if (c.kv_dtype != ICARUS_KV_SAME && c.kv_dtype != ICARUS_KV_FP8_E4M3) return fail(nullptr, ICARUS_ERR_INVALID_ARG, "kv_dtype %d unknown", c.kv_dtype);
+    if (c.kv_dtype == ICARUS_KV_FP8_E4M3 && !(c.k_scale > 0.0 && c.v_scale > 0.0 && std::isfinite(c.k_scale) && std::isfinite(c.v_scale)))
+        return fail(nullptr, ICARUS_ERR_INVALID_ARG, "k_scale and v_scale must be finite and > 0 for an FP8 cache");
     if (c.d_model <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.d_ffn <= 0 || c.block_size <= 0 ||
         c.num_blocks <= 0 || c.max_position <= 0 || c.n_models < 0 || c.lora_rank < 0)
         return fail(nullptr, ICARUS_ERR_SHAPE, "all sizes must be positive (n_models, lora_rank non-negative)");
@@ -902,6 +905,7 @@ icarus_status icarus_create(const icarus_layer_config *cfg, const icarus_base_we
     dm.d = c.d_model; dm.Hq = c.n_q_heads; dm.Hkv = c.n_kv_heads; dm.D = c.head_dim; dm.F = c.d_ffn; dm.Bk = c.block_size;
     dm.M = c.n_models; dm.r = c.lora_rank; dm.bf16 = c.dtype == ICARUS_BF16; dm.qk_norm = c.qk_norm != 0;
     dm.theta = c.rope_theta; dm.eps = (float)c.rms_eps; dm.lora_scale = (float)c.lora_scale;
+    dm.kv8 = c.kv_dtype == ICARUS_KV_FP8_E4M3; dm.k_scale = dm.kv8 ? (float)c.k_scale : 1.f; dm.v_scale = dm.kv8 ? (float)c.v_scale : 1.f;
     if (const char *e = getenv("ICARUS_ATTN_CHUNK")) ctx->attn_chunk_override = atoi(e);
     if (const char *e = getenv("ICARUS_ATTN_WGS")) ctx->attn_wgs = std::max(1, atoi(e));
     if (const char *e = getenv("ICARUS_ATTN_WEIGHT")) ctx->attn_weight_base = std::max(1, atoi(e));

@@ -11,6 +11,8 @@ typedef uint16_t bf16_raw;  // raw bfloat16 bits
 struct Dims {
     int d, Hq, Hkv, D, F, Bk, M, r;
     int bf16;      // storage type: 1 = bfloat16, 0 = float32
+    int kv8;       // 1: the KV pool holds FP8 E4M3 codes, value = code * k_scale (K plane) or v_scale (V plane)
+    float k_scale, v_scale;
     int qk_norm;
     double theta;
     float eps, lora_scale;

@@ -28,6 +28,7 @@ class DecodeWorkload:
     x: list               # rotating device inputs [R, d]
     x_host: list
     headroom: int
+    kv_scales: tuple = None   # (k_scale, v_scale) when the pool holds FP8 codes
 
     def ctx_lens(self, step: int) -> np.ndarray:
         return (self.batch.ctx_lens + step).astype(np.int32)
@@ -35,7 +36,7 @@ class DecodeWorkload:
     def kv_bytes(self, step: int) -> int:
         """Algorithmic KV bytes one attention launch reads: each cached token once per sequence."""
         s = self.shape
-        es = 2 if s.bf16 else 4
+        es = 1 if self.kv_scales else (2 if s.bf16 else 4)
         return int((self.ctx_lens(step).astype(np.int64) + 1).sum()) * s.n_kv_heads * s.head_dim * 2 * es
 
     def qo_bytes(self) -> int:
@@ -56,6 +57,9 @@ SPECS = {
     # reduced stand-ins for quick runs and tests
     "c3-small": (synth.LLAMA_SMALL.replace(n_models=8), 16, (100, 3000), (1, 8), "reduced config 3"),
 }
+SPECS["c3-fp8"] = SPECS["c3"][:4] + (SPECS["c3"][4] + "; KV cache in FP8 E4M3 (static scales)",)
+SPECS["c3-small-fp8"] = SPECS["c3-small"][:4] + ("reduced config 3, FP8 KV cache",)
+FP8_POOL_SCALE = 4.0 / 448.0   # the synthetic cache is N(0,1) clipped at 4 sigma: 4 sigma -> the largest code
 
 
 def upload(a: np.ndarray, bf16: bool, device) -> torch.Tensor:
@@ -83,21 +87,29 @@ def build_decode_workload(name: str, device="cuda:0", headroom: int = 128, seed:
     nact = synth.draw_active_counts(seed, S, alo, ahi) if alo != ahi else np.full(S, alo, dtype=np.int32)
     batch = synth.make_batch(shape, lens, nact, seed=seed, headroom=headroom)
     cfg = layer_config(shape, batch.num_blocks, int(lens.max()) + headroom + 1)
+    fp8 = name.endswith("-fp8")
+    if fp8:
+        cfg.kv_fp8, cfg.k_scale, cfg.v_scale = True, FP8_POOL_SCALE, FP8_POOL_SCALE
     dbase = {k: upload(v, shape.bf16, device) for k, v in base.items()}
     dlora = {p: (upload(A, shape.bf16, device), upload(B, shape.bf16, device)) for p, (A, B) in lora.items()}
     layer = binding.IcarusLayer(cfg, dbase, dlora)
     say(f"[workload {name}] pool: {batch.num_blocks} blocks")
     gen = torch.Generator(device=device)
     gen.manual_seed(1000 + seed)
-    pool = torch.empty(cfg.pool_shape(), dtype=cfg.torch_dtype, device=device)
+    pool = torch.empty(cfg.pool_shape(), dtype=cfg.pool_dtype, device=device)
     step_blocks = max(1, (1 << 28) // (pool[0].numel()))
     for b0 in range(0, batch.num_blocks, step_blocks):        # fill in slabs: bounded temporaries
         sl = pool[b0:b0 + step_blocks]
-        sl.copy_(torch.randn(sl.shape, generator=gen, device=device, dtype=torch.float32))
+        r = torch.randn(sl.shape, generator=gen, device=device, dtype=torch.float32)
+        if fp8:   # the same N(0,1) cache, as codes (the cast rounds to nearest even; values are clipped below 448)
+            sl.copy_((r.clamp_(-4.0, 4.0) / FP8_POOL_SCALE).to(torch.float8_e4m3fn).view(torch.uint8))
+        else:
+            sl.copy_(r)
     bt = torch.from_numpy(batch.block_tables).to(device)
     xs_host = [synth.make_hidden(shape, batch.R, seed=seed, tag=10 + i) for i in range(n_x)]
     xs = [upload(x, shape.bf16, device) for x in xs_host]
-    return DecodeWorkload(name, desc, shape, batch, base, lora, layer, pool, bt, xs, xs_host, headroom)
+    return DecodeWorkload(name, desc, shape, batch, base, lora, layer, pool, bt, xs, xs_host, headroom,
+                          (FP8_POOL_SCALE, FP8_POOL_SCALE) if fp8 else None)
 
 
 def build_private_kv_baseline(wl: DecodeWorkload, device="cuda:0", seed: int = 0, n_x: int = 4) -> DecodeWorkload:

@@ -37,7 +37,7 @@ def layer_config(shape: synth.LayerShape, num_blocks: int, max_position: int = 1
         max_position=max_position, rope_theta=shape.rope_theta, rms_eps=shape.rms_eps, lora_scale=shape.lora_scale)
 
 
-def make_layer(shape, base, lora, num_blocks, device="cuda:0", max_position=1 << 17) -> binding.IcarusLayer:
+def make_layer(shape, base, lora, num_blocks, device="cuda:0", max_position=1 << 17, **cfg_overrides) -> binding.IcarusLayer:
     dbase = {k: dev(v, shape.bf16, device) for k, v in base.items()}
     dlora = None
     if lora is not None:
@@ -45,7 +45,23 @@ def make_layer(shape, base, lora, num_blocks, device="cuda:0", max_position=1 <<
     cfg = layer_config(shape, num_blocks, max_position)
     if lora is None:
         cfg.n_models, cfg.lora_rank, cfg.lora_target_mask = 0, 0, 0
+    for k, v in cfg_overrides.items():
+        setattr(cfg, k, v)
     return binding.IcarusLayer(cfg, dbase, dlora)
+
+
+def fp8_pool_to_float(dpool: torch.Tensor, k_scale: float, v_scale: float) -> np.ndarray:
+    """Device pool of FP8 E4M3 codes [nb, Hkv, 2, Bk*D] (uint8) -> float32 values, library layout."""
+    vals = dpool.cpu().view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    vals[:, :, 0] *= np.float32(k_scale)
+    vals[:, :, 1] *= np.float32(v_scale)
+    return vals
+
+
+def e4m3_step(x: np.ndarray, scale: float) -> np.ndarray:
+    """Spacing of the FP8 E4M3 grid (times scale) at |x|."""
+    a = np.maximum(np.abs(x.astype(np.float64)) / scale, 2.0 ** -6)
+    return 2.0 ** (np.floor(np.log2(a)) - 3) * scale
 
 
 def bf16_ulp(x: np.ndarray) -> np.ndarray:

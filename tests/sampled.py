@@ -13,9 +13,10 @@ import oracle
 from helpers import assert_close, fill_pool
 
 
-def kv_to_host(shape, pool_dev, block_table_row, n_tokens):
+def kv_to_host(shape, pool_dev, block_table_row, n_tokens, kv_scales=None):
     """First n_tokens cached K, V of one sequence from the device pool (library layout
-    [blocks][Hkv][2][Bk*D], V transposed): float32 [n, Hkv, D] each."""
+    [blocks][Hkv][2][Bk*D], V transposed): float32 [n, Hkv, D] each.  kv_scales = (k_scale, v_scale): the pool
+    holds FP8 E4M3 codes (uint8) and the values are code * scale."""
     import torch
     Bk, D, Hkv = shape.block_size, shape.head_dim, shape.n_kv_heads
     nb = (n_tokens + Bk - 1) // Bk
@@ -23,14 +24,21 @@ def kv_to_host(shape, pool_dev, block_table_row, n_tokens):
         z = np.zeros((0, Hkv, D), dtype=np.float32)
         return z, z.copy()
     ids = torch.from_numpy(np.asarray(block_table_row[:nb], dtype=np.int64)).to(pool_dev.device)
-    blk = pool_dev.index_select(0, ids).to(torch.float32).cpu().numpy()      # [nb, Hkv, 2, Bk*D]
+    blk = pool_dev.index_select(0, ids)                                      # [nb, Hkv, 2, Bk*D]
+    if kv_scales is not None:
+        blk = blk.cpu().view(torch.float8_e4m3fn).to(torch.float32).numpy()
+        blk[:, :, 0] *= np.float32(kv_scales[0])
+        blk[:, :, 1] *= np.float32(kv_scales[1])
+    else:
+        blk = blk.to(torch.float32).cpu().numpy()
     K = blk[:, :, 0].reshape(nb, Hkv, Bk, D).transpose(0, 2, 1, 3).reshape(nb * Bk, Hkv, D)
     V = blk[:, :, 1].reshape(nb, Hkv, D, Bk).transpose(0, 3, 1, 2).reshape(nb * Bk, Hkv, D)
     return np.ascontiguousarray(K[:n_tokens]), np.ascontiguousarray(V[:n_tokens])
 
 
-def oracle_config(shape, num_blocks, with_lora=True):
+def oracle_config(shape, num_blocks, with_lora=True, kv_scales=None):
     return oracle.LayerConfig(
+        kv_fp8=kv_scales is not None, k_scale=kv_scales[0] if kv_scales else 1.0, v_scale=kv_scales[1] if kv_scales else 1.0,
         d_model=shape.d_model, n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
         d_ffn=shape.d_ffn, block_size=shape.block_size, num_blocks=num_blocks,
         n_models=shape.n_models if with_lora else 0, lora_rank=shape.lora_rank if with_lora else 0,
@@ -38,20 +46,20 @@ def oracle_config(shape, num_blocks, with_lora=True):
         rope_theta=shape.rope_theta, rms_eps=shape.rms_eps, lora_scale=shape.lora_scale)
 
 
-def snapshot_prefixes(shape, pool_dev, block_tables, ctx_lens, sample):
+def snapshot_prefixes(shape, pool_dev, block_tables, ctx_lens, sample, kv_scales=None):
     """K, V of the sampled sequences as cached BEFORE the call under test."""
-    return {int(s): kv_to_host(shape, pool_dev, block_tables[s], int(ctx_lens[s])) for s in sample}
+    return {int(s): kv_to_host(shape, pool_dev, block_tables[s], int(ctx_lens[s]), kv_scales) for s in sample}
 
 
 def decode_sample_check(shape, base, lora, prefixes, ctx_lens, row_seq, row_model, x_host, x_dev_out, tol, what,
-                        slots_dev=None, block_tables=None):
+                        slots_dev=None, block_tables=None, kv_scales=None):
     """Oracle decode step of the sequences in `prefixes` (their K/V before the call), compared with
     the device output rows of those sequences.  Returns timing and sizes of the sample."""
     import torch
     sample = sorted(prefixes)
     Bk = shape.block_size
     need = [(int(ctx_lens[s]) + 1 + Bk - 1) // Bk for s in sample]
-    orc = oracle.Oracle(oracle_config(shape, sum(need), lora is not None), base, lora)
+    orc = oracle.Oracle(oracle_config(shape, sum(need), lora is not None, kv_scales), base, lora)
     pool = orc.new_pool()
     bt = np.zeros((len(sample), max(need)), dtype=np.int32)
     k = 0
