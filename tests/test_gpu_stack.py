@@ -11,18 +11,23 @@ import torch
 pytestmark = pytest.mark.gpu
 
 
-def _build(shape, n_layers, vocab, num_blocks, seed, lora_std=0.05):
+def _build(shape, n_layers, vocab, num_blocks, seed, lora_std=0.05, kv_scales=None):
+    import dataclasses
     import oracle
     from gpu_util import dev, make_layer
     from helpers import oracle_config
     from paper_2603_13281_amd import binding, synth
     wts = synth.make_stack(shape, n_layers, vocab, seed=seed, lora_std=lora_std)
     cfg = oracle_config(shape, num_blocks)
+    kw = {}
+    if kv_scales is not None:      # FP8 cache in every layer, one pair of static scales
+        cfg = dataclasses.replace(cfg, kv_fp8=True, k_scale=kv_scales[0], v_scale=kv_scales[1])
+        kw = dict(kv_fp8=True, k_scale=kv_scales[0], v_scale=kv_scales[1])
     orc = oracle.OracleStack([oracle.Oracle(cfg, b, l) for b, l in zip(wts["bases"], wts["loras"])],
                              wts["embed"], wts["final_norm"], wts["lm_head"])
-    layers = [make_layer(shape, b, l, num_blocks) for b, l in zip(wts["bases"], wts["loras"])]
+    layers = [make_layer(shape, b, l, num_blocks, **kw) for b, l in zip(wts["bases"], wts["loras"])]
     stack = binding.IcarusStack(layers, dev(wts["embed"], shape.bf16), dev(wts["final_norm"], shape.bf16), dev(wts["lm_head"], shape.bf16))
-    pools = [torch.zeros(layers[0].cfg.pool_shape(), dtype=layers[0].cfg.torch_dtype, device="cuda:0") for _ in layers]
+    pools = [torch.zeros(layers[0].cfg.pool_shape(), dtype=layers[0].cfg.pool_dtype, device="cuda:0") for _ in layers]
     return wts, orc, stack, pools
 
 
@@ -38,21 +43,23 @@ def _check_tokens(got_tok, got_logits, want_logits, tol, what):
             assert got_tok[r] == order[0], f"{what}: row {r} token {got_tok[r]} != {order[0]}"
 
 
-@pytest.mark.parametrize("kind", ["tiny-fp32", "llama-small-bf16", "qwen-small-bf16"])
+@pytest.mark.parametrize("kind", ["tiny-fp32", "llama-small-bf16", "qwen-small-bf16", "llama-small-fp8kv"])
 def test_stack_prefill_then_greedy_decode(kind):
     from paper_2603_13281_amd import synth
     shape, n_layers, vocab, tol = {
         "tiny-fp32": (synth.TINY, 3, 264, 1e-4),
         "llama-small-bf16": (synth.LLAMA_SMALL, 3, 1024, 2e-2),
         "qwen-small-bf16": (synth.QWEN_SMALL, 2, 512, 2e-2),
+        "llama-small-fp8kv": (synth.LLAMA_SMALL, 3, 1024, 2e-2),
     }[kind]
+    kv_scales = (0.02, 0.02) if kind.endswith("fp8kv") else None
     S, steps = 3, 4
     rng = np.random.default_rng(4)
     prompt_lens = np.array([37, 5, 64], dtype=np.int32)
     Bk = shape.block_size
     max_blocks = int((prompt_lens.max() + steps + Bk) // Bk) + 1
     num_blocks = S * max_blocks + 2
-    wts, orc, stack, pools = _build(shape, n_layers, vocab, num_blocks, seed=11)
+    wts, orc, stack, pools = _build(shape, n_layers, vocab, num_blocks, seed=11, kv_scales=kv_scales)
     opools = orc.new_pools()
     bt = rng.permutation(num_blocks)[:S * max_blocks].reshape(S, max_blocks).astype(np.int32)
     dbt = torch.from_numpy(bt).to("cuda:0")
