@@ -121,14 +121,14 @@ def main_prefill(args):
     base = None
     if not args.no_cpu_baseline:
         s0, T, L = 0, int(wl.chunk_lens[0]), int(pre[0])
-        prefix = sampled.kv_to_host(sh, wl.pool, wl.batch.block_tables[s0], L)   # prefix as cached before the call
+        prefix = sampled.kv_to_host(sh, wl.pool, wl.batch.block_tables[s0], L, wl.kv_scales)   # prefix as cached before the call
     run()
     torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         pick = sorted(set([0, T - 1] + [int(v) for v in np.random.default_rng(7).choice(T, size=min(8, T), replace=False)]))
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         dt = sampled.prefill_sample_check(sh, wl.base, prefix, L, T, wl.x_host[:T], x_out[:T], pick, 2e-2,
-                                          "bench prefill sample vs oracle")["seconds"]
+                                          "bench prefill sample vs oracle", kv_scales=wl.kv_scales)["seconds"]
         base = {"value": len(pick) / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
                 "sample": f"sequence 0: K/V of all {T} chunk tokens and the full layer for tokens {pick} over its {L}-token "
                           f"prefix, {dt:.2f} s; GPU rows match the oracle within 2e-2", "seconds": dt}
@@ -301,7 +301,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c3-fp8", "c3-small-fp8", "c4", "c4-small", "stack", "stack-small", "prefix-cache"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c3-fp8", "c3-small-fp8", "c5-fp8", "c4", "c4-small", "c4-fp8", "c4-small-fp8", "stack", "stack-small", "prefix-cache"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-private-kv-baseline", action="store_true",
                     help="skip the conventional per-model-KV run of the same traffic (same kernels, M private caches)")
@@ -348,7 +348,7 @@ def main():
     torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         import sampled
-        nseq = {"c2": 1, "c3": 32, "c3-fp8": 32, "c5": 4, "c3-small": 8, "c3-small-fp8": 8}[args.workload]
+        nseq = {"c2": 1, "c3": 32, "c3-fp8": 32, "c5": 4, "c5-fp8": 4, "c3-small": 8, "c3-small-fp8": 8}[args.workload]
         sample = [int(s) for s in np.random.default_rng(12345).permutation(wl.batch.S)[:nseq]]
         # positions 0..L_s-1 of the cache are what the step read; the step itself appended position L_s
         prefixes = sampled.snapshot_prefixes(wl.shape, wl.pool, wl.batch.block_tables, wl.ctx_lens(0), sample, wl.kv_scales)

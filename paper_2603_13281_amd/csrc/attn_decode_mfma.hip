@@ -191,57 +191,6 @@ __device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restric
     }
 }
 
-// The walk used when the query tiles are split over wave pairs (more than 3 tiles).  Every group
-// must reach two waves (one per tile set) but should come from HBM once and stay a distinct load
-// in flight, so loading and computing are decoupled: in each round of four groups wave w loads
-// group 4r + w into registers, publishes it to an LDS ring as MFMA fragments in lane order, and
-// after one barrier computes the two groups of its parity (half) for its own tiles from the ring.
-// The loads of the next round are in flight while a round is computed.  ring: [2][4][16][64] x 16 B.
-template <int NT, int N>
-__device__ __forceinline__ void shared_walk(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
-                                            int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int half, int c,
-                                            int Hkv, bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds,
-                                            float scale_log2, int lane) {
-    const int n_grp = (n_tok + kGrp - 1) / kGrp;                       // groups, the masked ones included
-    const int n_round = (n_grp + 3) / 4;                               // the same for every wave
-    auto blk_of = [&](int grp, int which) {
-        return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
-    };
-    KVFrag f;
-    if (w < n_grp) load_group(f, pool, blk_of(w, 0), blk_of(w, 1), c, Hkv, lane);
-#pragma nounroll
-    for (int r = 0; r < n_round; ++r) {
-        bf16x8 *stage = ring + (size_t)(r & 1) * 4 * 16 * 64;
-        const int mine = 4 * r + w;
-        if (mine < n_grp) {
-            bf16x8 *dst = stage + (size_t)w * 16 * 64 + lane;
-#pragma unroll
-            for (int i = 0; i < 2 * kKS; ++i) dst[i * 64] = f.k[i / kKS][i % kKS];
-#pragma unroll
-            for (int dt = 0; dt < kDT; ++dt) dst[(2 * kKS + dt) * 64] = f.v[dt];
-        }
-        if (mine + 4 < n_grp) load_group(f, pool, blk_of(mine + 4, 0), blk_of(mine + 4, 1), c, Hkv, lane);
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int gi = half + 2 * u, grp = 4 * r + gi;
-            if (grp < n_grp) {
-                const bf16x8 *src = stage + (size_t)gi * 16 * 64 + lane;
-                KVFrag gfr;
-#pragma unroll
-                for (int i = 0; i < 2 * kKS; ++i) gfr.k[i / kKS][i % kKS] = src[i * 64];
-#pragma unroll
-                for (int dt = 0; dt < kDT; ++dt) gfr.v[dt] = src[(2 * kKS + dt) * 64];
-                if (grp >= n_clean)
-                    compute_group<NT, N, true>(st, gfr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
-                else
-                    compute_group<NT, N, false>(st, gfr, qlds, kGrp, stag, scale_log2, lane);
-            }
-        }
-    }
-    __syncthreads();  // the ring may be reused now
-}
-
 // ---- FP8 (E4M3) cache: 1-byte codes, value = code * scale (one scale for K, one for V) ----------------
 // The codes are exact in bf16, so they go through the same bf16 MFMAs after a register conversion; the
 // scales are folded into the softmax scale (K) and the final normalisation (V).  Loads stay 16 bytes
@@ -386,6 +335,76 @@ __device__ __forceinline__ void wave_walk8(State<NT> &st, const uint8_t *__restr
     }
 }
 
+// The walk used when the query tiles are split over wave pairs (more than 3 tiles).  Every group
+// must reach two waves (one per tile set) but should come from HBM once and stay a distinct load
+// in flight, so loading and computing are decoupled: in each round of four groups wave w loads
+// group 4r + w into registers, publishes it to an LDS ring as MFMA fragments in lane order, and
+// after one barrier computes the two groups of its parity (half) for its own tiles from the ring.
+// The loads of the next round are in flight while a round is computed.  ring: [2][4][16][64] x 16 B.
+template <int NT, int N, bool KV8 = false>
+__device__ __forceinline__ void shared_walk(State<NT> &st, const void *__restrict__ pool_v, const int *__restrict__ blds,
+                                            int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int half, int c,
+                                            int Hkv, bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds,
+                                            float scale_log2, int lane) {
+    const int n_grp = (n_tok + kGrp - 1) / kGrp;                       // groups, the masked ones included
+    const int n_round = (n_grp + 3) / 4;                               // the same for every wave
+    auto blk_of = [&](int grp, int which) {
+        return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
+    };
+    // bf16 cache: fragments as loaded.  FP8 cache: raw codes in registers, expanded to bf16 fragments when
+    // they are published (k-step order of KVRaw8), so that the ring and its readers are the same.
+    const bf16_t *pool = (const bf16_t *)pool_v;
+    const uint8_t *pool8 = (const uint8_t *)pool_v;
+    KVFrag f;
+    KVRaw8 f8;
+    auto load = [&](int grp) {
+        if constexpr (KV8) load_group8(f8, pool8, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
+        else load_group(f, pool, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
+    };
+    if (w < n_grp) load(w);
+#pragma nounroll
+    for (int r = 0; r < n_round; ++r) {
+        bf16x8 *stage = ring + (size_t)(r & 1) * 4 * 16 * 64;
+        const int mine = 4 * r + w;
+        if (mine < n_grp) {
+            bf16x8 *dst = stage + (size_t)w * 16 * 64 + lane;
+            if constexpr (KV8) {
+#pragma unroll
+                for (int i = 0; i < 2 * kKS; ++i) {
+                    const uint4 rk = f8.k[i / kKS][(i % kKS) >> 1];
+                    dst[i * 64] = (i & 1) ? cvt8(rk.z, rk.w) : cvt8(rk.x, rk.y);
+                }
+#pragma unroll
+                for (int dt = 0; dt < kDT; ++dt) dst[(2 * kKS + dt) * 64] = cvt8(f8.v[dt].x, f8.v[dt].y);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 2 * kKS; ++i) dst[i * 64] = f.k[i / kKS][i % kKS];
+#pragma unroll
+                for (int dt = 0; dt < kDT; ++dt) dst[(2 * kKS + dt) * 64] = f.v[dt];
+            }
+        }
+        if (mine + 4 < n_grp) load(mine + 4);
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int gi = half + 2 * u, grp = 4 * r + gi;
+            if (grp < n_grp) {
+                const bf16x8 *src = stage + (size_t)gi * 16 * 64 + lane;
+                KVFrag gfr;
+#pragma unroll
+                for (int i = 0; i < 2 * kKS; ++i) gfr.k[i / kKS][i % kKS] = src[i * 64];
+#pragma unroll
+                for (int dt = 0; dt < kDT; ++dt) gfr.v[dt] = src[(2 * kKS + dt) * 64];
+                if (grp >= n_clean)
+                    compute_group<NT, N, true>(st, gfr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
+                else
+                    compute_group<NT, N, false>(st, gfr, qlds, kGrp, stag, scale_log2, lane);
+            }
+        }
+    }
+    __syncthreads();  // the ring may be reused now
+}
+
 // LDS image of a state: o as [dt][qt][i][lane], then m[qt][lane], l[qt][lane].
 template <int NT>
 __device__ __forceinline__ void merge_from_lds(State<NT> &st, const float *__restrict__ lds, int lane) {
@@ -467,7 +486,6 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
                                                      bf16_t *__restrict__ out, float *__restrict__ part_o,
                                                      float *__restrict__ part_ml, int Hq, int Hkv, float scale_log2,
                                                      float v_scale) {
-    static_assert(!KV8 || NB == 0, "the FP8 cache path covers up to three query tiles");
     const bf16_t *pool = (const bf16_t *)pool_v;
     constexpr int NQT = NA + NB;
     constexpr int kImg = kDT * NA * 4 * 64 + 2 * NA * 64;  // floats per wave image of the merge
@@ -564,10 +582,18 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
         const int role = w >> 1, half = w & 1;  // role: which query tiles; half: which groups
         bf16x8 *ring = (bf16x8 *)lds;
         if (role == 0)
-            shared_walk<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
+            shared_walk<NA, NA, KV8>(st, pool_v, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
         else
-            shared_walk<NA, NB>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
-                                scale_log2, lane);
+            shared_walk<NA, NB, KV8>(st, pool_v, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
+                                     scale_log2, lane);
+        if constexpr (KV8) {
+#pragma unroll
+            for (int qt = 0; qt < NA; ++qt)
+#pragma unroll
+                for (int dt = 0; dt < kDT; ++dt) {
+                    st.o[dt][qt][0] *= v_scale; st.o[dt][qt][1] *= v_scale; st.o[dt][qt][2] *= v_scale; st.o[dt][qt][3] *= v_scale;
+                }
+        }
         // each pair merges its two halves through its own LDS image
         if (half == 1) store_to_lds<NA>(st, lds + role * kImg, lane);
         __syncthreads();
@@ -679,12 +705,36 @@ __device__ __forceinline__ void load_half(bf16x8 (&h)[8], int part, const bf16_t
 }
 static_assert(2 * kKS == 8 && kDT == 8, "a half group is 8 fragments");
 
+// The same half group from an FP8 cache: raw codes, r[i] = the 8 codes that become fragment i
+// (K: i = 4 t + k-step, in the k-step order of KVRaw8; V^T: i = d tile).
+__device__ __forceinline__ void load_half8(uint2 (&r)[8], int part, const uint8_t *__restrict__ pool, int blk0, int blk1, int c,
+                                           int Hkv, int lane) {
+    const int m = lane & 15, q = lane >> 4;
+    const size_t head_stride = (size_t)2 * kBk * kD;
+    if (part == 0) {
+        const uint8_t *kb = pool + ((size_t)((m >> 3) ? blk1 : blk0) * Hkv + c) * head_stride;
+        const int tok0 = 8 * ((m >> 2) & 1) + (m & 3);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int sl = 0; sl < 2; ++sl) {
+                const uint4 v = *(const uint4 *)(kb + (size_t)(tok0 + 4 * t) * kD + 64 * sl + 16 * q);
+                r[4 * t + 2 * sl] = uint2{v.x, v.y};
+                r[4 * t + 2 * sl + 1] = uint2{v.z, v.w};
+            }
+    } else {
+        const uint8_t *vb = pool + ((size_t)((q >> 1) ? blk1 : blk0) * Hkv + c) * head_stride + (size_t)kBk * kD;
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt) r[dt] = *(const uint2 *)(vb + (size_t)(16 * dt + m) * kBk + 8 * (q & 1));
+    }
+}
+
 // Prefill walk: the eight waves hold different query tiles and every wave needs every group, so a
 // group is loaded once -- in round r wave w loads half (w & 1: K or V^T) of group 4r + w/2 into
 // registers, one round ahead -- published to a one-round LDS ring as MFMA fragments in lane order,
 // and read from there by all eight.  ring: [4][16][64] x 16 B.
-template <int NT>
-__device__ __forceinline__ void prefill_walk(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
+template <int NT, bool KV8 = false>
+__device__ __forceinline__ void prefill_walk(State<NT> &st, const void *__restrict__ pool_v, const int *__restrict__ blds,
                                              int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int c, int Hkv,
                                              bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds, float scale_log2,
                                              int lane) {
@@ -695,7 +745,12 @@ __device__ __forceinline__ void prefill_walk(State<NT> &st, const bf16_t *__rest
         return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
     };
     bf16x8 h[8];
-    if (gl < n_grp) load_half(h, part, pool, blk_of(gl, 0), blk_of(gl, 1), c, Hkv, lane);
+    uint2 h8[8];
+    auto load = [&](int grp) {
+        if constexpr (KV8) load_half8(h8, part, (const uint8_t *)pool_v, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
+        else load_half(h, part, (const bf16_t *)pool_v, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
+    };
+    if (gl < n_grp) load(gl);
 #pragma nounroll
     for (int r = 0; r < n_round; ++r) {
         const int mine = 4 * r + gl;
@@ -703,9 +758,12 @@ __device__ __forceinline__ void prefill_walk(State<NT> &st, const bf16_t *__rest
         if (mine < n_grp) {
             bf16x8 *dst = ring + ((size_t)gl * 16 + part * 8) * 64 + lane;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) dst[i * 64] = h[i];
+            for (int i = 0; i < 8; ++i) {
+                if constexpr (KV8) dst[i * 64] = cvt8(h8[i].x, h8[i].y);  // codes are exact in bf16
+                else dst[i * 64] = h[i];
+            }
         }
-        if (mine + 4 < n_grp) load_half(h, part, pool, blk_of(mine + 4, 0), blk_of(mine + 4, 1), c, Hkv, lane);
+        if (mine + 4 < n_grp) load(mine + 4);
         __syncthreads();
 #pragma nounroll
         for (int gi = 0; gi < 4; ++gi) {
@@ -725,10 +783,11 @@ constexpr int kPrefillWaves = 8, kPrefillNT = 2;  // 8 waves x 2 tiles x 16 = 25
 // Causal attention of a prefill chunk.  A workgroup owns one kv-head of one group of T consecutive
 // chunk tokens (T * g <= 256 stacked queries; token t attends to kv_len - (T-1-t) positions) and
 // walks the sequence's cache once for all of them; wave w holds query tiles [w NT, (w+1) NT).
-template <int NT>
-__global__ void __launch_bounds__(64 * kPrefillWaves) k_attn_prefill(const bf16_t *__restrict__ qg, const bf16_t *__restrict__ pool,
+template <int NT, bool KV8 = false>
+__global__ void __launch_bounds__(64 * kPrefillWaves) k_attn_prefill(const bf16_t *__restrict__ qg, const void *__restrict__ pool,
                                                                      const int32_t *__restrict__ bt, int max_blocks, AttnPlan pl,
-                                                                     bf16_t *__restrict__ out, int Hq, int Hkv, float scale_log2) {
+                                                                     bf16_t *__restrict__ out, int Hq, int Hkv, float scale_log2,
+                                                                     float v_scale) {
     extern __shared__ float lds[];
     const int item = blockIdx.x / Hkv, c = blockIdx.x % Hkv;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -745,9 +804,12 @@ __global__ void __launch_bounds__(64 * kPrefillWaves) k_attn_prefill(const bf16_
 #pragma unroll
     for (int qt = 0; qt < NT; ++qt) {
         int j = 16 * (w * NT + qt) + m;
-        const bf16_t *qp = qg + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD + 8 * q;
+        const bf16_t *qp = qg + ((size_t)(row0 + j / g) * Hq + c * g + j % g) * kD;
 #pragma unroll
-        for (int ks = 0; ks < kKS; ++ks) qlds[(qt * kKS + ks) * 64 + lane] = j < G ? *(const bf16x8 *)(qp + 32 * ks) : zero8();
+        for (int ks = 0; ks < kKS; ++ks) {  // FP8 cache: the k-step order of KVRaw8
+            const int d0 = KV8 ? 64 * (ks >> 1) + 16 * q + 8 * (ks & 1) : 32 * ks + 8 * q;
+            qlds[(qt * kKS + ks) * 64 + lane] = j < G ? *(const bf16x8 *)(qp + d0) : zero8();
+        }
     }
     int *blds = (int *)(qall + kPrefillWaves * NT * kKS * 64);
     const int n_blk = (n_tok + kBk - 1) / kBk;
@@ -765,7 +827,15 @@ __global__ void __launch_bounds__(64 * kPrefillWaves) k_attn_prefill(const bf16_
         stag[qt] = T - 1 - min((16 * (w * NT + qt) + m) / g, T - 1);
     }
     const int n_clean = max(0, n_tok - (T - 1)) / kGrp;  // groups valid for every query
-    prefill_walk<NT>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, c, Hkv, ring, qlds, scale_log2, lane);
+    prefill_walk<NT, KV8>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, c, Hkv, ring, qlds, scale_log2, lane);
+    if constexpr (KV8) {
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt)
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) {
+                st.o[dt][qt][0] *= v_scale; st.o[dt][qt][1] *= v_scale; st.o[dt][qt][2] *= v_scale; st.o[dt][qt][3] *= v_scale;
+            }
+    }
     finish<NT>(st, w * NT, NT, G, g, row0, c, Hq, Hkv, 1, 0, 0, out, nullptr, nullptr, lane);
 }
 
@@ -814,13 +884,13 @@ hipError_t launch_one(const void *q, const void *pool, const int32_t *bt, int ma
 }  // namespace
 
 bool attn_decode_mfma_supported(const Dims &dm, int g_max) {
-    return dm.bf16 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= (dm.kv8 ? 48 : 80);
+    return dm.bf16 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= 80;
 }
 
 int attn_prefill_group_queries() { return kPrefillWaves * kPrefillNT * 16; }  // stacked queries one prefill workgroup holds
 
 bool attn_prefill_mfma_supported(const Dims &dm, int g_max) {
-    return dm.bf16 && !dm.kv8 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= attn_prefill_group_queries();
+    return dm.bf16 && dm.D == kD && dm.Bk == kBk && g_max >= 1 && g_max <= attn_prefill_group_queries();
 }
 
 hipError_t launch_attn_prefill_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
@@ -828,17 +898,20 @@ hipError_t launch_attn_prefill_mfma(const Dims &dm, const void *q, const void *p
     if (pl.n_items <= 0) return hipSuccess;
     if (!pl.causal || pl.chunk > kAttnMaxChunk) return hipErrorInvalidValue;
     constexpr int NT = kPrefillNT;
-    float scale_log2 = kLog2e / sqrtf((float)dm.D);
+    float scale_log2 = kLog2e / sqrtf((float)dm.D) * (dm.kv8 ? dm.k_scale : 1.f);
     size_t shm = (size_t)4 * 16 * 64 * 16 + (size_t)kPrefillWaves * NT * kKS * 64 * 16 + (size_t)(kAttnMaxChunk / kBk) * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)k_attn_prefill<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL((k_attn_prefill<NT>), dim3(pl.n_items * dm.Hkv), dim3(64 * kPrefillWaves), shm, st, (const bf16_t *)q, (const bf16_t *)pool, bt,
-                       max_blocks, pl, (bf16_t *)out, dm.Hq, dm.Hkv, scale_log2);
-    return hipGetLastError();
+    auto launch = [&](auto kernel, bool &attr_set) -> hipError_t {
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(kernel, dim3(pl.n_items * dm.Hkv), dim3(64 * kPrefillWaves), shm, st, (const bf16_t *)q, pool, bt, max_blocks, pl,
+                           (bf16_t *)out, dm.Hq, dm.Hkv, scale_log2, dm.kv8 ? dm.v_scale : 1.f);
+        return hipGetLastError();
+    };
+    static bool set_bf16 = false, set_fp8 = false;
+    return dm.kv8 ? launch(k_attn_prefill<NT, true>, set_fp8) : launch(k_attn_prefill<NT, false>, set_bf16);
 }
 
 hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
@@ -853,6 +926,8 @@ hipError_t launch_attn_decode_mfma(const Dims &dm, const void *q, const void *po
         case 1: return launch_one<1, 0, true>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, dm.v_scale, st);
         case 2: return launch_one<2, 0, true>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, dm.v_scale, st);
         case 3: return launch_one<3, 0, true>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, dm.v_scale, st);
+        case 4: return launch_one<2, 2, true>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, dm.v_scale, st);
+        case 5: return launch_one<3, 2, true>(q, pool, bt, max_blocks, pl, out, part_o, part_ml, dm.Hq, dm.Hkv, scale_log2, dm.v_scale, st);
         default: return hipErrorInvalidValue;
         }
     }

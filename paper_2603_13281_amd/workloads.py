@@ -59,6 +59,7 @@ SPECS = {
 }
 SPECS["c3-fp8"] = SPECS["c3"][:4] + (SPECS["c3"][4] + "; KV cache in FP8 E4M3 (static scales)",)
 SPECS["c3-small-fp8"] = SPECS["c3-small"][:4] + ("reduced config 3, FP8 KV cache",)
+SPECS["c5-fp8"] = SPECS["c5"][:4] + (SPECS["c5"][4] + "; KV cache in FP8 E4M3 (static scales)",)
 FP8_POOL_SCALE = 4.0 / 448.0   # the synthetic cache is N(0,1) clipped at 4 sigma: 4 sigma -> the largest code
 
 
@@ -164,6 +165,7 @@ class PrefillWorkload:
     block_tables: torch.Tensor
     x: torch.Tensor             # [sum chunk, d]
     x_host: np.ndarray
+    kv_scales: tuple = None     # (k_scale, v_scale) when the pool holds FP8 codes
 
     @property
     def n_tokens(self) -> int:
@@ -176,6 +178,8 @@ PREFILL_SPECS = {
            "prefixes, each appends a 512-token chunk through the frozen encoder"),
     "c4-small": (synth.LLAMA_SMALL, 4, 300, 70, "reduced config 4"),
 }
+PREFILL_SPECS["c4-fp8"] = PREFILL_SPECS["c4"][:4] + (PREFILL_SPECS["c4"][4] + "; KV cache in FP8 E4M3 (static scales)",)
+PREFILL_SPECS["c4-small-fp8"] = PREFILL_SPECS["c4-small"][:4] + ("reduced config 4, FP8 KV cache",)
 
 
 def build_prefill_workload(name: str, device="cuda:0", seed: int = 0, verbose: bool = False) -> PrefillWorkload:
@@ -188,21 +192,29 @@ def build_prefill_workload(name: str, device="cuda:0", seed: int = 0, verbose: b
     batch = synth.make_batch(shape, lens, np.zeros(S, dtype=np.int32), seed=seed, headroom=chunk + 16)
     cfg = layer_config(shape, batch.num_blocks, prefix + chunk + 17)
     cfg.n_models, cfg.lora_rank, cfg.lora_target_mask = 0, 0, 0      # prefill uses the frozen encoder only
+    fp8 = name.endswith("-fp8")
+    if fp8:
+        cfg.kv_fp8, cfg.k_scale, cfg.v_scale = True, FP8_POOL_SCALE, FP8_POOL_SCALE
     dbase = {k: upload(v, shape.bf16, device) for k, v in base.items()}
     layer = binding.IcarusLayer(cfg, dbase, None)
     say(f"[workload {name}] pool: {batch.num_blocks} blocks")
     gen = torch.Generator(device=device)
     gen.manual_seed(2000 + seed)
-    pool = torch.empty(cfg.pool_shape(), dtype=cfg.torch_dtype, device=device)
+    pool = torch.empty(cfg.pool_shape(), dtype=cfg.pool_dtype, device=device)
     step_blocks = max(1, (1 << 28) // (pool[0].numel()))
     for b0 in range(0, batch.num_blocks, step_blocks):
         sl = pool[b0:b0 + step_blocks]
-        sl.copy_(torch.randn(sl.shape, generator=gen, device=device, dtype=torch.float32))
+        r = torch.randn(sl.shape, generator=gen, device=device, dtype=torch.float32)
+        if fp8:
+            sl.copy_((r.clamp_(-4.0, 4.0) / FP8_POOL_SCALE).to(torch.float8_e4m3fn).view(torch.uint8))
+        else:
+            sl.copy_(r)
     bt = torch.from_numpy(batch.block_tables).to(device)
     chunk_lens = np.full(S, chunk, dtype=np.int32)
     x_host = synth.make_hidden(shape, int(chunk_lens.sum()), seed=seed, tag=20)
     x = upload(x_host, shape.bf16, device)
-    return PrefillWorkload(name, desc, shape, batch, chunk_lens, base, layer, pool, bt, x, x_host)
+    return PrefillWorkload(name, desc, shape, batch, chunk_lens, base, layer, pool, bt, x, x_host,
+                           (FP8_POOL_SCALE, FP8_POOL_SCALE) if fp8 else None)
 
 
 @dataclass

@@ -89,13 +89,13 @@ def decode_sample_check(shape, base, lora, prefixes, ctx_lens, row_seq, row_mode
             "sample": sample}
 
 
-def prefill_sample_check(shape, base, prefix_kv, L, T, x_host_chunk, x_dev_out_chunk, picks, tol, what):
+def prefill_sample_check(shape, base, prefix_kv, L, T, x_host_chunk, x_dev_out_chunk, picks, tol, what, kv_scales=None):
     """Oracle prefill of one sequence's chunk over its cached prefix: K/V of all T tokens, the full
     layer for the tokens in `picks`; compares those rows with the device output."""
     import torch
     Bk = shape.block_size
     nb = (L + T + Bk - 1) // Bk
-    orc = oracle.Oracle(oracle_config(shape, nb, False), base, None)
+    orc = oracle.Oracle(oracle_config(shape, nb, False, kv_scales), base, None)
     pool = orc.new_pool()
     bt = np.arange(nb, dtype=np.int32)[None]
     fill_pool(pool, bt[0], *prefix_kv)

@@ -92,12 +92,13 @@ def test_prefill_then_decode_with_fp8_cache(kind):
 
 def test_matrix_core_attention_equals_vector_attention_on_the_same_codes():
     """icarus_attn_shared_kv over one FP8 pool: the MFMA kernel against the library's plain vector kernel, with
-    1, 2 and 3 query tiles (up to 6 rows x 8 heads per kv-head), cut and uncut sequences, ragged tails."""
+    1 to 5 query tiles (up to 10 rows x 8 heads per kv-head), cut and uncut sequences, ragged tails."""
     from gpu_util import dev, host, make_layer
     from paper_2603_13281_amd import synth
     shape = synth.QWEN_SMALL
     base, lora = synth.make_base(shape, seed=2), synth.make_lora(shape, seed=2)
-    for rows_per_seq, lens in (([6, 1, 3, 5, 2], [1500, 31, 32, 33, 257]), ([2, 2], [4000, 15]), ([1], [700])):
+    for rows_per_seq, lens in (([6, 1, 3, 5, 2], [1500, 31, 32, 33, 257]), ([2, 2], [4000, 15]), ([1], [700]),
+                               ([10, 7, 1], [900, 2100, 40]), ([8, 2], [3000, 77])):      # 4 and 5 query tiles: wave pairs, LDS ring
         lens = np.int32(lens)
         batch = synth.make_batch(shape, lens, np.zeros(len(lens), np.int32), seed=2, headroom=1)
         layer = make_layer(shape, base, lora, batch.num_blocks, kv_fp8=True, k_scale=0.02, v_scale=0.013)
