@@ -499,7 +499,6 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
   for (int item = pl.wg_first[share]; item < pl.wg_first[share + 1]; ++item) {
     const int s = pl.item_seq[item];
     const int tok_begin = pl.item_begin[item];
-    const int kvlen = pl.seq_kvlen[s];
     const int tok_end = tok_begin + pl.item_len[item];
     const int row0 = pl.seq_row0[s], T = pl.seq_rows[s];
     const int G = T * g;
