@@ -48,7 +48,7 @@ class _Base(C.Structure):
 
 
 class _Lora(C.Structure):
-    _fields_ = [("A", C.c_void_p * NPROJ), ("B", C.c_void_p * NPROJ)]
+    _fields_ = [("A", C.c_void_p * NPROJ), ("B", C.c_void_p * NPROJ), ("F", C.c_void_p * NPROJ)]
 
 
 _lib = None
@@ -128,7 +128,9 @@ class Oracle:
     lora: dict p -> (A [M,r,in_p], B [M,out_p,r]) for the adapted projections, or None.
     """
 
-    def __init__(self, cfg: LayerConfig, base: dict, lora: dict | None = None):
+    def __init__(self, cfg: LayerConfig, base: dict, lora: dict | None = None, full: dict | None = None):
+        """full: dict p -> F [M, out_p, in_p] for p in q, o, gate, up, down: private full weights of every
+        decoder (instead of adapters).  K and V always come from the encoder row with the base weights."""
         self.cfg = cfg
         self._keep = []
         self._base = _Base()
@@ -153,6 +155,16 @@ class Oracle:
                     self._keep += [A, B]
                     self._lora.A[i] = A.ctypes.data
                     self._lora.B[i] = B.ctypes.data
+        if full:
+            assert not lora, "a decoder has adapters or private weights, not both"
+            self._lora = _Lora()
+            for i, p in enumerate(PROJ):
+                if p in ("k", "v"):
+                    continue
+                Fw = _f32(full[p])
+                assert Fw.shape == (cfg.n_models, cfg.proj_out(p), cfg.proj_in(p)), (p, Fw.shape)
+                self._keep.append(Fw)
+                self._lora.F[i] = Fw.ctypes.data
 
     # -- pool helpers -----------------------------------------------------
     def new_pool(self) -> np.ndarray:

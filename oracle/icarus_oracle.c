@@ -60,6 +60,9 @@ typedef struct {
 typedef struct {
     const float *A[ORC_NPROJ]; /* A_p [n_models, r, in_p]  */
     const float *B[ORC_NPROJ]; /* B_p [n_models, out_p, r] */
+    const float *F[ORC_NPROJ]; /* or: F_p [n_models, out_p, in_p], a private full weight per decoder
+                                  (full fine-tuning, or any adapter merged into the weight: Sec. 3.2
+                                  leaves the decoder's adaptation method open); overrides A, B */
 } orc_lora;
 
 static int proj_in(const orc_config *c, int p) {
@@ -160,6 +163,12 @@ void orc_adaptive_linear(const float *A, const float *B, int out, int in, int r,
 void orc_icarus_linear(const orc_config *c, const orc_base *b, const orc_lora *l,
                        int p, int T, const int32_t *model, const double *X, double *Y) {
     int in = proj_in(c, p), out = proj_out(c, p), r = c->lora_rank;
+    if (l && l->F[p]) {  /* private decoder weights: a decoder row uses its own matrix, an encoder row the base */
+        for (int t = 0; t < T; ++t)
+            orc_linear(model[t] < 0 ? b->w[p] : l->F[p] + (size_t)model[t] * out * in, out, in, X + (size_t)t * in,
+                       Y + (size_t)t * out);
+        return;
+    }
     for (int t = 0; t < T; ++t)
         orc_linear(b->w[p], out, in, X + (size_t)t * in, Y + (size_t)t * out);
     if (!l || !((c->lora_target_mask >> p) & 1) || !l->A[p] || !l->B[p]) return;

@@ -255,3 +255,15 @@ def make_agent_schedule(n_conversations: int, n_models: int, turns: int, seed: i
         if done[c] < turns:
             active.append(c)
     return out
+
+
+def make_full_decoders(shape: LayerShape, base: dict, seed: int = 0, std: float = 0.01) -> dict:
+    """Private full weights of every decoder (full fine-tuning, or adapters merged into the weights): the base
+    weight plus an independent N(0, std) perturbation per model, in storage precision.  p -> [M, out_p, in_p]
+    for the projections a decoder owns (q, o, gate, up, down; K and V stay the encoder's)."""
+    out = {}
+    for k, p in enumerate(("q", "o", "gate", "up", "down")):
+        rng = np.random.default_rng(np.random.SeedSequence([seed, 2027, k]))
+        w = base[p].astype(np.float32)
+        out[p] = to_storage(w[None] + rng.standard_normal((shape.n_models,) + w.shape).astype(np.float32) * std, shape.bf16)
+    return out
