@@ -40,16 +40,21 @@ def phase_model(wl, step):
     R, Rd, S = b.R, b.n_decoder_rows, b.S
     d, F, qd, kvd, r, M = s.d_model, s.d_ffn, s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim, s.lora_rank, s.n_models
     lora_b = lambda n_out: M * n_out * r * es
+    if getattr(wl, "full", None) is not None:   # private decoder weights: one weight set per active model beside the base's, no adapters
+        wf = 1 + len(set(int(m) for m in b.row_model if m >= 0))
+        lora_b = lambda n_out: 0
+    else:
+        wf = 1
     kv_tokens = int((wl.ctx_lens(step).astype("int64") + 1).sum())
     att_flops = 4 * s.head_dim * s.n_q_heads * sum(int(wl.ctx_lens(step)[q] + 1) for q in b.row_seq)
     return {
         "attn": dict(bytes=wl.kv_bytes(step) + wl.qo_bytes(), flops=att_flops),
-        "gemm_qkv": dict(bytes=(qd + 2 * kvd) * d * es + lora_b(qd) + R * d * es + R * (qd + 2 * kvd) * 4,
+        "gemm_qkv": dict(bytes=(wf * qd + 2 * kvd) * d * es + lora_b(qd) + R * d * es + R * (qd + 2 * kvd) * 4,
                          flops=2 * R * d * (qd + 2 * kvd) + 2 * R * M * r * qd),
-        "gemm_o": dict(bytes=d * qd * es + lora_b(d) + R * qd * es + 2 * R * d * es, flops=2 * R * d * qd + 2 * R * M * r * d),
-        "gemm_gateup": dict(bytes=2 * F * d * es + 2 * lora_b(F) + R * d * es + R * F * es,
+        "gemm_o": dict(bytes=wf * d * qd * es + lora_b(d) + R * qd * es + 2 * R * d * es, flops=2 * R * d * qd + 2 * R * M * r * d),
+        "gemm_gateup": dict(bytes=wf * 2 * F * d * es + 2 * lora_b(F) + R * d * es + R * F * es,
                             flops=4 * R * d * F + 4 * R * M * r * F),
-        "gemm_down": dict(bytes=d * F * es + lora_b(d) + R * F * es + 2 * R * d * es, flops=2 * R * d * F + 2 * R * M * r * d),
+        "gemm_down": dict(bytes=wf * d * F * es + lora_b(d) + R * F * es + 2 * R * d * es, flops=2 * R * d * F + 2 * R * M * r * d),
         "kv_tokens": kv_tokens,
     }
 
@@ -95,7 +100,7 @@ def cpu_baseline(wl, step, x_dev_out, prefixes):
     tol = 2e-2 if sh.bf16 else 1e-4
     info = sampled.decode_sample_check(sh, wl.base, wl.lora, prefixes, ctx, b.row_seq, b.row_model,
                                        wl.x_host[step % len(wl.x_host)], x_dev_out, tol, "bench sample vs oracle",
-                                       kv_scales=wl.kv_scales)
+                                       kv_scales=wl.kv_scales, full=wl.full)
     dt, n_dec = info["seconds"], info["decoder_rows"]
     return {"value": n_dec / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"sequences {info['sample']} of the workload at step {step}: {info['rows']} rows ({n_dec} decoder rows), "
@@ -301,7 +306,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c3-fp8", "c3-small-fp8", "c5-fp8", "c4", "c4-small", "c4-fp8", "c4-small-fp8", "stack", "stack-small", "prefix-cache"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c5", "c3-small", "c3-fp8", "c3-small-fp8", "c5-fp8", "c3-full", "c3-small-full", "c4", "c4-small", "c4-fp8", "c4-small-fp8", "stack", "stack-small", "prefix-cache"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-private-kv-baseline", action="store_true",
                     help="skip the conventional per-model-KV run of the same traffic (same kernels, M private caches)")
@@ -348,7 +353,7 @@ def main():
     torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         import sampled
-        nseq = {"c2": 1, "c3": 32, "c3-fp8": 32, "c5": 4, "c5-fp8": 4, "c3-small": 8, "c3-small-fp8": 8}[args.workload]
+        nseq = {"c2": 1, "c3": 32, "c3-fp8": 32, "c3-full": 16, "c5": 4, "c5-fp8": 4, "c3-small": 8, "c3-small-fp8": 8, "c3-small-full": 8}[args.workload]
         sample = [int(s) for s in np.random.default_rng(12345).permutation(wl.batch.S)[:nseq]]
         # positions 0..L_s-1 of the cache are what the step read; the step itself appended position L_s
         prefixes = sampled.snapshot_prefixes(wl.shape, wl.pool, wl.batch.block_tables, wl.ctx_lens(0), sample, wl.kv_scales)
@@ -402,7 +407,7 @@ def main():
 
     # the conventional alternative on the same GPU and kernels: a private KV cache per (sequence, model)
     private = None
-    if not args.no_private_kv_baseline and wl.kv_scales is None:
+    if not args.no_private_kv_baseline and wl.kv_scales is None and wl.full is None:
         kb = min(K, 20)
         pw = workloads.build_private_kv_baseline(wl, dev)
         py = torch.empty_like(pw.x[0])

@@ -105,6 +105,15 @@ typedef struct icarus_lora_weights { /* all DEVICE, dtype elements; NULL where n
     const void *B[ICARUS_NPROJ];       /* [n_models, out_p, r] */
 } icarus_lora_weights;
 
+/* Decoders with private weights instead of adapters (Sec. 3.2: the logical decoder may as well be trained by
+ * full fine-tuning or by an adapter that is merged into the weights, e.g. DoRA; at inference each such decoder
+ * is a full matrix of its own per projection).  All DEVICE, dtype elements: w[p] = [n_models][out_p][in_p] for
+ * p in {Q, O, GATE, UP, DOWN}; the K and V entries are ignored (K/V come from the encoder row with the base
+ * weights, Alg. 3).  The arrays must outlive the context. */
+typedef struct icarus_full_weights {
+    const void *w[ICARUS_NPROJ];
+} icarus_full_weights;
+
 typedef struct icarus_ctx icarus_ctx;
 
 /* Create a layer context: validates the configuration and keeps the (caller-owned)
@@ -211,6 +220,14 @@ icarus_status icarus_bench_mfma(float *out, int32_t waves, int32_t iters, void *
  * first generated token comes from the base model (Alg. 1, y_prefill).
  * The stack borrows the layer contexts (they must outlive it and must not be used concurrently with it) and
  * the device arrays embed [vocab, d_model], final_norm [d_model], lm_head [vocab, d_model] (storage dtype). */
+/* Switch the context's decoders to private full weights (fw != NULL) or back to its LoRA adapters (NULL).
+ * With private weights icarus_decode_step (and icarus_stack_decode) run every projection once per group of
+ * rows -- the encoder rows with the base weights, the rows of model j with w[p][j] -- i.e. M + 1 grouped
+ * GEMMs over row lists instead of one stacked GEMM: the weights are no longer shared, only the cache is.
+ * Needs the matrix-core path (ICARUS_BF16 shapes it supports), n_models >= 1, 16-byte aligned arrays;
+ * ICARUS_ERR_UNSUPPORTED otherwise.  Prefill is unaffected (encoder only). */
+icarus_status icarus_set_full_decoders(icarus_ctx *ctx, const icarus_full_weights *fw);
+
 typedef struct icarus_stack icarus_stack;
 typedef struct icarus_stack_config {
     int32_t n_layers;            /* >= 1 */

@@ -28,7 +28,7 @@ EXPORTS = ("icarus_create", "icarus_destroy", "icarus_last_error", "icarus_works
            "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read", "icarus_bench_copy", "icarus_bench_mfma", "icarus_stack_create", "icarus_stack_destroy",
            "icarus_stack_last_error", "icarus_stack_workspace_bytes", "icarus_stack_prefill", "icarus_stack_decode",
            "icarus_cache_create", "icarus_cache_destroy", "icarus_cache_last_error", "icarus_cache_acquire", "icarus_cache_extend",
-           "icarus_cache_commit", "icarus_cache_release", "icarus_cache_get_stats")
+           "icarus_cache_commit", "icarus_cache_release", "icarus_cache_get_stats", "icarus_set_full_decoders")
 
 PHASES = ("norm", "lora", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gateup", "gemm_down",
           "elementwise")
@@ -56,6 +56,10 @@ class _Base(C.Structure):
 
 class _Lora(C.Structure):
     _fields_ = [("A", C.c_void_p * NPROJ), ("B", C.c_void_p * NPROJ)]
+
+
+class _Full(C.Structure):
+    _fields_ = [("w", C.c_void_p * NPROJ)]
 
 
 class _StackCfg(C.Structure):
@@ -131,6 +135,8 @@ def _load():
     lib.icarus_cache_commit.argtypes = [vp, vp, i32, i32, vp, i32]
     lib.icarus_cache_release.restype = C.c_int
     lib.icarus_cache_release.argtypes = [vp, vp, i32]
+    lib.icarus_set_full_decoders.restype = C.c_int
+    lib.icarus_set_full_decoders.argtypes = [vp, C.POINTER(_Full)]
     lib.icarus_cache_get_stats.restype = C.c_int
     lib.icarus_cache_get_stats.argtypes = [vp, C.POINTER(_CacheStats)]
     return lib
@@ -281,6 +287,20 @@ class IcarusLayer:
             raise IcarusError(rc, _lib.icarus_last_error(self._h).decode())
 
     # -- C ABI mirrors ---------------------------------------------------------------
+    def set_full_decoders(self, full: dict | None):
+        """full: p -> device tensor [n_models, out_p, in_p] for p in q, o, gate, up, down (private weights of every
+        decoder, instead of the adapters); None switches back to the adapters.  The tensors are kept alive here."""
+        if full is None:
+            self._check(_lib.icarus_set_full_decoders(self._h, None))
+            self._full_keep = None
+            return
+        fw = _Full()
+        for i, p in enumerate(PROJ):
+            if p in full and full[p] is not None:
+                fw.w[i] = full[p].data_ptr()
+        self._check(_lib.icarus_set_full_decoders(self._h, C.byref(fw)))
+        self._full_keep = dict(full)
+
     def set_kernel_mode(self, mode: int):
         self._check(_lib.icarus_set_kernel_mode(self._h, mode))
 

@@ -180,12 +180,14 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
                                                      T *__restrict__ q_out, int64_t *__restrict__ slot_out, int slot_by_row,
                                                      const T *__restrict__ q_norm, const T *__restrict__ k_norm,
                                                      int Hq, int Hkv, int D, int Bk, double log2_theta, float eps, int qk_norm,
-                                                     float k_scale, float v_scale) {
+                                                     float k_scale, float v_scale, const int32_t *__restrict__ row_map) {
     extern __shared__ float sm[];  // the row [n_heads * D] | cos, sin [D/2 each] | inv_rms per head [Hq + Hkv]
-    int row = blockIdx.x;
+    // row_map (optional): the projections were computed on a permutation of the call's rows; input row i is the
+    // call's row row_map[i], whose metadata it takes and at whose place q is written
+    const float *src = qkv + (size_t)blockIdx.x * ldq;
+    int row = row_map ? row_map[blockIdx.x] : (int)blockIdx.x;
     int s = row_seq[row], pos = row_pos[row];
     bool enc = row_model[row] < 0;
-    const float *src = qkv + (size_t)row * ldq;
     int half = D >> 1;
     int n_rot = Hq + (enc ? Hkv : 0), n_heads = Hq + (enc ? 2 * Hkv : 0);
     int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -275,7 +277,7 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
 
 hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, int splits, size_t slice, const RowMeta &rm,
                               const int32_t *bt, int max_blocks, void *pool, void *q_out, int64_t *slot_out, int slot_by_row,
-                              const void *q_norm, const void *k_norm, int R, hipStream_t st) {
+                              const void *q_norm, const void *k_norm, int R, hipStream_t st, const int32_t *row_map) {
     if (R <= 0) return hipSuccess;
     size_t shm = sizeof(float) * ((size_t)(dm.Hq + 2 * dm.Hkv) * dm.D + dm.D + dm.Hq + dm.Hkv);
     double l2t = log2(dm.theta);
@@ -291,7 +293,7 @@ hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, int spl
         }
         hipLaunchKernelGGL((k_rope_append<T, KT>), dim3(R), dim3(256), shm, st, qkv, ldq, splits, slice, rm.row_seq, rm.row_model,
                            rm.row_pos, bt, max_blocks, (KT *)pool, (T *)q_out, slot_out, slot_by_row, (const T *)q_norm,
-                           (const T *)k_norm, dm.Hq, dm.Hkv, dm.D, dm.Bk, l2t, dm.eps, dm.qk_norm, dm.k_scale, dm.v_scale);
+                           (const T *)k_norm, dm.Hq, dm.Hkv, dm.D, dm.Bk, l2t, dm.eps, dm.qk_norm, dm.k_scale, dm.v_scale, row_map);
     });
     return hipGetLastError();
 }

@@ -54,6 +54,8 @@ struct icarus_ctx {
     icarus_base_weights base;
     icarus_lora_weights lora;
     Dims dm;
+    icarus_full_weights full{};   // private decoder weights (full_set), instead of the adapters
+    bool full_set = false;
     int mode = 0;
     int attn_chunk_override = 0;  // longest attention piece in tokens; 0 = automatic (ICARUS_ATTN_CHUNK, for experiments and tests)
     int attn_wgs = 256;           // workgroups of the decode attention: Hkv per equal share of the work (ICARUS_ATTN_WGS)
@@ -109,8 +111,15 @@ bool has_lora(const icarus_ctx *ctx, int p) {
 
 // ---- workspace layout ---------------------------------------------------------------
 struct WsLayout {
-    size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, part_o, part_ml, lora_t, total;
+    size_t meta, xn, qkv, q, attn, z, h, f32a, f32b, t, part_o, part_ml, lora_t, xg, ag, yg, total;
     size_t meta_ints, max_items, gemm_part, gemm_part_bytes;
+};
+
+// Rows regrouped for decoders with private weights: group 0 = encoder rows, group 1 + j = rows of model j.
+struct FullPlan {
+    const int32_t *perm = nullptr;  // device [R]: grouped position -> row of the call
+    const int32_t *inv = nullptr;   // device [R]: row of the call -> grouped position
+    std::vector<int32_t> off;       // host [n_models + 2]: first grouped position of each group
 };
 
 constexpr int kAttnTargetWgs = 1280;  // decode attention: sizing bound for pieces and partial results
@@ -137,7 +146,8 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t max_c
     // metadata: 4 row arrays and the attention plan (5 arrays per piece, the shares' first pieces, 6 arrays
     // per plan sequence); a prefill call has up to `rows` plan sequences of one piece each
     w.meta_ints = 4 * rows + 5 * std::max(rows, w.max_items) + (size_t)ctx->attn_wgs + 6 * std::max(rows, seqs) + 64 +
-                  rows + seqs;  // + what a layer stack stages with the call: prompt tokens, last row of each sequence
+                  rows + seqs +  // + what a layer stack stages with the call: prompt tokens, last row of each sequence
+                  2 * rows;      // + the regrouping of rows for decoders with private weights
     w.meta = take(w.meta_ints * 4);
     {
         size_t g = (size_t)c.n_q_heads / c.n_kv_heads;
@@ -159,6 +169,10 @@ WsLayout ws_layout(const icarus_ctx *ctx, size_t rows, size_t seqs, size_t max_c
     // split-K partials of a narrow GEMM: only calls of a few hundred rows are split
     w.gemm_part_bytes = (size_t)kGemmMaxSplits * std::min<size_t>(rows, 512) * std::max(qd + 2 * kvd, (size_t)c.d_model) * 4;
     w.gemm_part = take(w.gemm_part_bytes);
+    // rows regrouped by model (decoders with private weights): input, attention output, layer output
+    w.xg = take(rows * c.d_model * es);
+    w.ag = take(rows * qd * es);
+    w.yg = take(rows * c.d_model * es);
     w.total = off;
     return w;
 }
@@ -599,11 +613,88 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
     return ICARUS_OK;
 }
 
+// ---- decode step with private decoder weights -----------------------------------------
+// The rows are regrouped (encoder rows, then the rows of model 0, 1, ...) for everything but attention, and every
+// projection runs once per group with that group's weights; q is written back in call order by the RoPE kernel
+// (row map), the attention output is regrouped by a gather, the result returned to call order by another.
+icarus_status run_layer_full(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp, const FullPlan &fp,
+                             int R, int slot_by_row, void *pool, const int32_t *bt, int max_blocks, const void *x_in, void *x_out,
+                             int64_t *slot_out, hipStream_t st) {
+    const icarus_layer_config &c = ctx->cfg;
+    const Dims &dm = ctx->dm;
+    if (!fp.perm || fp.off.size() != (size_t)c.n_models + 2) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "rows were not regrouped for private decoder weights");
+    const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, F = c.d_ffn;
+    const int ldq = qd + 2 * kvd;
+    bf16_raw *xn = (bf16_raw *)(ws + L.xn), *q = (bf16_raw *)(ws + L.q), *attn = (bf16_raw *)(ws + L.attn),
+             *z = (bf16_raw *)(ws + L.z), *h = (bf16_raw *)(ws + L.h);
+    bf16_raw *xg = (bf16_raw *)(ws + L.xg), *ag = (bf16_raw *)(ws + L.ag), *yg = (bf16_raw *)(ws + L.yg);
+    float *qkv = (float *)(ws + L.qkv);
+    auto Wg = [&](int p, int grp) {  // weight of projection p for group grp
+        if (grp == 0) return (const bf16_raw *)ctx->base.w[p];
+        return (const bf16_raw *)ctx->full.w[p] + (size_t)(grp - 1) * proj_out(c, p) * proj_in(c, p);
+    };
+    const int n_groups = c.n_models + 1;
+    PHASE(ctx, st, ICARUS_PH_ELEMWISE, launch_gather_rows(x_in, fp.perm, xg, R, d * 2, st));
+    PHASE(ctx, st, ICARUS_PH_NORM, launch_norm_shrink(dm, xg, ctx->base.norm_attn, xn, R, d, nullptr, nullptr, nullptr, nullptr, nullptr, 0, st));
+    for (int grp = 0; grp < n_groups; ++grp) {  // Q per group; K, V of the encoder rows
+        const int o0 = fp.off[grp], n = fp.off[grp + 1] - o0;
+        if (n <= 0) continue;
+        GemmArgs g{};
+        g.X = xn + (size_t)o0 * d; g.ldx = d; g.R = n; g.K = d;
+        g.mode = GEMM_PLAIN; g.epi = EPI_F32; g.splits = 1;
+        g.W[0] = Wg(ICARUS_PROJ_Q, grp); g.n_seg[0] = qd; g.nseg = 1;
+        if (grp == 0) { g.W[1] = Wg(ICARUS_PROJ_K, 0); g.n_seg[1] = kvd; g.W[2] = Wg(ICARUS_PROJ_V, 0); g.n_seg[2] = kvd; g.nseg = 3; }
+        g.Y = qkv + (size_t)o0 * ldq; g.ldy = ldq;
+        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_QKV, g, st));
+    }
+    PHASE(ctx, st, ICARUS_PH_ROPE_APPEND, launch_rope_append(dm, qkv, ldq, 1, 0, rm, bt, max_blocks, pool, q, slot_out, slot_by_row,
+                                                             ctx->base.q_norm, ctx->base.k_norm, R, st, fp.perm));
+    LORA_TRY(run_decode_attention(ctx, ws, L, rm, hp, q, pool, bt, max_blocks, attn, R, st));
+    PHASE(ctx, st, ICARUS_PH_ELEMWISE, launch_gather_rows(attn, fp.perm, ag, R, qd * 2, st));
+    for (int grp = 0; grp < n_groups; ++grp) {  // O projection + residual
+        const int o0 = fp.off[grp], n = fp.off[grp + 1] - o0;
+        if (n <= 0) continue;
+        GemmArgs g{};
+        g.X = ag + (size_t)o0 * qd; g.ldx = qd; g.R = n; g.K = qd;
+        g.W[0] = Wg(ICARUS_PROJ_O, grp); g.n_seg[0] = d; g.nseg = 1;
+        g.mode = GEMM_PLAIN; g.epi = EPI_BF16_RESID; g.splits = 1;
+        g.Y = z + (size_t)o0 * d; g.ldy = d; g.resid = xg + (size_t)o0 * d; g.ldr = d;
+        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_O, g, st));
+    }
+    PHASE(ctx, st, ICARUS_PH_NORM, launch_norm_shrink(dm, z, ctx->base.norm_ffn, xn, R, d, nullptr, nullptr, nullptr, nullptr, nullptr, 0, st));
+    for (int grp = 0; grp < n_groups; ++grp) {  // gate, up, SwiGLU
+        const int o0 = fp.off[grp], n = fp.off[grp + 1] - o0;
+        if (n <= 0) continue;
+        GemmArgs g{};
+        g.X = xn + (size_t)o0 * d; g.ldx = d; g.R = n; g.K = d;
+        g.W[0] = Wg(ICARUS_PROJ_GATE, grp); g.W[1] = Wg(ICARUS_PROJ_UP, grp); g.n_seg[0] = F; g.nseg = 1;
+        g.mode = GEMM_DUAL; g.splits = 1;
+        g.Y = h + (size_t)o0 * F; g.ldy = F;
+        PHASE(ctx, st, ICARUS_PH_GEMM_GATEUP, launch_gemm_mfma(g, st));
+    }
+    for (int grp = 0; grp < n_groups; ++grp) {  // down projection + residual
+        const int o0 = fp.off[grp], n = fp.off[grp + 1] - o0;
+        if (n <= 0) continue;
+        GemmArgs g{};
+        g.X = h + (size_t)o0 * F; g.ldx = F; g.R = n; g.K = F;
+        g.W[0] = Wg(ICARUS_PROJ_DOWN, grp); g.n_seg[0] = d; g.nseg = 1;
+        g.mode = GEMM_PLAIN; g.epi = EPI_BF16_RESID; g.splits = 1;
+        g.Y = yg + (size_t)o0 * d; g.ldy = d; g.resid = z + (size_t)o0 * d; g.ldr = d;
+        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_DOWN, g, st));
+    }
+    PHASE(ctx, st, ICARUS_PH_ELEMWISE, launch_gather_rows(yg, fp.inv, x_out, R, d * 2, st));
+    return ICARUS_OK;
+}
+
 // ---- the layer, after metadata is on the device ---------------------------------------
 // rows: x_in [R, d].  use_lora: decoder rows get adapter deltas.  kv_only: stop after the append.
 icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp, int R, bool use_lora, bool kv_only,
                         int slot_by_row, void *pool, const int32_t *bt, int max_blocks, const void *x_in, void *x_out,
-                        int64_t *slot_out, hipStream_t st) {
+                        int64_t *slot_out, hipStream_t st, const FullPlan *fp = nullptr) {
+    if (use_lora && !kv_only && ctx->full_set) {  // decoder rows with private weights
+        if (!fp || !layer_mfma_supported(ctx)) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "private decoder weights need the matrix-core path");
+        return run_layer_full(ctx, ws, L, rm, hp, *fp, R, slot_by_row, pool, bt, max_blocks, x_in, x_out, slot_out, st);
+    }
     if (layer_mfma_supported(ctx)) {
         bool lg = use_lora && has_lora(ctx, ICARUS_PROJ_GATE), lu = use_lora && has_lora(ctx, ICARUS_PROJ_UP);
         if (lg == lu)
@@ -654,6 +745,7 @@ struct Prepared {
     WsLayout L;
     RowMeta rm;
     HostPlan hp;
+    FullPlan fp;
     const int32_t *extra_dev = nullptr;
 };
 
@@ -688,6 +780,23 @@ icarus_status prepare_decode(icarus_ctx *ctx, const void *kv_pool, const int32_t
         memcpy(m + used, extra, n_extra * 4);
         pr->extra_dev = dmeta + used;
         used += n_extra;
+    }
+    if (ctx->full_set) {  // counting sort of the rows by group
+        const int n_groups = ctx->cfg.n_models + 1;
+        std::vector<int32_t> &off = pr->fp.off;
+        off.assign((size_t)n_groups + 1, 0);
+        for (int r = 0; r < R; ++r) ++off[(size_t)row_model[r] + 2];
+        for (int g = 1; g <= n_groups; ++g) off[g] += off[g - 1];
+        std::vector<int32_t> next(off.begin(), off.end() - 1);
+        int32_t *perm = m + used, *inv = perm + R;
+        for (int r = 0; r < R; ++r) {
+            int pos = next[(size_t)row_model[r] + 1]++;
+            perm[pos] = r;
+            inv[r] = pos;
+        }
+        pr->fp.perm = dmeta + used;
+        pr->fp.inv = dmeta + used + R;
+        used += (size_t)2 * R;
     }
     rc = stage_commit(ctx, slot, ws + L.meta, used * 4, st);
     if (rc) return rc;
@@ -823,7 +932,7 @@ icarus_status run_stack(icarus_stack *st, char *ws, const StackLayout &SL, const
     STACK_TRY(launch_embed_rows(st->embed, tok, tok_idx, xa, R, row_bytes, s));
     for (size_t l = 0; l < st->layers.size(); ++l) {
         icarus_status rc = run_layer(st->layers[l], ws, pr.L, pr.rm, &pr.hp, R, decode, false, decode ? 0 : 1, kv_pools[l], bt, max_blocks,
-                                     xa, xb, nullptr, s);
+                                     xa, xb, nullptr, s, &pr.fp);
         if (rc) return stack_fail(st, rc, st->layers[l]->err);
         std::swap(xa, xb);
     }
@@ -925,6 +1034,27 @@ void icarus_destroy(icarus_ctx *ctx) {
     delete ctx;
 }
 
+icarus_status icarus_set_full_decoders(icarus_ctx *ctx, const icarus_full_weights *fw) {
+    if (!ctx) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    if (!fw) {
+        ctx->full_set = false;
+        return ICARUS_OK;
+    }
+    const icarus_layer_config &c = ctx->cfg;
+    if (c.n_models < 1) return fail(ctx, ICARUS_ERR_SHAPE, "private decoder weights need n_models >= 1");
+    if (c.dtype != ICARUS_BF16 || !gemm_mfma_supported(ctx->dm, c.d_model) || !gemm_mfma_supported(ctx->dm, c.n_q_heads * c.head_dim) ||
+        !gemm_mfma_supported(ctx->dm, c.d_ffn))
+        return fail(ctx, ICARUS_ERR_UNSUPPORTED, "private decoder weights need the matrix-core path (bf16, K dimensions multiple of 64)");
+    for (int p : {ICARUS_PROJ_Q, ICARUS_PROJ_O, ICARUS_PROJ_GATE, ICARUS_PROJ_UP, ICARUS_PROJ_DOWN}) {
+        if (!fw->w[p]) return fail(ctx, ICARUS_ERR_INVALID_ARG, "private weights of projection %d are null", p);
+        if (!aligned16(fw->w[p])) return fail(ctx, ICARUS_ERR_ALIGNMENT, "private weights of projection %d are not 16-byte aligned", p);
+    }
+    ctx->full = *fw;
+    ctx->full_set = true;
+    return ICARUS_OK;
+}
+
 icarus_status icarus_set_kernel_mode(icarus_ctx *ctx, int32_t mode) {
     if (!ctx) return ICARUS_ERR_INVALID_ARG;
     if (mode != 0 && mode != 1) return fail(ctx, ICARUS_ERR_INVALID_ARG, "kernel mode %d unknown", mode);
@@ -1000,7 +1130,7 @@ icarus_status icarus_decode_step(icarus_ctx *ctx, void *kv_pool, const int32_t *
                         (hipStream_t)stream, nullptr, 0, &pr);
     if (rc) return rc;
     return run_layer(ctx, (char *)workspace, pr.L, pr.rm, &pr.hp, R, true, false, 0, kv_pool, block_tables, max_blocks, x_in, x_out,
-                     slot_out, (hipStream_t)stream);
+                     slot_out, (hipStream_t)stream, &pr.fp);
 }
 
 icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *block_tables, int32_t max_blocks, int32_t S,

@@ -48,7 +48,7 @@ hipError_t launch_silu_mul(const Dims &dm, const float *gate, const float *up, v
 // summed (`slice` floats apart; splits = 1: the plain array).
 hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, int splits, size_t slice, const RowMeta &rm,
                               const int32_t *bt, int max_blocks, void *pool, void *q_out, int64_t *slot_out, int slot_by_row,
-                              const void *q_norm, const void *k_norm, int R, hipStream_t st);
+                              const void *q_norm, const void *k_norm, int R, hipStream_t st, const int32_t *row_map = nullptr);
 // out[row, h, :] = softmax(q[row,h,:] K^T / sqrt(D)) V over positions 0..row_kvlen[row]-1 of row_seq[row]
 hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, const int32_t *bt, int max_blocks,
                                const RowMeta &rm, void *out, int R, hipStream_t st);

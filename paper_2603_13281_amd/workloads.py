@@ -29,6 +29,7 @@ class DecodeWorkload:
     x_host: list
     headroom: int
     kv_scales: tuple = None   # (k_scale, v_scale) when the pool holds FP8 codes
+    full: dict = None         # host float32 private decoder weights p -> [M, out, in] (instead of adapters)
 
     def ctx_lens(self, step: int) -> np.ndarray:
         return (self.batch.ctx_lens + step).astype(np.int32)
@@ -59,6 +60,8 @@ SPECS = {
 }
 SPECS["c3-fp8"] = SPECS["c3"][:4] + (SPECS["c3"][4] + "; KV cache in FP8 E4M3 (static scales)",)
 SPECS["c3-small-fp8"] = SPECS["c3-small"][:4] + ("reduced config 3, FP8 KV cache",)
+SPECS["c3-full"] = SPECS["c3"][:4] + (SPECS["c3"][4] + "; decoders with private full weights instead of adapters",)
+SPECS["c3-small-full"] = SPECS["c3-small"][:4] + ("reduced config 3, private decoder weights",)
 SPECS["c5-fp8"] = SPECS["c5"][:4] + (SPECS["c5"][4] + "; KV cache in FP8 E4M3 (static scales)",)
 FP8_POOL_SCALE = 4.0 / 448.0   # the synthetic cache is N(0,1) clipped at 4 sigma: 4 sigma -> the largest code
 
@@ -109,8 +112,23 @@ def build_decode_workload(name: str, device="cuda:0", headroom: int = 128, seed:
     bt = torch.from_numpy(batch.block_tables).to(device)
     xs_host = [synth.make_hidden(shape, batch.R, seed=seed, tag=10 + i) for i in range(n_x)]
     xs = [upload(x, shape.bf16, device) for x in xs_host]
+    full_host = None
+    if name.endswith("-full"):   # every decoder its own weights: base + N(0, 0.01), made on the device, copied back for the oracle
+        say(f"[workload {name}] private decoder weights")
+        g2 = torch.Generator(device=device)
+        g2.manual_seed(5000 + seed)
+        full_dev, full_host = {}, {}
+        for p in ("q", "o", "gate", "up", "down"):
+            w = dbase[p]
+            t = torch.empty((shape.n_models,) + tuple(w.shape), dtype=w.dtype, device=device)
+            for j in range(shape.n_models):
+                t[j] = (w.float() + 0.01 * torch.randn(w.shape, generator=g2, device=device)).to(w.dtype)
+            full_dev[p] = t
+            full_host[p] = t.float().cpu().numpy()
+        layer.set_full_decoders(full_dev)
+        lora = None
     return DecodeWorkload(name, desc, shape, batch, base, lora, layer, pool, bt, xs, xs_host, headroom,
-                          (FP8_POOL_SCALE, FP8_POOL_SCALE) if fp8 else None)
+                          (FP8_POOL_SCALE, FP8_POOL_SCALE) if fp8 else None, full_host)
 
 
 def build_private_kv_baseline(wl: DecodeWorkload, device="cuda:0", seed: int = 0, n_x: int = 4) -> DecodeWorkload:

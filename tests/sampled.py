@@ -52,14 +52,14 @@ def snapshot_prefixes(shape, pool_dev, block_tables, ctx_lens, sample, kv_scales
 
 
 def decode_sample_check(shape, base, lora, prefixes, ctx_lens, row_seq, row_model, x_host, x_dev_out, tol, what,
-                        slots_dev=None, block_tables=None, kv_scales=None):
+                        slots_dev=None, block_tables=None, kv_scales=None, full=None):
     """Oracle decode step of the sequences in `prefixes` (their K/V before the call), compared with
     the device output rows of those sequences.  Returns timing and sizes of the sample."""
     import torch
     sample = sorted(prefixes)
     Bk = shape.block_size
     need = [(int(ctx_lens[s]) + 1 + Bk - 1) // Bk for s in sample]
-    orc = oracle.Oracle(oracle_config(shape, sum(need), lora is not None, kv_scales), base, lora)
+    orc = oracle.Oracle(oracle_config(shape, sum(need), lora is not None or full is not None, kv_scales), base, lora, full=full)
     pool = orc.new_pool()
     bt = np.zeros((len(sample), max(need)), dtype=np.int32)
     k = 0

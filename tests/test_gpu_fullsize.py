@@ -26,7 +26,7 @@ def _sample_sequences(batch, ctx, n_random, seed):
     return sorted(picks)
 
 
-@pytest.mark.parametrize("name,n_random", [("c3", 1), ("c5", 0), ("c2", 0), ("c3-fp8", 1)])
+@pytest.mark.parametrize("name,n_random", [("c3", 1), ("c5", 0), ("c2", 0), ("c3-fp8", 1), ("c3-full", 0)])
 def test_decode_full_size_sampled(name, n_random):
     import sampled
     from paper_2603_13281_amd import workloads
@@ -45,7 +45,7 @@ def test_decode_full_size_sampled(name, n_random):
     torch.cuda.synchronize()
     assert torch.isfinite(x_out.to(torch.float32)).all()
     info = sampled.decode_sample_check(sh, wl.base, wl.lora, prefixes, ctx, b.row_seq, b.row_model, wl.x_host[0], x_out, TOL_BF16,
-                                       f"{name} full-size sample", slots_dev=slots, block_tables=b.block_tables, kv_scales=wl.kv_scales)
+                                       f"{name} full-size sample", slots_dev=slots, block_tables=b.block_tables, kv_scales=wl.kv_scales, full=wl.full)
     assert info["rows"] >= len(sample)
     # every slot index, exactly; and no cache byte changed outside the S written slots
     Bk = sh.block_size
