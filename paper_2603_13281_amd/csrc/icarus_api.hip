@@ -59,7 +59,10 @@ struct icarus_ctx {
     int mode = 0;
     int attn_chunk_override = 0;  // longest attention piece in tokens; 0 = automatic (ICARUS_ATTN_CHUNK, for experiments and tests)
     int attn_wgs = 256;           // workgroups of the decode attention: Hkv per equal share of the work (ICARUS_ATTN_WGS)
-    int attn_weight_base = 128;   // per-token cost of a piece = this + stacked queries (ICARUS_ATTN_WEIGHT)
+    // cost model of the decode attention plan, from per-workgroup timings: a cached token costs
+    // attn_weight_base + attn_weight_tile * (16-query tiles of its sequence), a piece as much as
+    // attn_piece_tokens tokens on top (ICARUS_ATTN_WEIGHT, ICARUS_ATTN_TILE_WEIGHT, ICARUS_ATTN_PIECE)
+    int attn_weight_base = 128, attn_weight_tile = 7, attn_piece_tokens = 768;
     char err[512];
     StageSlot slots[kSlots];
     int next_slot = 0;
@@ -344,42 +347,54 @@ void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t
         return;
     }
     // ---- decode: equal shares of the weighted work line
-    auto weight = [&](int s) { return (int64_t)(ctx->attn_weight_base + seq_rows[s] * g); };  // cost of one cached token
+    auto weight = [&](int s) {  // cost of one cached token
+        return (int64_t)(ctx->attn_weight_base + ctx->attn_weight_tile * ((seq_rows[s] * g + 15) / 16));
+    };
+    auto piece_cost = [&](int s) { return (int64_t)ctx->attn_piece_tokens * weight(s); };  // fixed cost of starting a piece
     int64_t total = 0, tokens = 0;
     for (int s = 0; s < S; ++s)
         if (seq_rows[s] > 0) {
-            total += (int64_t)kv_lens[s] * weight(s);
+            total += (int64_t)kv_lens[s] * weight(s) + piece_cost(s);
             tokens += kv_lens[s];
         }
     if (tokens == 0) return;
     const int cap = ctx->attn_chunk_override > 0 ? std::max(32, ctx->attn_chunk_override / 32 * 32) : kAttnMaxChunk;  // longest piece
-    int n_wgs = (int)std::max<int64_t>(1, std::min<int64_t>(std::max(1, ctx->attn_wgs / Hkv), tokens / 256));
+    const int max_wgs = (int)std::max<int64_t>(1, std::min<int64_t>(std::max(1, ctx->attn_wgs / Hkv), tokens / 256));
     struct Piece { int32_t s, begin, len, wg; };
     std::vector<Piece> pieces;
-    int wg = 0;
-    int64_t remaining = total;                          // weighted work not yet handed out
-    int64_t room = (remaining + n_wgs - 1) / n_wgs;     // ... and what the current share can still take
-    for (int s = 0; s < S; ++s) {
-        if (seq_rows[s] <= 0) continue;
-        const int64_t wt = weight(s);
-        int begin = 0;
-        while (begin < kv_lens[s]) {
-            if (wg < n_wgs - 1 && room < 64 * wt) {
-                // not worth a piece: the next share starts, with an equal part of what is left
-                ++wg;
-                room = (remaining + (n_wgs - wg) - 1) / (n_wgs - wg);
+    // Shares are filled in order up to a target cost T (tokens x weight + a fixed cost per piece); a share closes when
+    // what is left of its target would not pay for another piece.  T is the smallest target with which max_wgs shares
+    // take everything (bisection: the fill is monotone in T), so that no share, the last included, exceeds it.
+    const int min_piece = std::max(64, ctx->attn_piece_tokens);  // a shorter piece is not worth its fixed cost
+    auto fill = [&](int64_t T, bool emit) {
+        int wg = 0;
+        int64_t room = T;
+        for (int s = 0; s < S; ++s) {
+            if (seq_rows[s] <= 0) continue;
+            const int64_t wt = weight(s), pc = piece_cost(s);
+            int begin = 0;
+            while (begin < kv_lens[s]) {
+                const int left = kv_lens[s] - begin;
+                if (room < pc + (int64_t)std::min(left, min_piece) * wt && room < T) {  // a fresh share always takes something
+                    ++wg;
+                    room = T;
+                }
+                int64_t fit = std::max<int64_t>(room - pc, 0) / wt;
+                int len = (int)std::min<int64_t>({(int64_t)left, (int64_t)cap, std::max<int64_t>(32, fit / 32 * 32)});
+                if (len < left) len = std::max(32, len / 32 * 32);  // inner boundaries on whole 32-token groups
+                if (emit) pieces.push_back({s, begin, len, wg});
+                begin += len;
+                room -= pc + (int64_t)len * wt;
             }
-            int left = kv_lens[s] - begin;
-            int64_t fit = wg < n_wgs - 1 ? room / wt : (int64_t)left;  // the last share takes whatever remains
-            int len = (int)std::min<int64_t>({(int64_t)left, (int64_t)cap, std::max<int64_t>(32, fit / 32 * 32)});
-            if (len < left) len = std::max(32, len / 32 * 32);  // inner boundaries on whole 32-token groups
-            pieces.push_back({s, begin, len, wg});
-            begin += len;
-            room -= (int64_t)len * wt;
-            remaining -= (int64_t)len * wt;
         }
+        return wg + 1;
+    };
+    int64_t lo = total / max_wgs, hi = 2 * total + 1;  // fill(hi) is a single share (cuts forced by the longest piece cost far less than total)
+    while (lo < hi) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (fill(mid, false) <= max_wgs) hi = mid; else lo = mid + 1;
     }
-    n_wgs = wg + 1;
+    int n_wgs = fill(lo, true);
     const size_t n_items = pieces.size();
     if (n_items > max_items) return;
     int32_t *item_seq = m + at, *item_begin = item_seq + n_items, *item_len = item_begin + n_items,
@@ -1018,6 +1033,8 @@ icarus_status icarus_create(const icarus_layer_config *cfg, const icarus_base_we
     if (const char *e = getenv("ICARUS_ATTN_CHUNK")) ctx->attn_chunk_override = atoi(e);
     if (const char *e = getenv("ICARUS_ATTN_WGS")) ctx->attn_wgs = std::max(1, atoi(e));
     if (const char *e = getenv("ICARUS_ATTN_WEIGHT")) ctx->attn_weight_base = std::max(1, atoi(e));
+    if (const char *e = getenv("ICARUS_ATTN_TILE_WEIGHT")) ctx->attn_weight_tile = std::max(0, atoi(e));
+    if (const char *e = getenv("ICARUS_ATTN_PIECE")) ctx->attn_piece_tokens = std::max(0, atoi(e));
     *out = ctx;
     return ICARUS_OK;
 }
