@@ -212,7 +212,14 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
     // the refill's issue and the barrier's wake-up.
     const int fr = lane & 31, fh = lane >> 5;
     constexpr int KS = BK / 16;
-    bf16x8 fa[TM], fb[TN];  // fragments of the K step to multiply next
+    static_assert(KS % 2 == 0, "the two fragment sets alternate over the K steps of a slab");
+    // Two fragment sets used alternately: while the MFMAs of one K step run from one set, the reads of
+    // the next step fill the other.  A wave issues in order and an MFMA holds the issue slot until the
+    // matrix pipe takes it, so the reads must be issued BEFORE the MFMAs they are to overlap with; the
+    // compiler, left alone, sinks them behind the MFMAs to save the second set (measured on a bare loop:
+    // 63 % of the matrix pipe's rate with 4 waves per CU, 87 % with the order pinned), hence the
+    // scheduling barriers.
+    bf16x8 fa[2][TM], fb[2][TN];
     auto read_frags = [&](int stage, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
         const char *sA = smem + stage * kStage, *sB = sA + kBOff;
 #pragma unroll
@@ -227,46 +234,53 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     };
+    // K steps 0 .. KS-2 of the slab in `stage`; set 0 holds step 0 on entry, set 1 holds step KS-1 on exit
+    auto slab_head = [&](int stage) {
+#pragma unroll
+        for (int ks = 0; ks + 1 < KS; ++ks) {
+            read_frags(stage, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(fa[ks & 1], fb[ks & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     auto wait_for_slab = [&](int younger) {  // younger: slabs enqueued after the one waited for
         if (NS > 4 && younger >= 3) wait_loads<(NS > 4 ? 3 : 0) * NL>();
         else if (NS > 3 && younger >= 2) wait_loads<(NS > 3 ? 2 : 0) * NL>();
         else if (younger >= 1) wait_loads<NL>();
         else wait_loads<0>();
     };
+    // Ring of NS stages.  One barrier per slab, placed before the last 16-wide K step of slab kt is
+    // multiplied: by then every wave has read all of slab kt into registers, so after the barrier
+    // (which also follows each wave's wait for its own loads of slab kt+1) slab kt+1 is complete
+    // in LDS and the stage of slab kt can be refilled with slab kt+NS.  The first fragments of slab
+    // kt+1 are fetched right after the barrier and the pending MFMAs of slab kt cover their latency,
+    // the refill's issue and the barrier's wake-up.
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
         if (s < nk) issue(s, s);
     wait_for_slab(min(NS - 2, nk - 1));
     __builtin_amdgcn_s_barrier();
     if (NS - 1 < nk) issue(NS - 1, NS - 1);
-    read_frags(0, 0, fa, fb);
+    read_frags(0, 0, fa[0], fb[0]);
     int stage = 0, kt = 0;
     // Steady state: the slab to enqueue (kt+NS) lies in the base weights, so the section after the
-    // barrier is straight-line code, scheduled by hand: fetch the first fragments of slab kt+1,
-    // then alternate the pending MFMAs of slab kt with the loads of slab kt+NS, so that the matrix
-    // pipe is fed while the wave issues its memory instructions.
+    // barrier is straight-line code: the first fragments of slab kt+1, then the pending MFMAs of slab
+    // kt alternating with the loads of slab kt+NS, so that the matrix pipe is fed while the wave
+    // issues its memory instructions.
     const int n_steady = min(nk, max(0, (K_base - k_begin) / BK)) - NS;
     for (; kt < n_steady; ++kt) {
-        bf16x8 ga[TM], gb[TN];
-#pragma unroll
-        for (int ks = 0; ks + 1 < KS; ++ks) {
-            read_frags(stage, ks + 1, ga, gb);
-            mma(fa, fb);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = ga[i];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = gb[j];
-        }
+        slab_head(stage);
         const int next = stage + 1 == NS ? 0 : stage + 1;
         wait_loads<(NS - 2) * NL>();
         __builtin_amdgcn_s_barrier();
-        read_frags(next, 0, ga, gb);
+        read_frags(next, 0, fa[0], fb[0]);
         const int k0 = k_begin + (kt + NS) * BK;
         const uint32_t la = lds0 + stage * kStage + w * 1024;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < TM * TN; ++t) {
-            acc[t / TN][t % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[t / TN], fb[t % TN], acc[t / TN][t % TN], 0, 0, 0);
+            acc[t / TN][t % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][t / TN], fb[1][t % TN], acc[t / TN][t % TN], 0, 0, 0);
 #pragma unroll
             for (int l = t * NL / (TM * TN); l < (t + 1) * NL / (TM * TN); ++l) {
                 if (l < A_LD) dma16(pa[l] + k0, la + l * (NW * 1024));
@@ -274,35 +288,20 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = ga[i];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[j] = gb[j];
         stage = next;
     }
     for (; kt < nk; ++kt) {  // the last slabs: adapter columns to enqueue, or nothing left to enqueue
-        bf16x8 ga[TM], gb[TN];
-#pragma unroll
-        for (int ks = 0; ks + 1 < KS; ++ks) {
-            read_frags(stage, ks + 1, ga, gb);
-            mma(fa, fb);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = ga[i];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = gb[j];
-        }
+        slab_head(stage);
         const int next = stage + 1 == NS ? 0 : stage + 1;
         if (kt + 1 < nk) {
             wait_for_slab(min(NS - 2, nk - 2 - kt));
             __builtin_amdgcn_s_barrier();
+            read_frags(next, 0, fa[0], fb[0]);
+            __builtin_amdgcn_sched_barrier(0);
             if (kt + NS < nk) issue(kt + NS, stage);
-            read_frags(next, 0, ga, gb);
         }
-        mma(fa, fb);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = ga[i];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[j] = gb[j];
+        mma(fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
         stage = next;
     }
 
@@ -325,8 +324,22 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
     const int n_lim = g.n_seg[dual ? 0 : seg];
     const int lpr = wcols / 8, rpp = 64 / lpr;                              // lanes per row, rows per pass
     const int rr0 = lane / lpr, c8 = (lane % lpr) * 8;
+    // The residual rows of the next 32-row group are requested before this group is turned through
+    // LDS, so that their latency (HBM: another kernel wrote them) is not paid once per pass.
+    constexpr int kPasses = WN / 16;  // passes over a 32-row group when the wave's columns are all outputs
+    const bool with_resid = !dual && g.epi != EPI_F32;
+    uint4 rres[2][kPasses];
+    auto load_resid = [&](int i, uint4 (&dst)[kPasses]) {
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
+            const int row = row0 + wm * WM + i * 32 + rr0 + p * rpp, n_in = n_wave + c8;
+            dst[p] = (row < g.R && n_in < n_lim) ? *(const uint4 *)(g.resid + (size_t)row * g.ldr + col_base + n_in) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    if (with_resid) load_resid(0, rres[0]);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        if (with_resid && i + 1 < TM) load_resid(i + 1, rres[(i + 1) & 1]);
         if (dual) {
             if constexpr (kMayBeDual) {
 #pragma unroll
@@ -343,7 +356,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
 #pragma unroll
                 for (int r = 0; r < 16; ++r) scr[(8 * (r >> 2) + row_l + (r & 3)) * kEs + j * 32 + col_l] = acc[i][j][r];
         }
-        for (int rr = rr0; rr < 32; rr += rpp) {
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
+            const int rr = rr0 + p * rpp;
+            if (rr >= 32) break;  // the fused gate/up tile has half the output columns: half the passes
             const int row = row0 + wm * WM + i * 32 + rr, n_in = n_wave + c8;
             if (row >= g.R || n_in >= n_lim) continue;  // output widths are multiples of 8
             const float4 a = *(const float4 *)(scr + rr * kEs + c8), b = *(const float4 *)(scr + rr * kEs + c8 + 4);
@@ -356,7 +372,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
                 continue;
             }
             if (!dual) {  // EPI_BF16_RESID
-                const uint4 rv = *(const uint4 *)(g.resid + (size_t)row * g.ldr + n);
+                const uint4 rv = rres[i & 1][p];
                 const uint32_t rw[4] = {rv.x, rv.y, rv.z, rv.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
