@@ -204,12 +204,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
         }
     };
 
-    // Ring of NS stages.  One barrier per slab, placed before the last 16-wide K step of slab kt is
-    // multiplied: by then every wave has read all of slab kt into registers, so after the barrier
-    // (which also follows each wave's wait for its own loads of slab kt+1) slab kt+1 is complete
-    // in LDS and the stage of slab kt can be refilled with slab kt+NS.  The first fragments of slab
-    // kt+1 are fetched right after the barrier and the pending MFMAs of slab kt cover their latency,
-    // the refill's issue and the barrier's wake-up.
     const int fr = lane & 31, fh = lane >> 5;
     constexpr int KS = BK / 16;
     static_assert(KS % 2 == 0, "the two fragment sets alternate over the K steps of a slab");
