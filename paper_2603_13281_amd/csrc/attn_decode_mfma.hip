@@ -405,6 +405,80 @@ __device__ __forceinline__ void shared_walk(State<NT> &st, const void *__restric
     __syncthreads();  // the ring may be reused now
 }
 
+// 16-byte LDS-direct load: lane i copies 16 bytes from its own global address to LDS byte lds_base + 16 i
+// (lds_base wave-uniform, passed in m0); the load counts in vmcnt until the data is in LDS.
+__device__ __forceinline__ void dma16(const void *g, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(g) : "memory");
+}
+
+// The shared walk of a bf16 cache with the ring filled by LDS-direct loads.  A wave's 16-byte loads of a
+// group ARE its MFMA fragments in lane order, so they can land in the ring as they are: no register buffer,
+// and what is in flight is bounded by LDS, not by VGPRs.  The ring (the same 128 KB) is cut into four
+// stages of two groups; in round r wave w loads half (w & 1: K or V^T fragments) of group 2r + w/2, three
+// rounds ahead -- 96 KB in flight per CU against 64 KB with one group per wave in registers, which is what
+// the five-tile walk was short of (a round waited for the load issued one round earlier).  Each wave issues
+// exactly 8 loads per round (a group past the end is clamped to the last one and never read), so the
+// number of younger loads at a wait is known: vmcnt(16) leaves the two younger rounds in flight.  One
+// barrier per round: after it every wave's loads of round r are in LDS and every wave has finished round
+// r-1, whose stage takes the loads of round r+3.
+template <int NT, int N>
+__device__ __forceinline__ void shared_walk_dma(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
+                                                int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int half, int c,
+                                                int Hkv, bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds,
+                                                float scale_log2, int lane) {
+    constexpr int kStages = 4, kStageFrags = 2 * 16;  // fragments (1 KiB each) per stage
+    static_assert(kRingBytes == (size_t)kStages * kStageFrags * 1024, "ring size");
+    const int n_grp = (n_tok + kGrp - 1) / kGrp;
+    const int n_round = (n_grp + 1) / 2;
+    const int part = w & 1, gl = w >> 1;
+    const int m = lane & 15, q = lane >> 4;
+    const size_t head_stride = (size_t)2 * kBk * kD;
+    const uint32_t ring0 = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)ring;
+    auto issue = [&](int r) {
+        const int grp = min(2 * r + gl, n_grp - 1);
+        const int blk0 = __builtin_amdgcn_readfirstlane(blds[min(grp * 2, n_blk - 1)]);
+        const int blk1 = __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + 1, n_blk - 1)]);
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(ring0 + ((r & (kStages - 1)) * kStageFrags + gl * 16 + part * 8) * 1024);
+        if (part == 0) {  // K fragments k[t][ks]: block m/8, token 8((m/4)%2) + 4t + m%4, d = 32ks + 8q
+            const bf16_t *kb = pool + ((size_t)((m >> 3) ? blk1 : blk0) * Hkv + c) * head_stride +
+                               (size_t)(8 * ((m >> 2) & 1) + (m & 3)) * kD + 8 * q;
+#pragma unroll
+            for (int i = 0; i < 2 * kKS; ++i) dma16(kb + (size_t)(4 * (i / kKS)) * kD + 32 * (i % kKS), dst + i * 1024);
+        } else {  // V^T fragments v[dt]: block q/2, d = 16dt + m, tokens 8(q%2) .. +7
+            const bf16_t *vb = pool + ((size_t)((q >> 1) ? blk1 : blk0) * Hkv + c) * head_stride + (size_t)kBk * kD +
+                               (size_t)m * kBk + 8 * (q & 1);
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) dma16(vb + (size_t)(16 * dt) * kBk, dst + dt * 1024);
+        }
+    };
+#pragma unroll
+    for (int r = 0; r < kStages - 1; ++r)
+        if (r < n_round) issue(r);
+#pragma nounroll
+    for (int r = 0; r < n_round; ++r) {
+        const int younger = min(n_round, r + kStages - 1) - (r + 1);  // rounds this wave has issued after round r
+        if (younger >= 2) __builtin_amdgcn_s_waitcnt(0x0f70 | 0x4000);  // vmcnt(16)
+        else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | 8);  // vmcnt(8)
+        else __builtin_amdgcn_s_waitcnt(0x0f70);                        // vmcnt(0)
+        __syncthreads();
+        if (r + kStages - 1 < n_round) issue(r + kStages - 1);
+        const int grp = 2 * r + half;
+        if (grp < n_grp) {
+            const bf16x8 *src = ring + ((size_t)(r & (kStages - 1)) * kStageFrags + half * 16) * 64 + lane;
+            KVFrag gfr;
+#pragma unroll
+            for (int i = 0; i < 2 * kKS; ++i) gfr.k[i / kKS][i % kKS] = src[i * 64];
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) gfr.v[dt] = src[(2 * kKS + dt) * 64];
+            if (grp >= n_clean)
+                compute_group<NT, N, true>(st, gfr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
+            else
+                compute_group<NT, N, false>(st, gfr, qlds, kGrp, stag, scale_log2, lane);
+        }
+    }
+    __syncthreads();  // the ring may be reused now
+}
+
 // LDS image of a state: o as [dt][qt][i][lane], then m[qt][lane], l[qt][lane].
 template <int NT>
 __device__ __forceinline__ void merge_from_lds(State<NT> &st, const float *__restrict__ lds, int lane) {
@@ -580,11 +654,18 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     } else {
         const int role = w >> 1, half = w & 1;  // role: which query tiles; half: which groups
         bf16x8 *ring = (bf16x8 *)lds;
-        if (role == 0)
-            shared_walk<NA, NA, KV8>(st, pool_v, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
-        else
-            shared_walk<NA, NB, KV8>(st, pool_v, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
-                                     scale_log2, lane);
+        if constexpr (KV8) {  // codes are expanded on the way into the ring: through registers
+            if (role == 0)
+                shared_walk<NA, NA, KV8>(st, pool_v, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
+            else
+                shared_walk<NA, NB, KV8>(st, pool_v, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
+                                         scale_log2, lane);
+        } else if (role == 0) {
+            shared_walk_dma<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
+        } else {
+            shared_walk_dma<NA, NB>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
+                                    scale_log2, lane);
+        }
         if constexpr (KV8) {
 #pragma unroll
             for (int qt = 0; qt < NA; ++qt)
