@@ -471,11 +471,10 @@ hipError_t launch_cfg(GemmArgs g, hipStream_t st) {
 // stream at about 60% of the rate), the grid must fill 256 CUs, so tiles stay 128 wide in N and K is
 // split, and the row tile is the smallest that covers the stacked rows in one or two tiles (64, 128,
 // 192 rows), which keeps the activation re-reads and the ring small enough for two workgroups per CU.
-enum TileKind { TILE_AUTO = 0, TILE_128, TILE_128_NARROW, TILE_256x128, TILE_384x128_W8, TILE_256x256, TILE_256x256_K64,
-                TILE_192x128_N3, TILE_192x128_N2, TILE_64x128, TILE_KINDS };
+enum TileKind { TILE_AUTO = 0, TILE_128, TILE_256x128, TILE_256x256_K64, TILE_192x128_N3, TILE_192x128_N2, TILE_64x128, TILE_KINDS };
 struct TileShape { int bm, bn, bk; };
-constexpr TileShape kTileShape[TILE_KINDS] = {{0, 0, 0},      {128, 128, 64}, {128, 128, 32}, {256, 128, 32}, {384, 128, 32},
-                                              {256, 256, 32}, {256, 256, 64}, {192, 128, 64}, {192, 128, 64}, {64, 128, 64}};
+constexpr TileShape kTileShape[TILE_KINDS] = {{0, 0, 0},      {128, 128, 64}, {256, 128, 32}, {256, 256, 64},
+                                              {192, 128, 64}, {192, 128, 64}, {64, 128, 64}};
 
 // ICARUS_GEMM_CFG = "<tile kind>" forces one tile shape for every GEMM (experiments, tests).
 int forced_tile() {
@@ -538,10 +537,7 @@ hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st) {
     if (g.K % bk) return hipErrorInvalidValue;
     g.k_per_split = ((g.K_ext + g.splits - 1) / g.splits + bk - 1) / bk * bk;
     switch (kind) {
-    case TILE_128_NARROW: return launch_cfg<128, 128, 32, 4, 2, 2>(g, st);
     case TILE_256x128: return launch_cfg<256, 128, 32, 4, 2, 2>(g, st);
-    case TILE_384x128_W8: return launch_cfg<384, 128, 32, 4, 4, 2>(g, st);
-    case TILE_256x256: return launch_cfg<256, 256, 32, 4, 2, 4>(g, st);
     case TILE_256x256_K64: return launch_cfg<256, 256, 64, 2, 2, 4>(g, st);
     case TILE_192x128_N3: return launch_cfg<192, 128, 64, 3, 2, 2>(g, st);
     case TILE_192x128_N2: return launch_cfg<192, 128, 64, 2, 2, 2>(g, st);

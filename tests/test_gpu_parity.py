@@ -115,6 +115,23 @@ def test_decode_ragged_batch(shape, mode):
     _check_decode(shape, ctx, n_active, seed=11, mode=mode)
 
 
+@pytest.mark.parametrize("rows", [100, 230, 300])
+def test_decode_row_counts_of_every_gemm_tile(rows):
+    # The GEMM launcher picks its tile from the stacked row count: up to 64, up to 128, 193-256 (fused gate/up),
+    # up to 384.  The other cases of this file stay below 64 rows; these reach the other tiles, each with a
+    # ragged last row tile.
+    _say("case: decode with", rows, "stacked rows")
+    shape = synth.LLAMA_SMALL
+    S = rows // 5
+    ctx = [(7 * i) % 45 for i in range(S)]
+    n_active = [4] * S
+    extra = rows - 5 * S                       # one shorter sequence makes up the exact count
+    if extra:
+        ctx.append(33)
+        n_active.append(extra - 1)
+    _check_decode(shape, ctx, n_active, seed=21, mode=MODES[0])
+
+
 @pytest.mark.parametrize("mode", MODES)
 def test_decode_long_context_many_models(mode):
     _say("case: long context decode mode", mode)
