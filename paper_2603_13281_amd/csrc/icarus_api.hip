@@ -971,7 +971,9 @@ icarus_status run_stack(icarus_stack *st, char *ws, const StackLayout &SL, const
         STACK_TRY(launch_rmsnorm(dm, xh, st->final_norm, xn, n_head, dm.d, s));
         STACK_TRY(launch_gemm_generic(dm, xn, dm.d, st->lm_head, n_head, st->vocab, dm.d, lg, st->vocab, s));
     }
-    STACK_TRY(launch_argmax(lg, n_head, st->vocab, next_out, s));
+    // the normed rows are dead once the logits exist: their buffer takes the argmax partials
+    if (argmax_scratch_bytes(n_head) > (size_t)n_head * row_bytes) return stack_fail(st, ICARUS_ERR_UNSUPPORTED, "d_model too small for the argmax scratch");
+    STACK_TRY(launch_argmax(lg, n_head, st->vocab, next_out, xn, s));
     if (seq_next && pick) STACK_TRY(launch_pick_rows(next_out, pick, seq_next, n_pick, s));
     return ICARUS_OK;
 }

@@ -146,7 +146,9 @@ hipError_t launch_embed_rows(const void *embed, const int32_t *tok, const int32_
 // out[i, :] = x[rows[i], :]
 hipError_t launch_gather_rows(const void *x, const int32_t *rows, void *out, int n, int row_bytes, hipStream_t st);
 // token[row] = first index of the largest of logits[row, 0..V)
-hipError_t launch_argmax(const float *logits, int R, int V, int32_t *token, hipStream_t st);
+// scratch: argmax_scratch_bytes(R) bytes of device memory, 8-byte aligned (partial results)
+size_t argmax_scratch_bytes(int R);
+hipError_t launch_argmax(const float *logits, int R, int V, int32_t *token, void *scratch, hipStream_t st);
 // seq_next[s] = row_next[last_row[s]]
 hipError_t launch_pick_rows(const int32_t *row_next, const int32_t *last_row, int32_t *seq_next, int S, hipStream_t st);
 
