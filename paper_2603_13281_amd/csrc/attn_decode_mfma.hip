@@ -335,32 +335,25 @@ __device__ __forceinline__ void wave_walk8(State<NT> &st, const uint8_t *__restr
     }
 }
 
-// The walk used when the query tiles are split over wave pairs (more than 3 tiles).  Every group
-// must reach two waves (one per tile set) but should come from HBM once and stay a distinct load
-// in flight, so loading and computing are decoupled: in each round of four groups wave w loads
-// group 4r + w into registers, publishes it to an LDS ring as MFMA fragments in lane order, and
-// after one barrier computes the two groups of its parity (half) for its own tiles from the ring.
-// The loads of the next round are in flight while a round is computed.  ring: [2][4][16][64] x 16 B.
-template <int NT, int N, bool KV8 = false>
-__device__ __forceinline__ void shared_walk(State<NT> &st, const void *__restrict__ pool_v, const int *__restrict__ blds,
-                                            int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int half, int c,
-                                            int Hkv, bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds,
-                                            float scale_log2, int lane) {
+// The walk used when the query tiles are split over wave pairs (more than 3 tiles), for an FP8 cache (a bf16
+// cache takes shared_walk_dma below).  Every group must reach two waves (one per tile set) but should come
+// from HBM once and stay a distinct load in flight, so loading and computing are decoupled: in each round of
+// four groups wave w loads the raw codes of group 4r + w into registers, expands them to bf16 MFMA fragments
+// (k-step order of KVRaw8) as it publishes them to an LDS ring in lane order, and after one barrier computes
+// the two groups of its parity (half) for its own tiles from the ring.  The loads of the next round are in
+// flight while a round is computed.  ring: [2][4][16][64] x 16 B.
+template <int NT, int N>
+__device__ __forceinline__ void shared_walk8(State<NT> &st, const uint8_t *__restrict__ pool8, const int *__restrict__ blds,
+                                             int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int half, int c,
+                                             int Hkv, bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds,
+                                             float scale_log2, int lane) {
     const int n_grp = (n_tok + kGrp - 1) / kGrp;                       // groups, the masked ones included
     const int n_round = (n_grp + 3) / 4;                               // the same for every wave
     auto blk_of = [&](int grp, int which) {
         return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
     };
-    // bf16 cache: fragments as loaded.  FP8 cache: raw codes in registers, expanded to bf16 fragments when
-    // they are published (k-step order of KVRaw8), so that the ring and its readers are the same.
-    const bf16_t *pool = (const bf16_t *)pool_v;
-    const uint8_t *pool8 = (const uint8_t *)pool_v;
-    KVFrag f;
     KVRaw8 f8;
-    auto load = [&](int grp) {
-        if constexpr (KV8) load_group8(f8, pool8, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
-        else load_group(f, pool, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
-    };
+    auto load = [&](int grp) { load_group8(f8, pool8, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane); };
     if (w < n_grp) load(w);
 #pragma nounroll
     for (int r = 0; r < n_round; ++r) {
@@ -368,20 +361,13 @@ __device__ __forceinline__ void shared_walk(State<NT> &st, const void *__restric
         const int mine = 4 * r + w;
         if (mine < n_grp) {
             bf16x8 *dst = stage + (size_t)w * 16 * 64 + lane;
-            if constexpr (KV8) {
 #pragma unroll
-                for (int i = 0; i < 2 * kKS; ++i) {
-                    const uint4 rk = f8.k[i / kKS][(i % kKS) >> 1];
-                    dst[i * 64] = (i & 1) ? cvt8(rk.z, rk.w) : cvt8(rk.x, rk.y);
-                }
-#pragma unroll
-                for (int dt = 0; dt < kDT; ++dt) dst[(2 * kKS + dt) * 64] = cvt8(f8.v[dt].x, f8.v[dt].y);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 2 * kKS; ++i) dst[i * 64] = f.k[i / kKS][i % kKS];
-#pragma unroll
-                for (int dt = 0; dt < kDT; ++dt) dst[(2 * kKS + dt) * 64] = f.v[dt];
+            for (int i = 0; i < 2 * kKS; ++i) {
+                const uint4 rk = f8.k[i / kKS][(i % kKS) >> 1];
+                dst[i * 64] = (i & 1) ? cvt8(rk.z, rk.w) : cvt8(rk.x, rk.y);
             }
+#pragma unroll
+            for (int dt = 0; dt < kDT; ++dt) dst[(2 * kKS + dt) * 64] = cvt8(f8.v[dt].x, f8.v[dt].y);
         }
         if (mine + 4 < n_grp) load(mine + 4);
         __syncthreads();
@@ -655,11 +641,12 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
         const int role = w >> 1, half = w & 1;  // role: which query tiles; half: which groups
         bf16x8 *ring = (bf16x8 *)lds;
         if constexpr (KV8) {  // codes are expanded on the way into the ring: through registers
+            const uint8_t *pool8 = (const uint8_t *)pool_v;
             if (role == 0)
-                shared_walk<NA, NA, KV8>(st, pool_v, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
+                shared_walk8<NA, NA>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
             else
-                shared_walk<NA, NB, KV8>(st, pool_v, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
-                                         scale_log2, lane);
+                shared_walk8<NA, NB>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
+                                     scale_log2, lane);
         } else if (role == 0) {
             shared_walk_dma<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
         } else {
