@@ -114,11 +114,13 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
             s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k[0][ks], qv, s0, 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k[1][ks], qv, s1, 0, 0, 0);
         }
+        // raw scores; the softmax scale (> 0) is applied to their maximum and inside the exponent's fused
+        // multiply-add, not to each score
         float sv[8];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            sv[i] = s0[i] * scale_log2;
-            sv[4 + i] = s1[i] * scale_log2;
+            sv[i] = s0[i];
+            sv[4 + i] = s1[i];
         }
         if (tail) {
             const int lim = left - stag[qt];
@@ -129,6 +131,7 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
         float mx = sv[0];
 #pragma unroll
         for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+        mx *= scale_log2;
         // st.m is a reference exponent, not necessarily the exact running max: it moves (and the
         // accumulators are rescaled) only when some score exceeds it by more than kSlack, so
         // p = 2^(s - m) stays below 2^kSlack and the common case needs no cross-lane exchange.
@@ -151,7 +154,7 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
         bf16x8 pb;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float p = __builtin_amdgcn_exp2f(sv[e] - m_ref);
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[e], scale_log2, -m_ref));
             if (tail && m_ref == -INFINITY) p = 0.f;
             rs += p;
             pb[e] = (__bf16)p;
@@ -257,11 +260,11 @@ __device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, c
     bf16x8 pb[N];
 #pragma unroll
     for (int qt = 0; qt < N; ++qt) {
-        float sv[8];
+        float sv[8];  // raw scores, see compute_group
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            sv[i] = s0[qt][i] * scale_log2;
-            sv[4 + i] = s1[qt][i] * scale_log2;
+            sv[i] = s0[qt][i];
+            sv[4 + i] = s1[qt][i];
         }
         if (tail) {
             const int lim = left - stag[qt];
@@ -272,6 +275,7 @@ __device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, c
         float mx = sv[0];
 #pragma unroll
         for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+        mx *= scale_log2;
         if (__any(mx > st.m[qt] + kSlack)) {  // see compute_group: lazy softmax reference
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
@@ -289,7 +293,7 @@ __device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, c
         float rs = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float p = __builtin_amdgcn_exp2f(sv[e] - m_ref);
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[e], scale_log2, -m_ref));
             if (tail && m_ref == -INFINITY) p = 0.f;
             rs += p;
             pb[qt][e] = (__bf16)p;
@@ -696,9 +700,9 @@ __device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *_
                 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][ks], qv, s1, 0, 0, 0);
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                sv[qt][i] = s0[i] * scale_log2;
-                sv[qt][4 + i] = s1[i] * scale_log2;
+            for (int i = 0; i < 4; ++i) {  // raw scores, see compute_group
+                sv[qt][i] = s0[i];
+                sv[qt][4 + i] = s1[i];
             }
         }
     }
@@ -714,6 +718,7 @@ __device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *_
         float mx = sv[qt][0];
 #pragma unroll
         for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[qt][e]);
+        mx *= scale_log2;
         if (__any(mx > st.m[qt] + kSlack)) {  // see compute_group: lazy softmax reference
             mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
@@ -731,7 +736,7 @@ __device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *_
         float rs = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float p = __builtin_amdgcn_exp2f(sv[qt][e] - m_ref);
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[qt][e], scale_log2, -m_ref));
             if (tail && m_ref == -INFINITY) p = 0.f;
             rs += p;
             pb[qt][e] = (__bf16)p;
