@@ -10,7 +10,7 @@ adapter can reuse it; N adapters working on one context hold N copies (Table 1: 
 O(M + L_t)) and, when memory is full, evict and recompute.
 
 The paper runs inside a serving stack and does not specify the bookkeeping; this is the policy both
-implementations follow (the readings are listed in the design doc):
+implementations follow (each reading where the paper is silent is spelled out below):
 
   * The pool has `num_blocks` blocks of `block_size` tokens.  A block is FREE, LIVE (referenced by
     ref >= 1 sequences) or CACHED (published, ref == 0, evictable).
