@@ -535,7 +535,11 @@ icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, 
 
 icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp, int R,
                              bool use_lora, bool kv_only, int slot_by_row, void *pool, const int32_t *bt, int max_blocks,
-                             const void *x_in, void *x_out, int64_t *slot_out, hipStream_t st) {
+                             const void *x_in, void *x_out, int64_t *slot_out, hipStream_t st, int in_splits = 0,
+                             int *out_splits = nullptr) {
+    // in_splits > 0 (layer stack): the input rows are still in pieces -- the previous layer's down projection left
+    // `in_splits` split-K slices in the workspace and its residual in z -- and are formed (and stored to x_in) by
+    // this layer's first row kernel.  out_splits != null: this layer may leave its own output the same way.
     const icarus_layer_config &c = ctx->cfg;
     const Dims &dm = ctx->dm;
     int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, F = c.d_ffn;
@@ -550,8 +554,14 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
     auto Aw = [&](int p) { return ctx->lora.A[p]; };
     const bool lq = !kv_only && lo(ICARUS_PROJ_Q);
     // RMSNorm, with the shrink of the Q adapters on the normalised rows
-    PHASE(ctx, st, ICARUS_PH_NORM, launch_norm_shrink(dm, x_in, ctx->base.norm_attn, xn, R, d, lq ? Aw(ICARUS_PROJ_Q) : nullptr, nullptr,
-                                                      rm.row_model, T, nullptr, 0, st));
+    if (in_splits > 0) {
+        PHASE(ctx, st, ICARUS_PH_NORM, launch_sum_norm_shrink(dm, (const float *)(ws + L.gemm_part), in_splits, (size_t)R * d, z,
+                                                              const_cast<void *>(x_in), ctx->base.norm_attn, xn, R, d,
+                                                              lq ? Aw(ICARUS_PROJ_Q) : nullptr, nullptr, rm.row_model, T, st));
+    } else {
+        PHASE(ctx, st, ICARUS_PH_NORM, launch_norm_shrink(dm, x_in, ctx->base.norm_attn, xn, R, d, lq ? Aw(ICARUS_PROJ_Q) : nullptr,
+                                                          nullptr, rm.row_model, T, nullptr, 0, st));
+    }
     int qkv_splits = 0, o_splits = 0;
     {   // Q (ICaRusLinear) and the encoder's K, V in one GEMM over [W_q; W_k; W_v]
         GemmArgs g{};
@@ -623,7 +633,7 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
             g.T = T; g.ldt = mr; g.B[0] = Bw(ICARUS_PROJ_DOWN);
         }
         g.Y = x_out; g.ldy = d; g.resid = z; g.ldr = d;
-        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_DOWN, g, st));
+        LORA_TRY(run_gemm(ctx, ws, L, ICARUS_PH_GEMM_DOWN, g, st, out_splits));
     }
     return ICARUS_OK;
 }
@@ -701,11 +711,20 @@ icarus_status run_layer_full(icarus_ctx *ctx, char *ws, const WsLayout &L, const
     return ICARUS_OK;
 }
 
+// Whether run_layer would take rows that are still in pieces (split-K slices + residual) as its input: only the
+// matrix-core path forms its rows in its first row kernel.
+bool layer_takes_slices(icarus_ctx *ctx, bool use_lora) {
+    if (use_lora && ctx->full_set) return false;
+    if (!layer_mfma_supported(ctx)) return false;
+    return (use_lora && has_lora(ctx, ICARUS_PROJ_GATE)) == (use_lora && has_lora(ctx, ICARUS_PROJ_UP));
+}
+
 // ---- the layer, after metadata is on the device ---------------------------------------
 // rows: x_in [R, d].  use_lora: decoder rows get adapter deltas.  kv_only: stop after the append.
 icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowMeta &rm, const HostPlan *hp, int R, bool use_lora, bool kv_only,
                         int slot_by_row, void *pool, const int32_t *bt, int max_blocks, const void *x_in, void *x_out,
-                        int64_t *slot_out, hipStream_t st, const FullPlan *fp = nullptr) {
+                        int64_t *slot_out, hipStream_t st, const FullPlan *fp = nullptr, int in_splits = 0, int *out_splits = nullptr) {
+    if (out_splits) *out_splits = 0;
     if (use_lora && !kv_only && ctx->full_set) {  // decoder rows with private weights
         if (!fp || !layer_mfma_supported(ctx)) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "private decoder weights need the matrix-core path");
         return run_layer_full(ctx, ws, L, rm, hp, *fp, R, slot_by_row, pool, bt, max_blocks, x_in, x_out, slot_out, st);
@@ -713,8 +732,10 @@ icarus_status run_layer(icarus_ctx *ctx, char *ws, const WsLayout &L, const RowM
     if (layer_mfma_supported(ctx)) {
         bool lg = use_lora && has_lora(ctx, ICARUS_PROJ_GATE), lu = use_lora && has_lora(ctx, ICARUS_PROJ_UP);
         if (lg == lu)
-            return run_layer_mfma(ctx, ws, L, rm, hp, R, use_lora, kv_only, slot_by_row, pool, bt, max_blocks, x_in, x_out, slot_out, st);
+            return run_layer_mfma(ctx, ws, L, rm, hp, R, use_lora, kv_only, slot_by_row, pool, bt, max_blocks, x_in, x_out, slot_out, st,
+                                  in_splits, out_splits);
     }
+    if (in_splits > 0) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "input rows in pieces need the matrix-core path");
     const icarus_layer_config &c = ctx->cfg;
     const Dims &dm = ctx->dm;
     int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, F = c.d_ffn;
@@ -945,10 +966,16 @@ icarus_status run_stack(icarus_stack *st, char *ws, const StackLayout &SL, const
         if (rc) return stack_fail(st, rc, st->layers[l]->err);
     }
     STACK_TRY(launch_embed_rows(st->embed, tok, tok_idx, xa, R, row_bytes, s));
+    // A layer whose down projection was split over K leaves its slices (and the residual) in the workspace when the
+    // next layer can form its input rows from them: the separate reduction launch between two layers is saved.
+    int pending = 0;
     for (size_t l = 0; l < st->layers.size(); ++l) {
+        int left = 0;
+        const bool may_defer = l + 1 < st->layers.size() && layer_takes_slices(st->layers[l + 1], decode);
         icarus_status rc = run_layer(st->layers[l], ws, pr.L, pr.rm, &pr.hp, R, decode, false, decode ? 0 : 1, kv_pools[l], bt, max_blocks,
-                                     xa, xb, nullptr, s, &pr.fp);
+                                     xa, xb, nullptr, s, &pr.fp, pending, may_defer ? &left : nullptr);
         if (rc) return stack_fail(st, rc, st->layers[l]->err);
+        pending = left;
         std::swap(xa, xb);
     }
     // final norm + LM head on the chosen rows, greedy token
