@@ -236,6 +236,8 @@ typedef struct icarus_stack_config {
     const void *embed, *final_norm, *lm_head; /* device */
 } icarus_stack_config;
 
+/* All layers must share one configuration; a row of d_model elements must hold at least 256 bytes
+ * (ICARUS_ERR_UNSUPPORTED otherwise: the greedy token's partial results reuse a row buffer). */
 icarus_status icarus_stack_create(const icarus_stack_config *cfg, icarus_stack **out);
 void icarus_stack_destroy(icarus_stack *st);
 const char *icarus_stack_last_error(const icarus_stack *st);

@@ -1266,6 +1266,9 @@ icarus_status icarus_stack_create(const icarus_stack_config *cfg, icarus_stack *
     }
     const icarus_layer_config &c = cfg->layers[0]->cfg;
     if ((c.d_model * (c.dtype == ICARUS_BF16 ? 2 : 4)) % 16) return fail(nullptr, ICARUS_ERR_SHAPE, "d_model rows must be a multiple of 16 bytes");
+    // the greedy token's partial results take the place of the normed rows once the logits exist
+    if (argmax_scratch_bytes(1) > (size_t)c.d_model * (c.dtype == ICARUS_BF16 ? 2 : 4))
+        return fail(nullptr, ICARUS_ERR_UNSUPPORTED, "a row of d_model must hold at least %zu bytes", argmax_scratch_bytes(1));
     icarus_stack *st = new (std::nothrow) icarus_stack();
     if (!st) return fail(nullptr, ICARUS_ERR_HIP, "out of host memory");
     st->layers.assign(cfg->layers, cfg->layers + cfg->n_layers);
