@@ -971,7 +971,9 @@ icarus_status run_stack(icarus_stack *st, char *ws, const StackLayout &SL, const
     int pending = 0;
     for (size_t l = 0; l < st->layers.size(); ++l) {
         int left = 0;
-        const bool may_defer = l + 1 < st->layers.size() && layer_takes_slices(st->layers[l + 1], decode);
+        // the last layer may do the same when every row goes to the LM head as it is: the final norm sums the slices
+        const bool head_takes_slices = !head_rows && n_head == R && layer_mfma_supported(c0) && gemm_mfma_supported(dm, dm.d);
+        const bool may_defer = l + 1 < st->layers.size() ? layer_takes_slices(st->layers[l + 1], decode) : head_takes_slices;
         icarus_status rc = run_layer(st->layers[l], ws, pr.L, pr.rm, &pr.hp, R, decode, false, decode ? 0 : 1, kv_pools[l], bt, max_blocks,
                                      xa, xb, nullptr, s, &pr.fp, pending, may_defer ? &left : nullptr);
         if (rc) return stack_fail(st, rc, st->layers[l]->err);
@@ -987,7 +989,11 @@ icarus_status run_stack(icarus_stack *st, char *ws, const StackLayout &SL, const
     }
     float *lg = logits ? logits : (float *)(ws + SL.logits);
     if (layer_mfma_supported(c0) && gemm_mfma_supported(dm, dm.d)) {
-        STACK_TRY(launch_norm_shrink(dm, xh, st->final_norm, xn, n_head, dm.d, nullptr, nullptr, nullptr, nullptr, nullptr, 0, s));
+        if (pending > 0)  // the last layer left its output in pieces (only when head_takes_slices)
+            STACK_TRY(launch_sum_norm_shrink(dm, (const float *)(ws + pr.L.gemm_part), pending, (size_t)R * dm.d, ws + pr.L.z, xa, st->final_norm,
+                                             xn, n_head, dm.d, nullptr, nullptr, nullptr, nullptr, s));
+        else
+            STACK_TRY(launch_norm_shrink(dm, xh, st->final_norm, xn, n_head, dm.d, nullptr, nullptr, nullptr, nullptr, nullptr, 0, s));
         GemmArgs g{};
         g.X = (const bf16_raw *)xn; g.ldx = dm.d; g.R = n_head; g.K = dm.d;
         g.W[0] = (const bf16_raw *)st->lm_head; g.n_seg[0] = st->vocab; g.nseg = 1;
