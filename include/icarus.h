@@ -15,8 +15,12 @@
  *  - The CALLER owns all device memory (weights, KV pool, block tables,
  *    activations, workspace).  The library allocates no device memory, frees
  *    nothing of the caller's, and enqueues all work on the caller's stream
- *    without synchronising it.  It keeps a small ring of pinned HOST staging
- *    buffers for per-call metadata.
+ *    without synchronising that stream.  Per-call metadata goes through a ring
+ *    of 16 pinned HOST staging buffers per context: a buffer is allocated
+ *    (hipHostMalloc) the first time its turn comes or when a call needs a
+ *    larger one, and a call that finds its buffer still in use by the call
+ *    made 16 calls earlier blocks the HOST until that call's metadata copy has
+ *    run (back-pressure: at most 16 calls of one context are in flight).
  *  - "host" / "device" after a pointer says where the memory lives.
  *  - Small integer metadata (lengths, row lists) is passed as HOST arrays so it
  *    can be validated; block tables are DEVICE int32 [S, max_blocks].
@@ -139,6 +143,21 @@ icarus_status icarus_validate_decode(icarus_ctx *ctx, int32_t max_blocks, int32_
                                      const int32_t *row_seq /*host [R]*/,
                                      const int32_t *row_model /*host [R]*/);
 
+/* Host-only check of a HOST copy of the block tables (the device table itself is never read back): the
+ * kernels index the pool with the ids they find in the table, so an id outside the pool is an out-of-bounds
+ * device access.  For each sequence s the entries that a call with ctx_lens[s] cached tokens and extra[s] new
+ * tokens touches -- the first ceil((ctx_lens[s] + extra[s]) / block_size) of its row -- must lie in
+ * 0..num_blocks-1 (ICARUS_ERR_CAPACITY otherwise, also when the row is too short), and no block may receive the
+ * new tokens of two different sequences (ICARUS_ERR_INVALID_ARG: the appends would overwrite each other; blocks
+ * that are only read may be shared, as with a common cached prefix).  extra = NULL means one new token per
+ * sequence (a decode step).  Meant for debugging and for callers that build tables from untrusted input; the
+ * entry points themselves trust the device table (Alg. 1 / Alg. 3: the block table is the serving layer's).
+ *   tables            host int32 [S, max_blocks], the same contents as the device table
+ *   ctx_lens, extra   host int32 [S] */
+icarus_status icarus_validate_block_tables(icarus_ctx *ctx, const int32_t *tables /*host*/, int32_t max_blocks,
+                                           int32_t S, const int32_t *ctx_lens /*host*/,
+                                           const int32_t *extra /*host or NULL*/);
+
 /* Prefill of the logical encoder (Alg. 1; Sec. 3.3: prefill uses the encoder only).
  * Sequence s appends chunk_lens[s] new rows at positions ctx_lens[s] .. ctx_lens[s] +
  * chunk_lens[s] - 1 of its (possibly non-empty) paged prefix.  K (after RoPE) and V
@@ -189,6 +208,12 @@ icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *
  * where the shape allows, default), 1 = force the generic vector kernels. */
 icarus_status icarus_set_kernel_mode(icarus_ctx *ctx, int32_t mode);
 
+/* For tests and measurements: the longest piece, in tokens, that the decode attention's plan may give one
+ * workgroup (rounded down to a multiple of 32, at least 32); 0 = automatic (default: up to 16384).  A small
+ * limit cuts even short sequences into several pieces, which exercises the partial-result merge at sizes an
+ * oracle finishes in seconds.  Changes the workspace a call needs: query icarus_workspace_bytes afterwards. */
+icarus_status icarus_set_attn_piece_limit(icarus_ctx *ctx, int32_t tokens);
+
 /* Per-phase kernel timing for measurements.  While enabled, every kernel launch of the entry
  * points above is bracketed by HIP events recorded on the caller's stream (this costs a few
  * microseconds per launch: leave it off when timing whole steps).  icarus_timing_read waits
@@ -205,11 +230,26 @@ icarus_status icarus_timing_read(icarus_ctx *ctx, double *ms /*host*/, int32_t *
  * bytes, against which the profiler's HBM traffic counters are calibrated. */
 icarus_status icarus_bench_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/* Streaming read of `bytes` bytes (a multiple of 8192; src device, 16-byte aligned) by kernel k_bench_read: every
+ * wave reads whole 8 KB chunks -- the size of one (block, kv-head) of the cache -- with 16-byte loads, sixteen in
+ * flight per lane, and stores nothing (out: one device word, written only if the fold of the data hits one value).
+ * For measurements only: the read rate this GPU's HBM sustains, beside the published peak (use a buffer well
+ * beyond the 256 MB memory-side cache). */
+icarus_status icarus_bench_read(const void *src, size_t bytes, uint32_t *out, void *stream);
+
 /* Register-resident matrix-core loop (kernel k_bench_mfma): `waves` wavefronts (a multiple of 4) each issue
  * `iters` rounds of 8 independent 32x32x16 bf16 MFMAs on operands that never leave the registers, then write
  * one float each to out (device, `waves` * 64 floats).  2 * 32*32*16 * 8 * iters * waves flops in all.  For
  * measurements only: the bf16 MFMA rate this GPU sustains, beside the published peak. */
 icarus_status icarus_bench_mfma(float *out, int32_t waves, int32_t iters, void *stream);
+
+/* Switch the context's decoders to private full weights (fw != NULL) or back to its LoRA adapters (NULL).
+ * With private weights icarus_decode_step (and icarus_stack_decode) run every projection once per group of
+ * rows -- the encoder rows with the base weights, the rows of model j with w[p][j] -- i.e. M + 1 grouped
+ * GEMMs over row lists instead of one stacked GEMM: the weights are no longer shared, only the cache is.
+ * Needs the matrix-core path (ICARUS_BF16 shapes it supports), n_models >= 1, 16-byte aligned arrays;
+ * ICARUS_ERR_UNSUPPORTED otherwise.  Prefill is unaffected (encoder only). */
+icarus_status icarus_set_full_decoders(icarus_ctx *ctx, const icarus_full_weights *fw);
 
 /* ---- Layer stack: the outer loop of Alg. 3 and, for the prompt, Alg. 1 --------------------------------------
  * n_layers layer contexts of identical configuration, each with its own KV pool (all pools share the block
@@ -220,14 +260,6 @@ icarus_status icarus_bench_mfma(float *out, int32_t waves, int32_t iters, void *
  * first generated token comes from the base model (Alg. 1, y_prefill).
  * The stack borrows the layer contexts (they must outlive it and must not be used concurrently with it) and
  * the device arrays embed [vocab, d_model], final_norm [d_model], lm_head [vocab, d_model] (storage dtype). */
-/* Switch the context's decoders to private full weights (fw != NULL) or back to its LoRA adapters (NULL).
- * With private weights icarus_decode_step (and icarus_stack_decode) run every projection once per group of
- * rows -- the encoder rows with the base weights, the rows of model j with w[p][j] -- i.e. M + 1 grouped
- * GEMMs over row lists instead of one stacked GEMM: the weights are no longer shared, only the cache is.
- * Needs the matrix-core path (ICARUS_BF16 shapes it supports), n_models >= 1, 16-byte aligned arrays;
- * ICARUS_ERR_UNSUPPORTED otherwise.  Prefill is unaffected (encoder only). */
-icarus_status icarus_set_full_decoders(icarus_ctx *ctx, const icarus_full_weights *fw);
-
 typedef struct icarus_stack icarus_stack;
 typedef struct icarus_stack_config {
     int32_t n_layers;            /* >= 1 */

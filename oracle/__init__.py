@@ -69,6 +69,13 @@ def lib():
     return _lib
 
 
+def set_threads(n: int) -> None:
+    """Number of OpenMP threads the oracle's loops may use from now on (timing only: no result depends on it,
+    the loops split independent output features / heads and no sum is reordered)."""
+    lib()   # the OpenMP runtime is loaded with the oracle
+    C.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
 def _f32(a):
     a = np.ascontiguousarray(a, dtype=np.float32)
     return a

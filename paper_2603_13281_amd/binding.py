@@ -28,7 +28,8 @@ EXPORTS = ("icarus_create", "icarus_destroy", "icarus_last_error", "icarus_works
            "icarus_set_kernel_mode", "icarus_timing_enable", "icarus_timing_read", "icarus_bench_copy", "icarus_bench_mfma", "icarus_stack_create", "icarus_stack_destroy",
            "icarus_stack_last_error", "icarus_stack_workspace_bytes", "icarus_stack_prefill", "icarus_stack_decode",
            "icarus_cache_create", "icarus_cache_destroy", "icarus_cache_last_error", "icarus_cache_acquire", "icarus_cache_extend",
-           "icarus_cache_commit", "icarus_cache_release", "icarus_cache_get_stats", "icarus_set_full_decoders")
+           "icarus_cache_commit", "icarus_cache_release", "icarus_cache_get_stats", "icarus_set_full_decoders",
+           "icarus_validate_block_tables", "icarus_set_attn_piece_limit", "icarus_bench_read")
 
 PHASES = ("norm", "lora", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gateup", "gemm_down",
           "elementwise")
@@ -98,6 +99,10 @@ def _load():
     lib.icarus_decode_step.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.icarus_attn_shared_kv.restype = C.c_int
     lib.icarus_attn_shared_kv.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+    lib.icarus_validate_block_tables.restype = C.c_int
+    lib.icarus_validate_block_tables.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.icarus_set_attn_piece_limit.restype = C.c_int
+    lib.icarus_set_attn_piece_limit.argtypes = [vp, i32]
     lib.icarus_set_kernel_mode.restype = C.c_int
     lib.icarus_set_kernel_mode.argtypes = [vp, i32]
     lib.icarus_timing_enable.restype = C.c_int
@@ -106,6 +111,8 @@ def _load():
     lib.icarus_timing_read.argtypes = [vp, vp, vp]
     lib.icarus_bench_copy.restype = C.c_int
     lib.icarus_bench_copy.argtypes = [vp, vp, sz, vp]
+    lib.icarus_bench_read.restype = C.c_int
+    lib.icarus_bench_read.argtypes = [vp, sz, vp, vp]
     lib.icarus_bench_mfma.restype = C.c_int
     lib.icarus_bench_mfma.argtypes = [vp, C.c_int32, C.c_int32, vp]
     lib.icarus_stack_create.restype = C.c_int
@@ -208,12 +215,48 @@ def _host_i32(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
+def _want(t, what: str, dtype, shape=None, device=None):
+    """Marshalling guard: a device tensor handed to the library must have the element type, the shape and the
+    device the C signature assumes (a numpy-default int64 block table would be read as pairs of int32)."""
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{what}: expected a torch tensor, got {type(t).__name__}")
+    if t.dtype != dtype:
+        raise TypeError(f"{what}: dtype {t.dtype}, the library reads {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{what}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if device is not None and t.device != device:
+        raise ValueError(f"{what}: on {t.device}, expected {device}")
+    if not t.is_cuda:
+        raise ValueError(f"{what}: must be a device tensor")
+
+
 def bench_copy(src: torch.Tensor, dst: torch.Tensor):
     """dst <- src by the library's plain copy kernel (profiler counter calibration)."""
     n = src.numel() * src.element_size()
     rc = _lib.icarus_bench_copy(_ptr(src), _ptr(dst), n, C.c_void_p(torch.cuda.current_stream(src.device).cuda_stream))
     if rc != 0:
         raise IcarusError(rc, "icarus_bench_copy failed")
+
+
+def bench_read(src: torch.Tensor, reps: int = 5) -> float:
+    """Seconds per pass of the library's streaming-read kernel over `src` (whole 8 KB chunks), best of `reps`."""
+    n = src.numel() * src.element_size() // 8192 * 8192
+    out = torch.zeros(1, dtype=torch.int32, device=src.device)
+    stream = C.c_void_p(torch.cuda.current_stream(src.device).cuda_stream)
+    best = None
+    for _ in range(reps + 1):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        rc = _lib.icarus_bench_read(_ptr(src), n, _ptr(out), stream)
+        ev[1].record()
+        if rc != 0:
+            raise IcarusError(rc, "icarus_bench_read failed")
+        torch.cuda.synchronize()
+        t = ev[0].elapsed_time(ev[1]) * 1e-3
+        best = t if best is None else min(best, t)
+    return best
 
 
 def bench_mfma(waves: int, iters: int, device="cuda:0") -> float:
@@ -317,6 +360,42 @@ class IcarusLayer:
     def workspace_bytes(self, max_rows: int, max_seqs: int, max_ctx: int) -> int:
         return int(_lib.icarus_workspace_bytes(self._h, max_rows, max_seqs, max_ctx))
 
+    def set_attn_piece_limit(self, tokens: int):
+        """Longest piece of the decode attention's plan, in tokens (0 = automatic); for tests and measurements."""
+        self._check(_lib.icarus_set_attn_piece_limit(self._h, int(tokens)))
+        self._ws = None
+
+    def validate_block_tables(self, block_tables, ctx_lens, extra=None):
+        """Host-side check of a HOST copy of the block tables ([S, max_blocks] int32)."""
+        bt = np.ascontiguousarray(block_tables)
+        if bt.dtype != np.int32 or bt.ndim != 2:
+            raise TypeError(f"block_tables: need a 2-d int32 array, got {bt.dtype} with {bt.ndim} dims")
+        ctx_lens = _host_i32(ctx_lens)
+        if len(ctx_lens) != bt.shape[0]:
+            raise ValueError(f"ctx_lens has {len(ctx_lens)} entries for {bt.shape[0]} table rows")
+        ex = None if extra is None else _host_i32(extra)
+        if ex is not None and len(ex) != bt.shape[0]:
+            raise ValueError(f"extra has {len(ex)} entries for {bt.shape[0]} table rows")
+        self._check(_lib.icarus_validate_block_tables(self._h, _ptr(bt), bt.shape[1], bt.shape[0], _ptr(ctx_lens), _ptr(ex)))
+
+    def _check_call(self, kv_pool, block_tables, n_seq_meta, what_meta, x=None, x_cols=None, rows=None, outs=()):
+        """Shapes, dtypes and devices of a call's tensors against what the C signature assumes."""
+        dev = block_tables.device if isinstance(block_tables, torch.Tensor) else None
+        _want(block_tables, "block_tables", torch.int32)
+        if block_tables.dim() != 2:
+            raise ValueError(f"block_tables: need [S, max_blocks], got {tuple(block_tables.shape)}")
+        if block_tables.shape[0] != n_seq_meta:
+            raise ValueError(f"{what_meta} has {n_seq_meta} entries for {block_tables.shape[0]} block-table rows")
+        _want(kv_pool, "kv_pool", self.cfg.pool_dtype, None, dev)
+        want = self.cfg.pool_shape()
+        if kv_pool.dim() != 4 or tuple(kv_pool.shape[1:]) != want[1:] or kv_pool.shape[0] < want[0]:
+            raise ValueError(f"kv_pool: shape {tuple(kv_pool.shape)}, expected at least {want[0]} blocks of {want[1:]}")
+        if x is not None:
+            _want(x, "input rows", self.cfg.torch_dtype, (rows, x_cols), dev)
+        for name, t, dtype, shape in outs:
+            if t is not None:
+                _want(t, name, dtype, shape, dev)
+
     def validate_decode(self, max_blocks, ctx_lens, row_seq, row_model):
         ctx_lens, row_seq, row_model = _host_i32(ctx_lens), _host_i32(row_seq), _host_i32(row_model)
         self._check(_lib.icarus_validate_decode(self._h, max_blocks, len(ctx_lens), _ptr(ctx_lens), len(row_seq),
@@ -335,8 +414,13 @@ class IcarusLayer:
     def prefill_kv(self, kv_pool, block_tables, ctx_lens, chunk_lens, x_in, x_out=None, slot_out=None,
                    workspace=None, want_out=True):
         ctx_lens, chunk_lens = _host_i32(ctx_lens), _host_i32(chunk_lens)
-        S, max_blocks = block_tables.shape
+        if len(ctx_lens) != len(chunk_lens):
+            raise ValueError("ctx_lens and chunk_lens differ in length")
         total = int(chunk_lens.sum())
+        self._check_call(kv_pool, block_tables, len(ctx_lens), "ctx_lens", x_in, self.cfg.d_model, total,
+                         (("x_out", x_out if want_out else None, self.cfg.torch_dtype, (total, self.cfg.d_model)),
+                          ("slot_out", slot_out, torch.int64, (total,))))
+        S, max_blocks = block_tables.shape
         if want_out and x_out is None:
             x_out = torch.empty_like(x_in)
         if not want_out:
@@ -351,8 +435,12 @@ class IcarusLayer:
     def decode_step(self, kv_pool, block_tables, ctx_lens, row_seq, row_model, x_in, x_out=None, slot_out=None,
                     workspace=None):
         ctx_lens, row_seq, row_model = _host_i32(ctx_lens), _host_i32(row_seq), _host_i32(row_model)
-        S, max_blocks = block_tables.shape
         R = len(row_seq)
+        if len(row_model) != R:
+            raise ValueError("row_seq and row_model differ in length")
+        self._check_call(kv_pool, block_tables, len(ctx_lens), "ctx_lens", x_in, self.cfg.d_model, R,
+                         (("x_out", x_out, self.cfg.torch_dtype, (R, self.cfg.d_model)), ("slot_out", slot_out, torch.int64, (len(ctx_lens),))))
+        S, max_blocks = block_tables.shape
         if x_out is None:
             x_out = torch.empty_like(x_in)
         max_ctx = int(ctx_lens.max()) + 1 if S else 0
@@ -362,8 +450,18 @@ class IcarusLayer:
                                             _ptr(ws), ws.numel(), self._stream(x_in.device)))
         return x_out
 
+    def _check_attn(self, q, kv_pool, block_tables, kv_lens, row_seq, out):
+        R = len(row_seq)
+        self._check_call(kv_pool, block_tables, len(kv_lens), "kv_lens")
+        _want(q, "q", self.cfg.torch_dtype, None, block_tables.device)
+        if q.numel() != R * self.cfg.n_q_heads * self.cfg.head_dim:
+            raise ValueError(f"q has {q.numel()} elements for {R} rows of {self.cfg.n_q_heads} x {self.cfg.head_dim}")
+        if out is not None:
+            _want(out, "out", self.cfg.torch_dtype, tuple(q.shape), block_tables.device)
+
     def attn_shared_kv(self, q, kv_pool, block_tables, kv_lens, row_seq, out=None, workspace=None):
         kv_lens, row_seq = _host_i32(kv_lens), _host_i32(row_seq)
+        self._check_attn(q, kv_pool, block_tables, kv_lens, row_seq, out)
         S, max_blocks = block_tables.shape
         R = len(row_seq)
         if out is None:

@@ -476,19 +476,6 @@ struct TileShape { int bm, bn, bk; };
 constexpr TileShape kTileShape[TILE_KINDS] = {{0, 0, 0},      {128, 128, 64}, {256, 128, 32}, {256, 256, 64},
                                               {192, 128, 64}, {192, 128, 64}, {64, 128, 64}, {192, 256, 64}};
 
-// ICARUS_GEMM_CFG = "<tile kind>" forces one tile shape for every GEMM (experiments, tests).
-int forced_tile() {
-    static int t = -1;
-    if (t < 0) {
-        t = 0;
-        if (const char *e = getenv("ICARUS_GEMM_CFG")) {
-            int a = 0;
-            if (sscanf(e, "%d", &a) == 1 && a > 0 && a < TILE_KINDS) t = a;
-        }
-    }
-    return t;
-}
-
 int n_tiles_for(const GemmArgs &g, int bm, int bn) {
     int m_tiles = (g.R + bm - 1) / bm, n_tiles = 0;
     if (g.mode == GEMM_DUAL) return m_tiles * ((g.n_seg[0] + bn / 2 - 1) / (bn / 2));
@@ -498,7 +485,6 @@ int n_tiles_for(const GemmArgs &g, int bm, int bn) {
 
 int pick_tile_unchecked(const GemmArgs &g) {
     if (g.tile > 0 && g.tile < TILE_KINDS) return g.tile;
-    if (int f = forced_tile()) return f;
     if (g.R >= 1024 && n_tiles_for(g, 256, 256) >= 192) return TILE_256x256_K64;  // enough large tiles for 256 CUs
     if (g.R <= 64) return TILE_64x128;
     if (g.R <= 128) return TILE_128;

@@ -57,11 +57,11 @@ struct icarus_ctx {
     icarus_full_weights full{};   // private decoder weights (full_set), instead of the adapters
     bool full_set = false;
     int mode = 0;
-    int attn_chunk_override = 0;  // longest attention piece in tokens; 0 = automatic (ICARUS_ATTN_CHUNK, for experiments and tests)
-    int attn_wgs = 256;           // workgroups of the decode attention: Hkv per equal share of the work (ICARUS_ATTN_WGS)
+    int attn_chunk_override = 0;  // longest attention piece in tokens; 0 = automatic (icarus_set_attn_piece_limit)
+    int attn_wgs = 256;           // workgroups of the decode attention: Hkv per equal share of the work
     // cost model of the decode attention plan, from per-workgroup timings: a cached token costs
     // attn_weight_base + attn_weight_tile * (16-query tiles of its sequence), a piece as much as
-    // attn_piece_tokens tokens on top (ICARUS_ATTN_WEIGHT, ICARUS_ATTN_TILE_WEIGHT, ICARUS_ATTN_PIECE)
+    // attn_piece_tokens tokens on top
     int attn_weight_base = 128, attn_weight_tile = 7, attn_piece_tokens = 768;
     char err[512];
     StageSlot slots[kSlots];
@@ -485,35 +485,18 @@ bool layer_mfma_supported(const icarus_ctx *ctx) {
            gemm_mfma_supported(ctx->dm, c.d_ffn) && shrink_ok;
 }
 
-// Experiments: ICARUS_GEMM_PLAN = "tile,splits" pairs for the QKV, O, gate/up and down GEMMs (0 = automatic).
-const int *gemm_plan() {
-    static int plan[16] = {-1};
-    if (plan[0] < 0) {
-        for (int &v : plan) v = 0;
-        if (const char *e = getenv("ICARUS_GEMM_PLAN")) {
-            int i = 0;
-            for (const char *q = e; *q && i < 16; ++i) { plan[i] = atoi(q); while (*q && *q != ',') ++q; if (*q) ++q; }
-        }
-    }
-    return plan;
-}
-
 // One plain ICaRusLinear GEMM.  When its grid would leave most of the chip idle (few rows and a
 // narrow output), K is split over several workgroups into fp32 partials [splits][R][N]; a second
 // small kernel sums them and applies the epilogue, unless the caller takes the slices as they are
 // (deferred_splits: set to the number of slices left in the workspace, 0 if the output is final).
 icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, GemmArgs g, hipStream_t st,
                        int *deferred_splits = nullptr) {
-    const int *plan = gemm_plan();
-    int pi = phase == ICARUS_PH_GEMM_QKV ? 0 : phase == ICARUS_PH_GEMM_O ? 2 : phase == ICARUS_PH_GEMM_DOWN ? 6 : 4;
-    g.tile = plan[pi];
     int tiles = gemm_mfma_tiles(g);
     int n_total = 0;
     for (int s = 0; s < g.nseg; ++s) n_total += g.n_seg[s];
     int k_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
     int splits = 1;
     if (tiles < 160) splits = std::max(1, std::min({kGemmMaxSplits, 256 / tiles, k_ext / 256}));
-    if (plan[pi + 1] > 0) splits = plan[pi + 1];
     splits = (int)std::max<size_t>(1, std::min<size_t>(splits, L.gemm_part_bytes / ((size_t)g.R * n_total * 4)));
     if (deferred_splits) *deferred_splits = 0;
     if (splits == 1) {
@@ -620,7 +603,6 @@ icarus_status run_layer_mfma(icarus_ctx *ctx, char *ws, const WsLayout &L, const
         g.mode = GEMM_DUAL; g.splits = 1; g.r = c.lora_rank; g.M_models = c.n_models;
         if (lg) { g.T = T; g.ldt = 2 * mr; g.B[0] = Bw(ICARUS_PROJ_GATE); g.B[1] = Bw(ICARUS_PROJ_UP); }
         g.Y = h; g.ldy = F;
-        g.tile = gemm_plan()[4];
         PHASE(ctx, st, ICARUS_PH_GEMM_GATEUP, launch_gemm_mfma(g, st));
     }
     {   // down projection (ICaRusLinear) + residual
@@ -1065,11 +1047,6 @@ icarus_status icarus_create(const icarus_layer_config *cfg, const icarus_base_we
     dm.M = c.n_models; dm.r = c.lora_rank; dm.bf16 = c.dtype == ICARUS_BF16; dm.qk_norm = c.qk_norm != 0;
     dm.theta = c.rope_theta; dm.eps = (float)c.rms_eps; dm.lora_scale = (float)c.lora_scale;
     dm.kv8 = c.kv_dtype == ICARUS_KV_FP8_E4M3; dm.k_scale = dm.kv8 ? (float)c.k_scale : 1.f; dm.v_scale = dm.kv8 ? (float)c.v_scale : 1.f;
-    if (const char *e = getenv("ICARUS_ATTN_CHUNK")) ctx->attn_chunk_override = atoi(e);
-    if (const char *e = getenv("ICARUS_ATTN_WGS")) ctx->attn_wgs = std::max(1, atoi(e));
-    if (const char *e = getenv("ICARUS_ATTN_WEIGHT")) ctx->attn_weight_base = std::max(1, atoi(e));
-    if (const char *e = getenv("ICARUS_ATTN_TILE_WEIGHT")) ctx->attn_weight_tile = std::max(0, atoi(e));
-    if (const char *e = getenv("ICARUS_ATTN_PIECE")) ctx->attn_piece_tokens = std::max(0, atoi(e));
     *out = ctx;
     return ICARUS_OK;
 }
@@ -1147,6 +1124,11 @@ icarus_status icarus_timing_read(icarus_ctx *ctx, double *ms, int32_t *launches)
 icarus_status icarus_bench_copy(const void *src, void *dst, size_t bytes, void *stream) {
     if (!src || !dst || bytes % 16 || !aligned16(src) || !aligned16(dst)) return ICARUS_ERR_INVALID_ARG;
     return launch_bench_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? ICARUS_OK : ICARUS_ERR_HIP;
+}
+
+icarus_status icarus_bench_read(const void *src, size_t bytes, uint32_t *out, void *stream) {
+    if (!src || !out || bytes % 8192 || !aligned16(src)) return ICARUS_ERR_INVALID_ARG;
+    return launch_bench_read(src, bytes, out, (hipStream_t)stream) == hipSuccess ? ICARUS_OK : ICARUS_ERR_HIP;
 }
 
 icarus_status icarus_bench_mfma(float *out, int32_t waves, int32_t iters, void *stream) {
@@ -1253,6 +1235,44 @@ icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *
     if (rc) return rc;
     RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
     return run_decode_attention(ctx, ws, L, rm, &hp, q, kv_pool, block_tables, max_blocks, out, R, st);
+}
+
+icarus_status icarus_set_attn_piece_limit(icarus_ctx *ctx, int32_t tokens) {
+    if (!ctx) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    if (tokens < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "piece limit %d is negative", tokens);
+    ctx->attn_chunk_override = tokens;
+    return ICARUS_OK;
+}
+
+icarus_status icarus_validate_block_tables(icarus_ctx *ctx, const int32_t *tables, int32_t max_blocks, int32_t S,
+                                           const int32_t *ctx_lens, const int32_t *extra) {
+    if (!ctx) return ICARUS_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(ctx->mu);
+    const icarus_layer_config &c = ctx->cfg;
+    if (S < 0 || max_blocks < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "negative size");
+    if (S == 0) return ICARUS_OK;
+    if (!tables || !ctx_lens) return fail(ctx, ICARUS_ERR_INVALID_ARG, "null table / ctx_lens");
+    std::vector<int32_t> writer((size_t)c.num_blocks, -1);  // sequence that appends into the block
+    for (int s = 0; s < S; ++s) {
+        const int64_t add = extra ? extra[s] : 1;
+        if (ctx_lens[s] < 0 || add < 0) return fail(ctx, ICARUS_ERR_INVALID_ARG, "sequence %d: negative length", s);
+        const int64_t end = (int64_t)ctx_lens[s] + add;
+        const int64_t nb = (end + c.block_size - 1) / c.block_size;
+        if (nb > max_blocks) return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: %lld tokens need %lld blocks, table has %d", s, (long long)end, (long long)nb, max_blocks);
+        const int32_t *row = tables + (size_t)s * max_blocks;
+        for (int64_t b = 0; b < nb; ++b)
+            if (row[b] < 0 || row[b] >= c.num_blocks)
+                return fail(ctx, ICARUS_ERR_CAPACITY, "sequence %d: block table entry %lld is %d, the pool has blocks 0..%d", s, (long long)b, row[b], c.num_blocks - 1);
+        if (add == 0) continue;
+        for (int64_t b = ctx_lens[s] / c.block_size; b < nb; ++b) {
+            int32_t &w = writer[(size_t)row[b]];
+            if (w >= 0 && w != s)
+                return fail(ctx, ICARUS_ERR_INVALID_ARG, "block %d would be appended to by sequences %d and %d", row[b], w, s);
+            w = s;
+        }
+    }
+    return ICARUS_OK;
 }
 
 // ---- layer stack -----------------------------------------------------------------------------------------

@@ -55,6 +55,8 @@ hipError_t launch_attn_generic(const Dims &dm, const void *q, const void *pool, 
 
 // plain grid-stride copy of `bytes` bytes (multiple of 16), kernel k_bench_copy: profiler calibration
 hipError_t launch_bench_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+// streaming read of `bytes` bytes (whole 8 KB chunks) by kernel k_bench_read: the read rate HBM sustains; out: one word
+hipError_t launch_bench_read(const void *src, size_t bytes, uint32_t *out, hipStream_t st);
 // register-resident MFMA loop, kernel k_bench_mfma: waves (multiple of 4) x iters x 8 MFMAs 32x32x16 bf16
 hipError_t launch_bench_mfma(float *out, int waves, int iters, hipStream_t st);
 

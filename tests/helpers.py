@@ -40,6 +40,52 @@ def filled_batch(shape, batch, seed=0):
     return pool
 
 
+# Cache gate, bf16 storage: |got - want| <= one bf16 ulp of the oracle's value (the entry's own rounding) +
+# CACHE_SLACK_BF16 * rms of the written entries.  The slack is 1.5 x the worst deviation that rounding the normed
+# row to bf16 (what the matrix cores are fed) causes over 10^6 entries: 8.07e-3 rms, sigma 1.66e-3 rms
+# (tests/test_cache_gate_model.py measures both on the CPU and ties this constant to them).
+CACHE_SLACK_BF16 = 1.2e-2
+
+
+def bf16_spacing(x: np.ndarray) -> np.ndarray:
+    """Spacing of bfloat16 at |x| (8 significant bits)."""
+    ax = np.maximum(np.abs(np.asarray(x, dtype=np.float64)), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(ax)) - 7)
+
+
+def assert_cache_close(got, want, bf16: bool, what: str, rms=None):
+    """Cache entries against the oracle's rounded values (see CACHE_SLACK_BF16).  fp32 storage: one ulp plus the
+    fp32 accumulation allowance (1e-5 of the largest entry).  rms: of the written entries; by default of the
+    entries that differ at all."""
+    want = np.asarray(want, dtype=np.float64)
+    diff = np.abs(np.asarray(got, dtype=np.float64) - want)
+    if bf16:
+        if rms is None:
+            written = want[diff > 0]
+            rms = float(np.sqrt(np.mean(written ** 2))) if written.size else 0.0
+        ok = diff <= bf16_spacing(want) * 1.0001 + CACHE_SLACK_BF16 * rms
+    else:
+        ok = diff <= np.abs(want) * 2.0 ** -23 + 1e-5 * float(np.max(np.abs(want)))
+    assert ok.all(), f"{what}: {int((~ok).sum())} cache elements outside the gate, worst {float(diff.max()):.3e}"
+
+
+def e4m3_spacing(x: np.ndarray, scale: float) -> np.ndarray:
+    """Spacing of the FP8 E4M3 grid (times scale) at |x|."""
+    a = np.maximum(np.abs(np.asarray(x, dtype=np.float64)) / scale, 2.0 ** -6)
+    return 2.0 ** (np.floor(np.log2(a)) - 3) * scale
+
+
+def assert_fp8_cache_close(got, want, scale: float, bf16: bool, what: str):
+    """FP8 cache entries (values = code * scale) against the oracle's.  A float decides the code on both sides:
+    the device rounds its fp32 K/V, the oracle its float64 K/V, which differ by the bf16 arithmetic upstream
+    (2^-7 of the tensor's rms covers it); on top of that the rounding may fall one grid step apart."""
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    assert np.isfinite(got).all(), f"{what}: non-finite cache values"
+    slack = (2.0 ** -7 if bf16 else 2.0 ** -16) * np.sqrt(np.mean(want ** 2))
+    ratio = (np.abs(got - want) - slack) / e4m3_spacing(np.maximum(np.abs(got), np.abs(want)), scale)
+    assert ratio.max() <= 1.001, f"{what}: {ratio.max():.3f} grid steps apart; {(ratio > 1.001).sum()} of {ratio.size}"
+
+
 def rel_err(got: np.ndarray, want: np.ndarray) -> float:
     """max|g - o| / max|o| -- the per-tensor gate."""
     want = np.asarray(want, dtype=np.float64)

@@ -10,7 +10,7 @@ import time
 import numpy as np
 
 import oracle
-from helpers import assert_close, fill_pool
+from helpers import assert_cache_close, assert_close, assert_fp8_cache_close, fill_pool, read_pool
 
 
 def kv_to_host(shape, pool_dev, block_table_row, n_tokens, kv_scales=None):
@@ -52,9 +52,11 @@ def snapshot_prefixes(shape, pool_dev, block_tables, ctx_lens, sample, kv_scales
 
 
 def decode_sample_check(shape, base, lora, prefixes, ctx_lens, row_seq, row_model, x_host, x_dev_out, tol, what,
-                        slots_dev=None, block_tables=None, kv_scales=None, full=None):
+                        slots_dev=None, block_tables=None, kv_scales=None, full=None, pool_dev_after=None):
     """Oracle decode step of the sequences in `prefixes` (their K/V before the call), compared with
-    the device output rows of those sequences.  Returns timing and sizes of the sample."""
+    the device output rows of those sequences.  pool_dev_after (with block_tables): the device pool after the
+    call; the K/V entry the call appended for each sampled sequence is compared with the oracle's.
+    Returns timing and sizes of the sample."""
     import torch
     sample = sorted(prefixes)
     Bk = shape.block_size
@@ -84,6 +86,21 @@ def decode_sample_check(shape, base, lora, prefixes, ctx_lens, row_seq, row_mode
         for i, s in enumerate(sample):
             p = int(ctx_lens[s])
             assert int(got_slots[s]) == int(block_tables[s, p // Bk]) * Bk + p % Bk, f"{what}: slot of sequence {s}"
+    if pool_dev_after is not None:   # the values of the appended entries
+        gk, gv, wk, wv = [], [], [], []
+        for i, s in enumerate(sample):
+            p = int(ctx_lens[s])
+            # the block that holds position p, read from the device through the table
+            Kd, Vd = kv_to_host(shape, pool_dev_after, block_tables[s][p // Bk:p // Bk + 1], p % Bk + 1, kv_scales)
+            Ko, Vo = read_pool(pool, bt[i], p + 1)
+            gk.append(Kd[-1]); gv.append(Vd[-1]); wk.append(Ko[-1]); wv.append(Vo[-1])
+        for got_e, want_e, nm, sc in ((np.stack(gk), np.stack(wk), "K", kv_scales[0] if kv_scales else None),
+                                      (np.stack(gv), np.stack(wv), "V", kv_scales[1] if kv_scales else None)):
+            if kv_scales is not None:
+                assert_fp8_cache_close(got_e, want_e, sc, shape.bf16, f"{what}: appended {nm}")
+            else:
+                assert_cache_close(got_e, want_e, shape.bf16, f"{what}: appended {nm}",
+                                   rms=float(np.sqrt(np.mean(want_e.astype(np.float64) ** 2))))
     n_dec = sum(1 for m in rmod if m >= 0)
     return {"seconds": dt, "rows": len(rs), "decoder_rows": n_dec, "cached_tokens": int(sum(int(ctx_lens[s]) + 1 for s in sample)),
             "sample": sample}

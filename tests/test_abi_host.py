@@ -109,3 +109,49 @@ def test_validate_decode_row_rules():
     bad("INVALID_ARG", [-1], [0], [-1])
     ok([127], [0], [-1], mb=8)
     layer.close()
+
+
+def test_validate_block_tables_on_a_host_copy():
+    """Ids outside the pool, rows too short for the call and two sequences appending into one block are refused
+    on the host; shared read-only prefix blocks are fine.  No table, good or bad, is given to a kernel here."""
+    base, lora = _weights()
+    layer = IcarusLayer(_cfg(num_blocks=32), base, lora)
+    bt = np.int32([[3, 4, 5, 0], [3, 4, 9, 0]])                  # blocks 3, 4: a common cached prefix, read only
+    layer.validate_block_tables(bt, [40, 35])                     # decode: one new token each, into blocks 5 and 9
+    layer.validate_block_tables(bt, [32, 33], extra=[15, 15])     # chunks that stay inside blocks 5 and 9
+    layer.validate_block_tables(bt, [47, 0], extra=[1, 0])        # last slot of block 5; sequence 1 touches nothing
+    layer.validate_block_tables(bt[:, :3], [47, 40])
+
+    def bad(status, table, ctx, extra=None):
+        with pytest.raises(IcarusError) as e:
+            layer.validate_block_tables(table, ctx, extra)
+        assert e.value.status_name == status, str(e.value)
+    bad("CAPACITY", np.int32([[3, 32, 5, 0]]), [40])              # id == num_blocks inside the range read
+    bad("CAPACITY", np.int32([[3, -1, 5, 0]]), [40])
+    bad("CAPACITY", np.int32([[3, 4, 5, 77]]), [47], [2])         # the chunk spills into entry 3
+    layer.validate_block_tables(np.int32([[3, 4, 5, 77]]), [40])  # ... which a call that stops before it never reads
+    bad("CAPACITY", bt, [63, 10], [2, 1])                         # 65 tokens need 5 blocks, the row has 4
+    bad("INVALID_ARG", np.int32([[3, 4, 5, 0], [6, 7, 5, 0]]), [40, 39])      # both append into block 5
+    bad("INVALID_ARG", np.int32([[3, 4, 5, 0], [3, 4, 9, 0]]), [20, 20])      # both append into the "shared" block 4
+    bad("INVALID_ARG", bt, [-1, 3])
+    with pytest.raises(TypeError):
+        layer.validate_block_tables(np.int64([[1, 2]]), [3])      # a numpy-default table would be read as int32 pairs
+    with pytest.raises(ValueError):
+        layer.validate_block_tables(bt, [3])
+    layer.close()
+
+
+def test_binding_refuses_tensors_the_c_signature_would_misread():
+    """The marshalling layer checks element type, shape and placement before a pointer crosses the boundary."""
+    import torch
+    base, lora = _weights()
+    layer = IcarusLayer(_cfg(num_blocks=4), base, lora)
+    pool = torch.zeros(layer.cfg.pool_shape(), dtype=torch.bfloat16)
+    x = torch.zeros(2, 256, dtype=torch.bfloat16)
+    with pytest.raises(TypeError):       # int64 table
+        layer.decode_step(pool, torch.zeros(1, 4, dtype=torch.int64), [3], [0, 0], [-1, 0], x)
+    with pytest.raises(ValueError):      # ctx_lens shorter than the table
+        layer.decode_step(pool, torch.zeros(2, 4, dtype=torch.int32), [3], [0, 0], [-1, 0], x)
+    with pytest.raises(ValueError):      # host tensors are not device memory
+        layer.decode_step(pool, torch.zeros(1, 4, dtype=torch.int32), [3], [0, 0], [-1, 0], x)
+    layer.close()

@@ -1,14 +1,15 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle, element by element, on the same
 seeded inputs.  Tolerances (per output tensor): max|g-o|/max|o| <= 2e-2 for bf16 storage, 1e-4 for fp32,
-plus an elementwise rtol/atol gate (helpers.assert_close); cache entries within one storage ulp; slots,
-and everything the call must not touch, bit-exact."""
+plus an elementwise rtol/atol gate (helpers.assert_close); cache entries within one storage ulp plus the slack that
+the bf16 rounding of the normed row causes (helpers.CACHE_SLACK_BF16, measured in tests/test_cache_gate_model.py);
+slots, and everything the call must not touch, bit-exact."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
 from paper_2603_13281_amd import synth
-from helpers import assert_close, fill_pool, filled_batch, oracle_config, read_pool
+from helpers import assert_cache_close, assert_close, fill_pool, filled_batch, oracle_config, read_pool
 from gpu_util import bf16_ulp, dev, host, make_layer, pool_from_device_layout, pool_to_device_layout
 
 pytestmark = pytest.mark.gpu
@@ -22,19 +23,10 @@ def _say(*a):
 
 
 def _cache_close(shape, got_pool, want_pool, what):
-    """Cache entries against the oracle's rounded values.  bf16 storage: the matrix cores take the normed row
-    rounded to bf16 (relative error up to 2^-9 per element), which moves a K/V entry by sigma ~ 1.6e-3 * rms before
-    its own rounding, so the gate is one bf16 ulp of the value plus 2^-6 of the rms of the written entries (~10 sigma).
-    fp32 storage: one ulp plus the fp32 accumulation allowance (1e-5 of the largest entry)."""
-    want = want_pool.astype(np.float64)
-    diff = np.abs(got_pool.astype(np.float64) - want)
-    if shape.bf16:
-        written = want[diff > 0]
-        rms = float(np.sqrt(np.mean(written ** 2))) if written.size else 0.0
-        ok = diff <= bf16_ulp(want_pool) * 1.0001 + 2.0 ** -6 * rms
-    else:
-        ok = diff <= np.abs(want) * 2.0 ** -23 + 1e-5 * float(np.max(np.abs(want)))
-    assert ok.all(), f"{what}: {int((~ok).sum())} cache elements outside the gate, worst {float(diff.max()):.3e}"
+    # pools in the oracle's layout [blocks, 2, Hkv, Bk, D]; K and V are different tensors (with QK-norm K has unit
+    # rms per head, V the scale of the weights), so each plane is gated against the rms of its own written entries
+    for plane, nm in ((0, "K"), (1, "V")):
+        assert_cache_close(got_pool[:, plane], want_pool[:, plane], shape.bf16, f"{what} {nm}")
 
 
 def _decode_case(shape, ctx, n_active, seed, mode, norm_ones=False):
@@ -267,9 +259,12 @@ def test_zero_B_rows_equal_encoder_row_and_runs_are_deterministic(mode):
     orc = oracle.Oracle(oracle_config(shape, batch.num_blocks), base, lora)
     want, _ = orc.decode_step(pool.copy(), batch.block_tables, batch.ctx_lens, batch.row_seq, batch.row_model, x)
     assert_close(y, want, 2e-2, "zero-B x_out")
+    # Sec. 3.2: with B = 0 a decoder is the base model.  On the device too, bit for bit: a row's arithmetic does not
+    # depend on its place in a tile, the adapter's K-steps add exact zeros, and equal queries of one sequence see
+    # equal scores, so every step of a decoder row repeats the encoder row's.
     for r in range(batch.R):
         enc = int(np.flatnonzero((batch.row_seq == batch.row_seq[r]) & (batch.row_model == -1))[0])
-        assert_close(y[r], y[enc], 2e-2, f"row {r} vs encoder row")
+        assert torch.equal(ys[0][r], ys[0][enc]), f"row {r} differs from its sequence's encoder row {enc}"
 
 
 def test_errors_surface_through_the_binding():
@@ -293,12 +288,10 @@ def test_errors_surface_through_the_binding():
 
 @pytest.mark.parametrize("chunk", [0, 128, 256])
 @pytest.mark.parametrize("g,rows", [(4, 1), (4, 4), (4, 9), (8, 2), (8, 7), (8, 9), (1, 3)])
-def test_attn_mfma_tiles_splits_and_tails(g, rows, chunk, monkeypatch):
+def test_attn_mfma_tiles_splits_and_tails(g, rows, chunk):
     # matrix-core attention: every query-tile count (1..5 tiles of 16 stacked queries), single-chunk and
     # split sequences, lengths around the 16-token block, 32-token group and 128-token chunk boundaries
     _say("case: mfma attention g", g, "rows", rows, "chunk", chunk)
-    if chunk:
-        monkeypatch.setenv("ICARUS_ATTN_CHUNK", str(chunk))
     shape = synth.LLAMA_SMALL.replace(n_q_heads=2 * g, n_kv_heads=2, d_model=256, n_models=8)
     lens = [1, 15, 16, 17, 31, 32, 33, 127, 128, 129, 255, 257, 1000, 3001]
     rows_per_seq = [rows if i % 3 else max(1, rows - 1) for i in range(len(lens))]
@@ -312,6 +305,7 @@ def test_attn_mfma_tiles_splits_and_tails(g, rows, chunk, monkeypatch):
     orc = oracle.Oracle(oracle_config(shape, batch.num_blocks), synth.make_base(shape), None)
     want = orc.attn_shared_kv(q, pool, batch.block_tables, lens, row_seq)
     layer = make_layer(shape, synth.make_base(shape), None, batch.num_blocks)
+    layer.set_attn_piece_limit(chunk)          # 0: automatic; else sequences longer than this are cut into pieces
     dpool = dev(pool_to_device_layout(pool), True)
     got = layer.attn_shared_kv(dev(q, True), dpool, torch.from_numpy(batch.block_tables).cuda(), lens, row_seq)
     torch.cuda.synchronize()

@@ -311,11 +311,15 @@ def test_cache_is_adapter_independent():
     assert np.array_equal(p3, pool) and np.array_equal(y3, y)
 
 
-def test_decoder_row_equals_merged_weight_model_on_shared_cache():
+@pytest.mark.parametrize("shape", [SHAPES[0], SHAPES[2]], ids=lambda s: s.name)
+def test_decoder_row_equals_merged_weight_model_on_shared_cache(shape):
     # Eq. 5: D_task = base weights + adapter, reading the cache E_base wrote.  A model whose q, o, gate,
     # up, down weights are W + s B A (K/V weights untouched) and no adapter gives the same row when both
     # see the same input (then the entry E_base appends at the current position is the same too).
-    shape = SHAPES[0].replace(lora_target_mask=synth.ALL_TARGETS)
+    # On the QK-norm shape this also fixes where the per-head norm of q sits: after the adapter's delta, as in
+    # the merged model, where it cannot sit anywhere else (a norm taken before the delta would differ by far
+    # more than the float32 storage of the merged weights).
+    shape = shape.replace(lora_target_mask=synth.ALL_TARGETS)
     base, lora, batch, pool, orc = _setup(shape, [29], [2])
     x = synth.make_hidden(shape, 1, seed=6)
     for j in range(shape.n_models):
