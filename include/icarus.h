@@ -21,6 +21,7 @@
  *    larger one, and a call that finds its buffer still in use by the call
  *    made 16 calls earlier blocks the HOST until that call's metadata copy has
  *    run (back-pressure: at most 16 calls of one context are in flight).
+ *    icarus_attn_shared_kv_static uses neither the ring nor a workspace.
  *  - "host" / "device" after a pointer says where the memory lives.
  *  - Small integer metadata (lengths, row lists) is passed as HOST arrays so it
  *    can be validated; block tables are DEVICE int32 [S, max_blocks].
@@ -203,6 +204,21 @@ icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *
                                     const int32_t *kv_lens /*host*/, int32_t R,
                                     const int32_t *row_seq /*host*/, void *out, void *workspace,
                                     size_t workspace_bytes, void *stream);
+
+/* The same attention for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It takes no workspace and allocates nothing, on the device or pinned: what
+ * icarus_attn_shared_kv keeps in the caller's workspace (row arrays, the attention plan, the partial results of
+ * sequences cut into several pieces) lives in a 32 MiB array inside the library's code object, one copy per GPU,
+ * held until the process ends; the per-call metadata reaches it as kernel arguments.  Same arguments, checks and
+ * results as icarus_attn_shared_kv.  A call whose plan needs more than the array holds returns
+ * ICARUS_ERR_CAPACITY (need = 16 R + 4 (plan ints) + pieces * n_kv_heads * largest stacked group * (head_dim + 2)
+ * * 4 bytes; the benchmark decode batches need 10-16 MiB).  Every call on a GPU shares that GPU's array:
+ * calls that may overlap on one GPU (different streams, different contexts) race and must be ordered by the
+ * caller.  Nothing in the array has to start at zero: a call writes every entry it later reads. */
+icarus_status icarus_attn_shared_kv_static(icarus_ctx *ctx, const void *q, const void *kv_pool,
+                                           const int32_t *block_tables, int32_t max_blocks, int32_t S,
+                                           const int32_t *kv_lens /*host*/, int32_t R,
+                                           const int32_t *row_seq /*host*/, void *out, void *stream);
 
 /* Kernel selection for tests and measurements: 0 = automatic (matrix-core kernels
  * where the shape allows, default), 1 = force the generic vector kernels. */

@@ -29,7 +29,7 @@ EXPORTS = ("icarus_create", "icarus_destroy", "icarus_last_error", "icarus_works
            "icarus_stack_last_error", "icarus_stack_workspace_bytes", "icarus_stack_prefill", "icarus_stack_decode",
            "icarus_cache_create", "icarus_cache_destroy", "icarus_cache_last_error", "icarus_cache_acquire", "icarus_cache_extend",
            "icarus_cache_commit", "icarus_cache_release", "icarus_cache_get_stats", "icarus_set_full_decoders",
-           "icarus_validate_block_tables", "icarus_set_attn_piece_limit", "icarus_bench_read")
+           "icarus_validate_block_tables", "icarus_set_attn_piece_limit", "icarus_attn_shared_kv_static", "icarus_bench_read")
 
 PHASES = ("norm", "lora", "gemm_qkv", "rope_append", "attn", "attn_merge", "gemm_o", "gemm_gateup", "gemm_down",
           "elementwise")
@@ -99,6 +99,8 @@ def _load():
     lib.icarus_decode_step.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.icarus_attn_shared_kv.restype = C.c_int
     lib.icarus_attn_shared_kv.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, sz, vp]
+    lib.icarus_attn_shared_kv_static.restype = C.c_int
+    lib.icarus_attn_shared_kv_static.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp]
     lib.icarus_validate_block_tables.restype = C.c_int
     lib.icarus_validate_block_tables.argtypes = [vp, vp, i32, i32, vp, vp]
     lib.icarus_set_attn_piece_limit.restype = C.c_int
@@ -458,6 +460,15 @@ class IcarusLayer:
             raise ValueError(f"q has {q.numel()} elements for {R} rows of {self.cfg.n_q_heads} x {self.cfg.head_dim}")
         if out is not None:
             _want(out, "out", self.cfg.torch_dtype, tuple(q.shape), block_tables.device)
+
+    def attn_shared_kv_static(self, q, kv_pool, block_tables, kv_lens, row_seq, out):
+        """icarus_attn_shared_kv_static: no workspace, nothing allocated (the caller passes `out`)."""
+        kv_lens, row_seq = _host_i32(kv_lens), _host_i32(row_seq)
+        self._check_attn(q, kv_pool, block_tables, kv_lens, row_seq, out)
+        S, max_blocks = block_tables.shape
+        self._check(_lib.icarus_attn_shared_kv_static(self._h, _ptr(q), _ptr(kv_pool), _ptr(block_tables), max_blocks, S,
+                                                      _ptr(kv_lens), len(row_seq), _ptr(row_seq), _ptr(out), self._stream(q.device)))
+        return out
 
     def attn_shared_kv(self, q, kv_pool, block_tables, kv_lens, row_seq, out=None, workspace=None):
         kv_lens, row_seq = _host_i32(kv_lens), _host_i32(row_seq)

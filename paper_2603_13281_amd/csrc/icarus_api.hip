@@ -17,9 +17,29 @@
 
 using namespace icarus;
 
+// ---- device scratch of the entry point that allocates nothing ------------------------------------------
+// icarus_attn_shared_kv_static keeps what icarus_attn_shared_kv keeps in the caller's workspace -- row arrays,
+// the attention plan, the partial results of cut sequences -- in this array.  Every GPU the library runs on holds
+// its own copy until the process ends.  In host code the array's name is only a stand-in: the address that
+// kernels and copies take is the one hipGetSymbolAddress returns for the current device (static_scratch()).
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Per-call metadata of that entry point travels to the device as kernel arguments (no pinned host buffer to
+// allocate, nothing for the host to wait on): kStageInts ints per launch.
+constexpr int kStageInts = 960;
+struct StageChunk { int32_t v[kStageInts]; };
+__global__ void __launch_bounds__(256) k_stage_ints(StageChunk c, int32_t *__restrict__ dst, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = c.v[i];
+}
+
 namespace {
 
 constexpr int kSlots = 16;  // pinned staging ring depth
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};  // device address of `scratch` on each GPU, once looked up
+std::mutex g_scratch_mu;
 
 struct StageSlot {
     void *host = nullptr;
@@ -223,6 +243,34 @@ icarus_status stage_commit(icarus_ctx *ctx, StageSlot *s, void *dev, size_t byte
         hipError_t e__ = (expr);                                                                   \
         if (e__ != hipSuccess) return fail(ctx, ICARUS_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e__)); \
     } while (0)
+
+// Device address of the static scratch array on the current GPU (looked up once per device).
+icarus_status static_scratch(icarus_ctx *ctx, char **out) {
+    int dev = -1;
+    HIP_TRY(ctx, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ctx, ICARUS_ERR_UNSUPPORTED, "device %d: at most %d devices", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(ctx, ICARUS_ERR_HIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (char *)g_scratch_ptr[dev];
+    return ICARUS_OK;
+}
+
+// Copy n host ints to device memory through kernel arguments.
+icarus_status stage_by_kernarg(icarus_ctx *ctx, const int32_t *src, size_t n, int32_t *dst, hipStream_t st) {
+    for (size_t at = 0; at < n; at += kStageInts) {
+        StageChunk c;
+        const int k = (int)std::min<size_t>(kStageInts, n - at);
+        memcpy(c.v, src + at, (size_t)k * 4);
+        hipLaunchKernelGGL(k_stage_ints, dim3((k + 255) / 256), dim3(256), 0, st, c, dst + at, k);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    return ICARUS_OK;
+}
 
 // Run one launch; with phase timing on, bracket it with events on the launch stream.
 #define PHASE(ctx, st, phase, expr)                                                 \
@@ -1186,9 +1234,11 @@ icarus_status icarus_prefill_kv(icarus_ctx *ctx, void *kv_pool, const int32_t *b
                      x_out, slot_out, (hipStream_t)stream);
 }
 
-icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *kv_pool, const int32_t *block_tables,
-                                    int32_t max_blocks, int32_t S, const int32_t *kv_lens, int32_t R, const int32_t *row_seq,
-                                    void *out, void *workspace, size_t workspace_bytes, void *stream) {
+// Shared-KV attention alone.  use_static: the device scratch is the library's static array (nothing is allocated,
+// the metadata travels as kernel arguments); else the caller's workspace and the pinned staging ring.
+static icarus_status attn_shared_kv_impl(icarus_ctx *ctx, const void *q, const void *kv_pool, const int32_t *block_tables,
+                                         int32_t max_blocks, int32_t S, const int32_t *kv_lens, int32_t R, const int32_t *row_seq,
+                                         void *out, void *workspace, size_t workspace_bytes, bool use_static, void *stream) {
     if (!ctx) return ICARUS_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> lk(ctx->mu);
     const icarus_layer_config &c = ctx->cfg;
@@ -1210,14 +1260,27 @@ icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *
     }
     if (!q || !out) return fail(ctx, ICARUS_ERR_INVALID_ARG, "q / out is null");
     if (!aligned16(q) || !aligned16(out)) return fail(ctx, ICARUS_ERR_ALIGNMENT, "q and out must be 16-byte aligned");
-    WsLayout L = ws_layout(ctx, (size_t)R, (size_t)S, (size_t)max_ctx);
-    icarus_status rc = check_common_ptrs(ctx, kv_pool, block_tables, workspace, workspace_bytes, L.total);
-    if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
-    StageSlot *slot;
-    rc = stage_acquire(ctx, L.meta_ints * 4, &slot);
-    if (rc) return rc;
-    int32_t *m = (int32_t *)slot->host;
+    WsLayout L = ws_layout(ctx, (size_t)R, (size_t)S, (size_t)max_ctx);
+    icarus_status rc;
+    char *ws = (char *)workspace;
+    StageSlot *slot = nullptr;
+    std::vector<int32_t> hostmeta;
+    int32_t *m;
+    if (use_static) {
+        if (!kv_pool || !block_tables) return fail(ctx, ICARUS_ERR_INVALID_ARG, "kv_pool / block_tables is null");
+        if (!aligned16(kv_pool) || !aligned16(block_tables)) return fail(ctx, ICARUS_ERR_ALIGNMENT, "kv_pool and block_tables must be 16-byte aligned");
+        rc = static_scratch(ctx, &ws);
+        if (rc) return rc;
+        hostmeta.resize(L.meta_ints);
+        m = hostmeta.data();
+    } else {
+        rc = check_common_ptrs(ctx, kv_pool, block_tables, workspace, workspace_bytes, L.total);
+        if (rc) return rc;
+        rc = stage_acquire(ctx, L.meta_ints * 4, &slot);
+        if (rc) return rc;
+        m = (int32_t *)slot->host;
+    }
     std::vector<int32_t> row0((size_t)S, 0), rows((size_t)S, 0);
     for (int r = 0; r < R; ++r) {
         int s = row_seq[r];
@@ -1227,14 +1290,39 @@ icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *
         m[3 * R + r] = kv_lens[s];
         if (rows[s]++ == 0) row0[s] = r;
     }
-    char *ws = (char *)workspace;
+    if (use_static) L.meta = 0;  // the static scratch starts with the metadata
     const int32_t *dmeta = (const int32_t *)(ws + L.meta);
     HostPlan hp;
     build_attn_plan(ctx, m, (size_t)4 * R, dmeta, S, kv_lens, row0.data(), rows.data(), nullptr, false, L.max_items, &hp);
-    rc = stage_commit(ctx, slot, ws + L.meta, ((size_t)4 * R + hp.ints) * 4, st);
+    const size_t used = (size_t)4 * R + hp.ints;
+    if (use_static) {
+        // what THIS call needs, from its own plan: metadata, then the partial results of its pieces
+        const size_t pj = hp.valid ? (size_t)hp.pl.n_items * c.n_kv_heads * hp.pl.g_max : 0;
+        L.part_o = align_up(used * 4, 256);
+        L.part_ml = align_up(L.part_o + pj * c.head_dim * 4, 256);
+        const size_t need = L.part_ml + pj * 2 * 4;
+        if (need > kStaticScratchBytes)
+            return fail(ctx, ICARUS_ERR_CAPACITY, "this call needs %zu bytes of scratch, the static array holds %zu", need, kStaticScratchBytes);
+        rc = stage_by_kernarg(ctx, m, used, (int32_t *)ws, st);
+    } else {
+        rc = stage_commit(ctx, slot, ws + L.meta, used * 4, st);
+    }
     if (rc) return rc;
     RowMeta rm{dmeta, dmeta + R, dmeta + 2 * R, dmeta + 3 * R};
     return run_decode_attention(ctx, ws, L, rm, &hp, q, kv_pool, block_tables, max_blocks, out, R, st);
+}
+
+icarus_status icarus_attn_shared_kv(icarus_ctx *ctx, const void *q, const void *kv_pool, const int32_t *block_tables,
+                                    int32_t max_blocks, int32_t S, const int32_t *kv_lens, int32_t R, const int32_t *row_seq,
+                                    void *out, void *workspace, size_t workspace_bytes, void *stream) {
+    return attn_shared_kv_impl(ctx, q, kv_pool, block_tables, max_blocks, S, kv_lens, R, row_seq, out, workspace, workspace_bytes, false,
+                               stream);
+}
+
+icarus_status icarus_attn_shared_kv_static(icarus_ctx *ctx, const void *q, const void *kv_pool, const int32_t *block_tables,
+                                           int32_t max_blocks, int32_t S, const int32_t *kv_lens, int32_t R,
+                                           const int32_t *row_seq, void *out, void *stream) {
+    return attn_shared_kv_impl(ctx, q, kv_pool, block_tables, max_blocks, S, kv_lens, R, row_seq, out, nullptr, 0, true, stream);
 }
 
 icarus_status icarus_set_attn_piece_limit(icarus_ctx *ctx, int32_t tokens) {
