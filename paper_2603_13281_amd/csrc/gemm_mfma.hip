@@ -512,13 +512,29 @@ bool gemm_mfma_supported(const Dims &dm, int K) {
     return dm.bf16 && K % kKAlign == 0 && r_ok && n_ok;
 }
 
+// Batches of a few hundred rows against a wide weight matrix (enough 192 x 256 tiles to fill the chip without
+// splitting K: the fused gate/up projection, an LM head) take the register-staged decode kernel.  Narrow
+// projections stay on the smaller LDS-direct tiles of this file: with 192 x 128 tiles they need half as many
+// split-K slices, and the slices' fp32 partial sums are what their epilogues spend their time writing.
+bool gemm_uses_decode(const GemmArgs &g) {
+    return g.R > 192 && g.R < 1024 && g.tile == 0 && gemm_decode_supported(g) && gemm_decode_tiles(g) >= 160;
+}
+
+int gemm_mfma_max_splits(const GemmArgs &g) {
+    if (gemm_uses_decode(g)) return std::max(1, gemm_decode_slabs(g) / 8);
+    int k_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
+    return std::max(1, k_ext / 256);
+}
+
 int gemm_mfma_tiles(const GemmArgs &g) {
+    if (gemm_uses_decode(g)) return gemm_decode_tiles(g);
     int t = pick_tile(g);
     return n_tiles_for(g, kTileShape[t].bm, kTileShape[t].bn);
 }
 
 hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st) {
     if (g.R <= 0) return hipSuccess;
+    if (gemm_uses_decode(g)) return launch_gemm_decode(g, st);
     if (g.mode == GEMM_DUAL)
         g.K_ext = g.K + (g.T ? 2 * g.M_models * g.r : 0);
     else

@@ -542,9 +542,8 @@ icarus_status run_gemm(icarus_ctx *ctx, char *ws, const WsLayout &L, int phase, 
     int tiles = gemm_mfma_tiles(g);
     int n_total = 0;
     for (int s = 0; s < g.nseg; ++s) n_total += g.n_seg[s];
-    int k_ext = g.K + ((g.T && g.B[0]) ? g.M_models * g.r : 0);
     int splits = 1;
-    if (tiles < 160) splits = std::max(1, std::min({kGemmMaxSplits, 256 / tiles, k_ext / 256}));
+    if (tiles < 160) splits = std::max(1, std::min({kGemmMaxSplits, 256 / tiles, gemm_mfma_max_splits(g)}));
     splits = (int)std::max<size_t>(1, std::min<size_t>(splits, L.gemm_part_bytes / ((size_t)g.R * n_total * 4)));
     if (deferred_splits) *deferred_splits = 0;
     if (splits == 1) {

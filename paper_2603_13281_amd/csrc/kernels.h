@@ -100,10 +100,19 @@ struct GemmArgs {
     // filled by the launcher
     int tiles_seg[3]; int m_tiles, n_tiles, K_ext, k_per_split;
     int run, panel_m, panel_n, panels_m, n_panels;  // tile order: panels of panel_m x panel_n <= run tiles
+    int slabs_per_split;                            // decode kernel: 64-wide K slabs per split-K slice
 };
 bool gemm_mfma_supported(const Dims &dm, int K);
 hipError_t launch_gemm_mfma(GemmArgs g, hipStream_t st);
 int gemm_mfma_tiles(const GemmArgs &g);  // workgroups of one K slice
+int gemm_mfma_max_splits(const GemmArgs &g);  // most split-K slices worth launching (each keeps a pipeline's worth of K)
+// The same contraction for decode-sized batches (gemm_decode.hip): both operands loaded coalesced, parked in registers
+// two slabs ahead and staged through LDS by register stores; launch_gemm_mfma takes this path when gemm_uses_decode.
+bool gemm_uses_decode(const GemmArgs &g);
+bool gemm_decode_supported(const GemmArgs &g);
+int gemm_decode_tiles(const GemmArgs &g);
+int gemm_decode_slabs(const GemmArgs &g);
+hipError_t launch_gemm_decode(GemmArgs g, hipStream_t st);
 // Sum split-K partials P[splits][R][N] (fp32) and apply the epilogue `epi` into Y.
 hipError_t launch_splitk_reduce(const float *P, int splits, int R, int N, int epi, void *Y, int ldy, const void *resid,
                                 int ldr, hipStream_t st);
