@@ -228,14 +228,26 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     };
-    // K steps 0 .. KS-2 of the slab in `stage`; set 0 holds step 0 on entry, set 1 holds step KS-1 on exit
+    // K steps 0 .. KS-2 of the slab in `stage`; set 0 holds step 0 on entry, set 1 holds step KS-1 on exit.
+    // A wave issues in order, and an LDS read that the LDS cannot take yet blocks the MFMAs behind it while the
+    // matrix pipe runs dry; so each fragment read of the next step sits right behind an MFMA of this one, whose
+    // passes cover it (a batch of reads ahead of the MFMAs cost the sum of both).
     auto slab_head = [&](int stage) {
+        const char *sA = smem + stage * kStage, *sB = sA + kBOff;
 #pragma unroll
         for (int ks = 0; ks + 1 < KS; ++ks) {
-            read_frags(stage, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-            mma(fa[ks & 1], fb[ks & 1]);
-            __builtin_amdgcn_sched_barrier(0);
+            const int cur = ks & 1, nxt = cur ^ 1;
+#pragma unroll
+            for (int m = 0; m < TM * TN; ++m) {
+                const int i = m / TN, j = m % TN;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+                if (TM * TN >= TM + TN) {
+                    if (m < TM) fa[nxt][m] = *(const bf16x8 *)(sA + swz<CPR>(wm * WM + m * 32 + fr, 2 * (ks + 1) + fh));
+                    else if (m < TM + TN) fb[nxt][m - TM] = *(const bf16x8 *)(sB + swz<CPR>(wn * WN + (m - TM) * 32 + fr, 2 * (ks + 1) + fh));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (TM * TN < TM + TN) read_frags(stage, ks + 1, fa[nxt], fb[nxt]);  // tiles with fewer MFMAs than fragments
         }
     };
     auto wait_for_slab = [&](int younger) {  // younger: slabs enqueued after the one waited for
@@ -341,7 +353,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) k_gemm_mfma(GemmArgs g
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         float gt = acc[i][j][r], up = acc[i][j + TN / 2][r];
-                        scr[(8 * (r >> 2) + row_l + (r & 3)) * kEs + j * 32 + col_l] = gt * __frcp_rn(1.f + __expf(-gt)) * up;
+                        scr[(8 * (r >> 2) + row_l + (r & 3)) * kEs + j * 32 + col_l] = gt * __builtin_amdgcn_rcpf(1.f + __expf(-gt)) * up;  // 1 ulp reciprocal: the result is rounded to bf16
                     }
             }
         } else {

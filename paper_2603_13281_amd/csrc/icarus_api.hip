@@ -367,11 +367,29 @@ void build_attn_plan(const icarus_ctx *ctx, int32_t *m, size_t at, const int32_t
     if (causal ? !attn_prefill_mfma_supported(ctx->dm, g_max) : (!attn_decode_mfma_supported(ctx->dm, g_max) || g_max > kAttnGMax)) return;
     const int32_t *d = dmeta + at;
     if (causal) {
-        // one piece per token group (x kv-heads in the launch), longest contexts first
+        // One piece per token group (x kv-heads in the launch).  The launch maps kv-head c of piece i to workgroup
+        // i * Hkv + c, so with Hkv = 8 every XCD runs one kv-head and takes the pieces in this order, about 32 at a
+        // time: the token groups of one sequence are kept next to each other, so that they walk the sequence's
+        // cached prefix at the same time and all but the first find it in that XCD's L2 (sorted by length alone,
+        // the groups of a sequence were rounds apart and each one fetched the prefix from HBM again).  Sequences
+        // with the longest contexts go first, and within a sequence the longest group.
         std::vector<int32_t> order;
-        for (int s = 0; s < S; ++s)
+        int n_bt = 0;
+        for (int s = 0; s < S; ++s) {
             if (seq_rows[s] > 0) order.push_back(s);
-        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return kv_lens[a] > kv_lens[b]; });
+            n_bt = std::max(n_bt, (seq_bt ? seq_bt[s] : s) + 1);
+        }
+        std::vector<int32_t> longest((size_t)n_bt, 0);  // per block-table row (= sequence of the call)
+        for (int s : order) {
+            int32_t &l = longest[seq_bt ? seq_bt[s] : s];
+            l = std::max(l, kv_lens[s]);
+        }
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+            const int ra = seq_bt ? seq_bt[a] : a, rb = seq_bt ? seq_bt[b] : b;
+            if (longest[ra] != longest[rb]) return longest[ra] > longest[rb];
+            if (ra != rb) return ra < rb;
+            return kv_lens[a] > kv_lens[b];
+        });
         const size_t n_items = order.size();
         int32_t *item_seq = m + at, *seq_kvlen = item_seq + n_items, *row0 = seq_kvlen + S, *rows = row0 + S, *sbt = rows + S;
         for (size_t i = 0; i < n_items; ++i) item_seq[i] = order[i];
