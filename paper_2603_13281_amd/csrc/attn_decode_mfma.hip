@@ -678,34 +678,38 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
 }
 
 // compute_group for a group that sits in LDS as fragments (src[i * 64]: K fragments i = 0..7, then
-// V^T fragments): all tiles' S^T first, so that the K fragments are dead before the V^T fragments
-// are fetched -- half the operand registers of the tile-by-tile form.
+// V^T fragments) with the wave's Q fragments in registers (qr[qt][ks]): all tiles' S^T first, each K
+// fragment fetched once and multiplied with every tile's Q while the next ones arrive, so that no K
+// fragment is live when the V^T fragments are fetched.
 template <int NT, bool tail>
-__device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *__restrict__ src, const bf16x8 *__restrict__ qlds,
+__device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *__restrict__ src, const bf16x8 (&qr)[NT][kKS],
                                                   int left, const int (&stag)[NT], float scale_log2, int lane) {
     const int q = lane >> 4;
     const int tbase = 16 * (q >> 1) + 8 * (q & 1);
     float sv[NT][8];
+    __builtin_amdgcn_s_setprio(1);  // matrix-core sections run at raised priority, see prefill_walk
     {
-        bf16x8 kf[2][kKS];
+        f32x4 s0[NT], s1[NT];
 #pragma unroll
-        for (int i = 0; i < 2 * kKS; ++i) kf[i / kKS][i % kKS] = src[i * 64];
+        for (int qt = 0; qt < NT; ++qt) { s0[qt] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[qt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-        for (int qt = 0; qt < NT; ++qt) {
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < kKS; ++ks) {
+            const bf16x8 k0 = src[ks * 64], k1 = src[(kKS + ks) * 64];
 #pragma unroll
-            for (int ks = 0; ks < kKS; ++ks) {
-                bf16x8 qv = qlds[(qt * kKS + ks) * 64 + lane];
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][ks], qv, s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][ks], qv, s1, 0, 0, 0);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {  // raw scores, see compute_group
-                sv[qt][i] = s0[i];
-                sv[qt][4 + i] = s1[i];
+            for (int qt = 0; qt < NT; ++qt) {
+                s0[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qr[qt][ks], s0[qt], 0, 0, 0);
+                s1[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qr[qt][ks], s1[qt], 0, 0, 0);
             }
         }
+#pragma unroll
+        for (int qt = 0; qt < NT; ++qt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {  // raw scores, see compute_group
+                sv[qt][i] = s0[qt][i];
+                sv[qt][4 + i] = s1[qt][i];
+            }
     }
+    __builtin_amdgcn_s_setprio(0);
     bf16x8 pb[NT];
 #pragma unroll
     for (int qt = 0; qt < NT; ++qt) {
@@ -743,6 +747,7 @@ __device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *_
         }
         st.l[qt] += rs;
     }
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int dt = 0; dt < kDT; ++dt) {
         bf16x8 vf = src[(2 * kKS + dt) * 64];
@@ -754,6 +759,7 @@ __device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *_
 #pragma unroll
         for (int qt = 0; qt < NT; ++qt) st.o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[qt], st.o[dt][qt], 0, 0, 0);
     }
+    __builtin_amdgcn_s_setprio(0);
 }
 
 // Half of a group's loads: part 0 = the 8 K fragments, part 1 = the 8 V^T fragments, in the order
@@ -803,12 +809,15 @@ __device__ __forceinline__ void load_half8(uint2 (&r)[8], int part, const uint8_
 
 // Prefill walk: the eight waves hold different query tiles and every wave needs every group, so a
 // group is loaded once -- in round r wave w loads half (w & 1: K or V^T) of group 4r + w/2 into
-// registers, one round ahead -- published to a one-round LDS ring as MFMA fragments in lane order,
-// and read from there by all eight.  ring: [4][16][64] x 16 B.
+// registers, one round ahead -- published to an LDS ring as MFMA fragments in lane order, and read
+// from there by all eight.  The ring has two stages of one round each: a wave publishes round r into
+// stage r % 2, whose last readers (round r - 2) all passed the barrier of round r - 1, so one barrier
+// per round is enough and the waves may drift up to a round apart (the matrix-core work of one then
+// overlaps the softmax arithmetic of the other on the same SIMD).  ring: [2][4][16][64] x 16 B.
 template <int NT, bool KV8 = false>
 __device__ __forceinline__ void prefill_walk(State<NT> &st, const void *__restrict__ pool_v, const int *__restrict__ blds,
                                              int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int c, int Hkv,
-                                             bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds, float scale_log2,
+                                             bf16x8 *__restrict__ ring, const bf16x8 (&qr)[NT][kKS], float scale_log2,
                                              int lane) {
     const int n_grp = (n_tok + kGrp - 1) / kGrp;  // groups, the masked ones included
     const int n_round = (n_grp + 3) / 4;          // the same for every wave
@@ -825,10 +834,10 @@ __device__ __forceinline__ void prefill_walk(State<NT> &st, const void *__restri
     if (gl < n_grp) load(gl);
 #pragma nounroll
     for (int r = 0; r < n_round; ++r) {
+        bf16x8 *stage = ring + (size_t)(r & 1) * 4 * 16 * 64;
         const int mine = 4 * r + gl;
-        __syncthreads();  // every wave has read the previous round out of the ring
         if (mine < n_grp) {
-            bf16x8 *dst = ring + ((size_t)gl * 16 + part * 8) * 64 + lane;
+            bf16x8 *dst = stage + ((size_t)gl * 16 + part * 8) * 64 + lane;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 if constexpr (KV8) dst[i * 64] = cvt8(h8[i].x, h8[i].y);  // codes are exact in bf16
@@ -837,16 +846,15 @@ __device__ __forceinline__ void prefill_walk(State<NT> &st, const void *__restri
         }
         if (mine + 4 < n_grp) load(mine + 4);
         __syncthreads();
+        // the round's unmasked groups, then its masked ones: two loops of one code path each (with both paths
+        // in one loop body the accumulators are copied between the registers the two paths leave them in)
+        const int n_here = min(4, n_grp - 4 * r), n_plain = max(0, min(n_here, n_clean - 4 * r));
 #pragma nounroll
-        for (int gi = 0; gi < 4; ++gi) {
-            const int grp = 4 * r + gi;
-            if (grp >= n_grp) break;
-            const bf16x8 *src = ring + (size_t)gi * 16 * 64 + lane;
-            if (grp >= n_clean)
-                compute_group_lds<NT, true>(st, src, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
-            else
-                compute_group_lds<NT, false>(st, src, qlds, kGrp, stag, scale_log2, lane);
-        }
+        for (int gi = 0; gi < n_plain; ++gi)
+            compute_group_lds<NT, false>(st, stage + (size_t)gi * 16 * 64 + lane, qr, kGrp, stag, scale_log2, lane);
+#pragma nounroll
+        for (int gi = n_plain; gi < n_here; ++gi)
+            compute_group_lds<NT, true>(st, stage + (size_t)gi * 16 * 64 + lane, qr, n_tok - (4 * r + gi) * kGrp, stag, scale_log2, lane);
     }
 }
 
@@ -869,10 +877,9 @@ __global__ void __launch_bounds__(64 * kPrefillWaves) k_attn_prefill(const bf16_
     const int g = Hq / Hkv, G = T * g;
     const int m = lane & 15, q = lane >> 4;
     const int32_t *btr = bt + (size_t)pl.seq_bt[s] * max_blocks;
-    // LDS: [KV ring 64 KB] [Q fragments: wave, tile, k-step, lane] [block ids]
+    // LDS: [KV ring, two stages of 64 KB] [block ids]; the wave's Q fragments (B operands) stay in registers
     bf16x8 *ring = (bf16x8 *)lds;
-    bf16x8 *qall = ring + 4 * 16 * 64;
-    bf16x8 *qlds = qall + (size_t)w * NT * kKS * 64;
+    bf16x8 qr[NT][kKS];
 #pragma unroll
     for (int qt = 0; qt < NT; ++qt) {
         int j = 16 * (w * NT + qt) + m;
@@ -880,12 +887,15 @@ __global__ void __launch_bounds__(64 * kPrefillWaves) k_attn_prefill(const bf16_
 #pragma unroll
         for (int ks = 0; ks < kKS; ++ks) {  // FP8 cache: the k-step order of KVRaw8
             const int d0 = KV8 ? 64 * (ks >> 1) + 16 * q + 8 * (ks & 1) : 32 * ks + 8 * q;
-            qlds[(qt * kKS + ks) * 64 + lane] = j < G ? *(const bf16x8 *)(qp + d0) : zero8();
+            qr[qt][ks] = j < G ? *(const bf16x8 *)(qp + d0) : zero8();
         }
     }
-    int *blds = (int *)(qall + kPrefillWaves * NT * kKS * 64);
+    int *blds = (int *)(ring + 2 * 4 * 16 * 64);
     const int n_blk = (n_tok + kBk - 1) / kBk;
     for (int i = threadIdx.x; i < n_blk; i += 64 * kPrefillWaves) blds[i] = btr[i];
+    // every load so far has landed: the walk's waits then count its own prefetch loads only (left to its own
+    // bookkeeping the compiler waits for the Q fragments inside the loop, and with them for the prefetch)
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
     __syncthreads();
 
     State<NT> st;
@@ -899,7 +909,7 @@ __global__ void __launch_bounds__(64 * kPrefillWaves) k_attn_prefill(const bf16_
         stag[qt] = T - 1 - min((16 * (w * NT + qt) + m) / g, T - 1);
     }
     const int n_clean = max(0, n_tok - (T - 1)) / kGrp;  // groups valid for every query
-    prefill_walk<NT, KV8>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, c, Hkv, ring, qlds, scale_log2, lane);
+    prefill_walk<NT, KV8>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, c, Hkv, ring, qr, scale_log2, lane);
     if constexpr (KV8) {
 #pragma unroll
         for (int qt = 0; qt < NT; ++qt)
@@ -971,7 +981,7 @@ hipError_t launch_attn_prefill_mfma(const Dims &dm, const void *q, const void *p
     if (!pl.causal || pl.chunk > kAttnMaxChunk) return hipErrorInvalidValue;
     constexpr int NT = kPrefillNT;
     float scale_log2 = kLog2e / sqrtf((float)dm.D) * (dm.kv8 ? dm.k_scale : 1.f);
-    size_t shm = (size_t)4 * 16 * 64 * 16 + (size_t)kPrefillWaves * NT * kKS * 64 * 16 + (size_t)(kAttnMaxChunk / kBk) * 4;
+    size_t shm = (size_t)2 * 4 * 16 * 64 * 16 + (size_t)(kAttnMaxChunk / kBk) * 4;  // two ring stages + the block ids
     auto launch = [&](auto kernel, bool &attr_set) -> hipError_t {
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
