@@ -75,6 +75,13 @@ __device__ __forceinline__ void load_group(KVFrag &f, const bf16_t *__restrict__
     for (int dt = 0; dt < kDT; ++dt) f.v[dt] = *(const bf16x8 *)(vb + (size_t)(16 * dt + m) * kBk + 8 * (q & 1));
 }
 
+// The O^T accumulators live in the accumulation registers, where the matrix cores update them in place.  The
+// rare rescale (a moved softmax reference) multiplies copies in ordinary registers; left to itself the
+// compiler then keeps the accumulators of the common path in ordinary registers too and moves all of them
+// across for every group.  An empty statement that demands its operand in an accumulation register, placed
+// where the two paths meet, keeps the copies inside the rare branch.
+#define ICARUS_IN_ACC(x) asm volatile("" : "+a"(x))
+
 // Per-wave running state for NT query tiles.
 template <int NT>
 struct State {
@@ -107,6 +114,8 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
     }
 #pragma unroll
     for (int qt = 0; qt < N; ++qt) {
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt) ICARUS_IN_ACC(st.o[dt][qt]);
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < kKS; ++ks) {
@@ -147,6 +156,7 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
 #pragma unroll
             for (int dt = 0; dt < kDT; ++dt) {
                 st.o[dt][qt][0] *= alpha; st.o[dt][qt][1] *= alpha; st.o[dt][qt][2] *= alpha; st.o[dt][qt][3] *= alpha;
+                ICARUS_IN_ACC(st.o[dt][qt]);
             }
         }
         const float m_ref = st.m[qt];
@@ -179,11 +189,14 @@ __device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restric
     };
     KVFrag f0, f1;
     if (first < n_clean) load_group(f0, pool, blk_of(first, 0), blk_of(first, 1), c, Hkv, lane);
+    // The loads of the loop are unconditional (past the end blk_of repeats the chunk's last block and the
+    // data is dropped): with a load under a condition the compiler no longer knows how many younger loads
+    // are in flight when a buffer is consumed and waits for all of them, the prefetch included.
 #pragma nounroll
     for (int grp = first; grp < n_clean; grp += 2 * stride) {
-        if (grp + stride < n_clean) load_group(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
+        load_group(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
         compute_group<NT, N, false>(st, f0, qlds, kGrp, stag, scale_log2, lane);
-        if (grp + 2 * stride < n_clean) load_group(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
+        load_group(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
         if (grp + stride < n_clean) compute_group<NT, N, false>(st, f1, qlds, kGrp, stag, scale_log2, lane);
     }
 #pragma nounroll
@@ -244,7 +257,11 @@ __device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, c
     const int tbase = 16 * (q >> 1) + 8 * (q & 1);
     f32x4 s0[N], s1[N];
 #pragma unroll
-    for (int qt = 0; qt < N; ++qt) { s0[qt] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[qt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int qt = 0; qt < N; ++qt) {
+        s0[qt] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int dt = 0; dt < kDT; ++dt) ICARUS_IN_ACC(st.o[dt][qt]);
+    }
 #pragma unroll
     for (int ks = 0; ks < kKS; ++ks) {
         const uint4 r0 = f.k[0][ks >> 1], r1 = f.k[1][ks >> 1];
@@ -287,6 +304,7 @@ __device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, c
 #pragma unroll
             for (int dt = 0; dt < kDT; ++dt) {
                 st.o[dt][qt][0] *= alpha; st.o[dt][qt][1] *= alpha; st.o[dt][qt][2] *= alpha; st.o[dt][qt][3] *= alpha;
+                ICARUS_IN_ACC(st.o[dt][qt]);
             }
         }
         const float m_ref = st.m[qt];
@@ -325,10 +343,10 @@ __device__ __forceinline__ void wave_walk8(State<NT> &st, const uint8_t *__restr
     KVRaw8 f0, f1;
     if (first < n_clean) load_group8(f0, pool, blk_of(first, 0), blk_of(first, 1), c, Hkv, lane);
 #pragma nounroll
-    for (int grp = first; grp < n_clean; grp += 2 * stride) {
-        if (grp + stride < n_clean) load_group8(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
+    for (int grp = first; grp < n_clean; grp += 2 * stride) {  // unconditional loads, see wave_walk
+        load_group8(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
         compute_group8<NT, N, false>(st, f0, qlds, kGrp, stag, scale_log2, lane);
-        if (grp + 2 * stride < n_clean) load_group8(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
+        load_group8(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
         if (grp + stride < n_clean) compute_group8<NT, N, false>(st, f1, qlds, kGrp, stag, scale_log2, lane);
     }
 #pragma nounroll
