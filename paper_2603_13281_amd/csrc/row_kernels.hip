@@ -56,20 +56,20 @@ constexpr int kHeadChunks = 16;  // 16-byte chunks per attention head (head_dim 
 // chain of dependent memory round trips if written naively (row model -> row -> norm -> adapter
 // rows), so the adapter rows, which depend on the row's model only, are requested first and stay
 // one group of loads ahead of the arithmetic throughout.
-template <int SRC, bool NORM, int NACC>
-__global__ void __launch_bounds__(kRowThreads) k_row(RowArgs a) {
+// SHRINK: the row has an adapter (a compile-time flag, so that every load of the main loop is unconditional:
+// the compiler then knows how many younger loads are in flight when it waits for a group and leaves them in
+// flight; with a load under a run-time condition it waits for everything, the group requested ahead included).
+template <int SRC, bool NORM, int NACC, bool SHRINK>
+__device__ __forceinline__ void row_body(const RowArgs &a, int j, float *__restrict__ red,
+                                         float (*__restrict__ part)[NACC > 0 ? NACC : 1], float *__restrict__ res) {
     constexpr int NA = NACC > 0 ? NACC : 1;
-    constexpr int GRP = NA == 32 ? 4 : (NA >= 8 ? 8 : NA);  // adapter rows per group of loads (two groups in flight); 128 registers at 32
+    constexpr int GRP = (NA == 16 || NA == 32) ? 4 : (NA >= 8 ? 8 : NA);  // adapter rows per group of loads (two groups in flight)
     constexpr int NG = NA / GRP;              // groups per chunk: 1, 2, 4 or 8
     constexpr int U = NG < 2 ? 2 : NG;        // steps per unrolled round (two load buffers)
     constexpr bool FIRST_PASS = NORM || SRC != SRC_PLAIN;
-    __shared__ float red[16];
-    __shared__ float part[kRowThreads / 64][NA];
-    __shared__ float res[NA];
+    constexpr bool shrink = SHRINK;
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int K = a.K, n_chunks = K >> 3;
-    const int j = NACC > 0 ? a.row_model[row] : -1;
-    const bool shrink = NACC > 0 && j >= 0;  // uniform over the workgroup
     if (row == 0)
         for (int i = tid; i < a.n_zero; i += kRowThreads) a.zero[i] = 0;
     bf16_t *xr = a.x + (size_t)row * a.ldx;
@@ -79,8 +79,9 @@ __global__ void __launch_bounds__(kRowThreads) k_row(RowArgs a) {
     const int n_steps = my_chunks * NG;  // step t: chunk t / NG of this thread, adapter rows (t % NG) * GRP ...
 
     uint4 av[2][GRP], xb[2], wb[2];
+    // a step past this thread's last one repeats the row's last chunk and its data is dropped
     auto issue = [&](int t, int gi, int b) {
-        const int c = tid + (t / NG) * kRowThreads;
+        const int c = min(tid + (t / NG) * kRowThreads, n_chunks - 1);
         if (gi == 0) {
             if (t > 0 || !FIRST_PASS) xb[b] = *(const uint4 *)(xr + c * 8);  // chunk 0 stays in registers after the first pass
             if (NORM) wb[b] = *(const uint4 *)(a.wn + c * 8);
@@ -93,7 +94,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row(RowArgs a) {
             }
         }
     };
-    if (n_steps > 0) issue(0, 0, 0);
+    issue(0, 0, 0);
 
     // first pass: form the row (and store it), sum of squares
     float f0[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, inv = 1.f;
@@ -188,7 +189,7 @@ __global__ void __launch_bounds__(kRowThreads) k_row(RowArgs a) {
         for (int u = 0; u < U; ++u) {
             const int t = t0 + u, gi = u % NG, b = u & 1;
             if (t < n_steps) {
-                if (t + 1 < n_steps) issue(t + 1, (u + 1) % NG, (u + 1) & 1);
+                issue(t + 1, (u + 1) % NG, (u + 1) & 1);
                 if (gi == 0) {
                     const int c = tid + (t / NG) * kRowThreads;
                     if (FIRST_PASS && t == 0) {
@@ -240,8 +241,19 @@ __global__ void __launch_bounds__(kRowThreads) k_row(RowArgs a) {
     const int mr = a.M * a.r;
     for (int c = tid; c < a.ldt; c += kRowThreads) {
         int t = c / mr, jj = (c % mr) / a.r, i = c % a.r;
-        a.T[(size_t)row * a.ldt + c] = f32_to_bf16(jj == j ? res[t * a.r + i] : 0.f);
+        a.T[(size_t)row * a.ldt + c] = f32_to_bf16(shrink && jj == j ? res[t * a.r + i] : 0.f);
     }
+}
+
+template <int SRC, bool NORM, int NACC>
+__global__ void __launch_bounds__(kRowThreads, NACC == 64 ? 2 : 4) k_row(RowArgs a) {  // four waves per SIMD = two rows per CU, where the registers allow
+    constexpr int NA = NACC > 0 ? NACC : 1;
+    __shared__ float red[16];
+    __shared__ float part[kRowThreads / 64][NA];
+    __shared__ float res[NA];
+    const int j = NACC > 0 ? a.row_model[blockIdx.x] : -1;  // uniform over the workgroup
+    if (NACC > 0 && j >= 0) row_body<SRC, NORM, NACC, true>(a, j, red, part, res);
+    else row_body<SRC, NORM, NACC, false>(a, j, red, part, res);
 }
 
 template <int SRC, bool NORM>
