@@ -529,7 +529,7 @@ bool gemm_mfma_supported(const Dims &dm, int K) {
 // projections stay on the smaller LDS-direct tiles of this file: with 192 x 128 tiles they need half as many
 // split-K slices, and the slices' fp32 partial sums are what their epilogues spend their time writing.
 bool gemm_uses_decode(const GemmArgs &g) {
-    return g.R > 192 && g.R < 1024 && g.tile == 0 && gemm_decode_supported(g) && gemm_decode_tiles(g) >= 160;
+    return g.R > 128 && g.R < 1024 && g.tile == 0 && gemm_decode_supported(g) && gemm_decode_tiles(g) >= 160;
 }
 
 int gemm_mfma_max_splits(const GemmArgs &g) {
