@@ -17,6 +17,7 @@ namespace icarus {
 namespace {
 
 constexpr int kRowThreads = 512;  // threads per row: 8 waves share the K range of one row
+constexpr int kRowMaxWorkgroups = 512;  // a row's accumulators are split over more workgroups while the launch stays below this
 
 __device__ __forceinline__ void unpack8(uint4 v, float (&f)[8]) {
     f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
@@ -69,8 +70,20 @@ __device__ __forceinline__ void row_body(const RowArgs &a, int j, float *__restr
     constexpr bool FIRST_PASS = NORM || SRC != SRC_PLAIN;
     constexpr bool shrink = SHRINK;
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    // blockIdx.y: which NACC of the row's targets * r accumulators this workgroup computes.  Every part forms the
+    // row with the same arithmetic in the same order and stores it (the same bytes from every part: a thread
+    // reads back chunks it stored itself, never another workgroup's).
+    const int part_id = blockIdx.y, acc0 = part_id * NA;
+    const bool owner = part_id == 0;
     const int K = a.K, n_chunks = K >> 3;
-    if (row == 0)
+    const int mr = a.M * a.r;
+    if (!shrink && !owner) {  // a row without adapter: the other parts only clear their share of its row of T
+        if (NACC > 0)
+            for (int c = tid; c < a.ldt; c += kRowThreads)
+                if (((c / mr) * a.r + c % a.r) / NA == part_id) a.T[(size_t)row * a.ldt + c] = 0;
+        return;
+    }
+    if (row == 0 && owner)
         for (int i = tid; i < a.n_zero; i += kRowThreads) a.zero[i] = 0;
     bf16_t *xr = a.x + (size_t)row * a.ldx;
     const bf16_t *pA0 = a.A0 + (size_t)(shrink ? j : 0) * a.r * K;
@@ -89,7 +102,7 @@ __device__ __forceinline__ void row_body(const RowArgs &a, int j, float *__restr
         if (shrink) {
 #pragma unroll
             for (int q = 0; q < GRP; ++q) {
-                const int ai = gi * GRP + q;
+                const int ai = acc0 + gi * GRP + q;
                 av[b][q] = *(const uint4 *)((ai < a.r ? pA0 + (size_t)ai * K : pA1 + (size_t)(ai - a.r) * K) + c * 8);
             }
         }
@@ -238,10 +251,10 @@ __device__ __forceinline__ void row_body(const RowArgs &a, int j, float *__restr
         }
         __syncthreads();
     }
-    const int mr = a.M * a.r;
+    // the row of T: entry (target t, model jj, i) belongs to the part that holds accumulator t * r + i
     for (int c = tid; c < a.ldt; c += kRowThreads) {
-        int t = c / mr, jj = (c % mr) / a.r, i = c % a.r;
-        a.T[(size_t)row * a.ldt + c] = f32_to_bf16(shrink && jj == j ? res[t * a.r + i] : 0.f);
+        const int t = c / mr, jj = (c % mr) / a.r, i = c % a.r, ai = t * a.r + i - acc0;
+        if (ai >= 0 && ai < NA) a.T[(size_t)row * a.ldt + c] = f32_to_bf16(shrink && jj == j ? res[ai] : 0.f);
     }
 }
 
@@ -256,9 +269,15 @@ __global__ void __launch_bounds__(kRowThreads, NACC == 64 ? 2 : 4) k_row(RowArgs
     else row_body<SRC, NORM, NACC, false>(a, j, red, part, res);
 }
 
+// nacc: the row's accumulators (targets * r).  With few rows they are split over several workgroups per row
+// (each computes 8 or more of them against its share of the adapter rows and forms the row for itself), so
+// that a handful of rows still spreads over the chip and a thread's chain of dependent load groups gets shorter.
 template <int SRC, bool NORM>
 hipError_t launch_row(int nacc, int R, hipStream_t st, const RowArgs &a) {
-#define ICARUS_ROW(N) hipLaunchKernelGGL((k_row<SRC, NORM, N>), dim3(R), dim3(kRowThreads), 0, st, a)
+    int parts = 1;
+    while (nacc / (2 * parts) >= 8 && R * 2 * parts <= kRowMaxWorkgroups) parts *= 2;
+    nacc /= parts;
+#define ICARUS_ROW(N) hipLaunchKernelGGL((k_row<SRC, NORM, N>), dim3(R, parts), dim3(kRowThreads), 0, st, a)
     switch (nacc) {
     case 0: ICARUS_ROW(0); break;
     case 8: ICARUS_ROW(8); break;
