@@ -190,17 +190,21 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
     bool enc = row_model[row] < 0;
     int half = D >> 1;
     int n_rot = Hq + (enc ? Hkv : 0), n_heads = Hq + (enc ? 2 * Hkv : 0);
+    // With few rows a row's heads are split over gridDim.y workgroups: this one takes heads [h0, h1) of the
+    // row's q heads and, on an encoder row, its k and v heads (numbered Hq .. Hq + 2 Hkv - 1).
+    const int h0 = (int)((long long)n_heads * blockIdx.y / gridDim.y), h1 = (int)((long long)n_heads * (blockIdx.y + 1) / gridDim.y);
+    const int r1 = min(h1, n_rot);  // end of this part's rotated heads
     int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     float *xr = sm, *cs_t = sm + (size_t)(Hq + 2 * Hkv) * D, *sn_t = cs_t + half, *inv = sn_t + half;
     const bool vec_ok = D % 4 == 0 && ldq % 4 == 0 && slice % 4 == 0;
     if (!vec_ok)
-        for (int i = threadIdx.x; i < n_heads * D; i += 256) {
+        for (int i = h0 * D + threadIdx.x; i < h1 * D; i += 256) {
             float v = src[i];
             for (int z = 1; z < splits; ++z) v += src[z * slice + i];
             xr[i] = v;
         }
     // rows and slices 16-byte aligned: 16-byte loads, four slices in flight
-    for (int i = threadIdx.x * 4; vec_ok && i < n_heads * D; i += 1024) {
+    for (int i = h0 * D + threadIdx.x * 4; vec_ok && i < h1 * D; i += 1024) {
         float4 v = *(const float4 *)(src + i);
         int z = 1;
         for (; z + 3 < splits; z += 4) {
@@ -226,7 +230,7 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
     }
     __syncthreads();
     if (qk_norm) {
-        for (int h = w; h < n_rot; h += 4) {
+        for (int h = h0 + w; h < r1; h += 4) {
             float ss = 0.f;
             for (int i = lane; i < D; i += 64) { float v = xr[(size_t)h * D + i]; ss += v * v; }
             ss = wave_sum(ss);
@@ -243,9 +247,9 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
         slot = (int64_t)blk * Bk + off;
         kdst = pool + (size_t)blk * Hkv * 2 * Bk * D;
         vdst = kdst;
-        if (threadIdx.x == 0 && slot_out) slot_out[slot_by_row ? row : s] = slot;
+        if (threadIdx.x == 0 && blockIdx.y == 0 && slot_out) slot_out[slot_by_row ? row : s] = slot;
     }
-    for (int idx = threadIdx.x; idx < n_rot * half; idx += 256) {
+    for (int idx = h0 * half + threadIdx.x; idx < r1 * half; idx += 256) {
         int h = idx / half, i = idx % half;
         float cs = cs_t[i], sn = sn_t[i];
         float a = xr[(size_t)h * D + i], b = xr[(size_t)h * D + i + half];
@@ -267,7 +271,8 @@ __global__ void __launch_bounds__(256) k_rope_append(const float *__restrict__ q
     }
     if (enc) {
         const float *vsrc = xr + (size_t)(Hq + Hkv) * D;
-        for (int idx = threadIdx.x; idx < Hkv * D; idx += 256) {
+        const int v0 = max(h0 - (Hq + Hkv), 0), v1 = h1 - (Hq + Hkv);  // this part's v heads
+        for (int idx = v0 * D + threadIdx.x; idx < v1 * D; idx += 256) {
             int h = idx / D, i = idx % D;
             KT *dst = vdst + ((size_t)h * 2 + 1) * Bk * D;  // V plane [D][Bk]
             KVElem<KT>::st(dst + (size_t)i * Bk + off, vsrc[idx], v_scale);
@@ -282,6 +287,9 @@ hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, int spl
     size_t shm = sizeof(float) * ((size_t)(dm.Hq + 2 * dm.Hkv) * dm.D + dm.D + dm.Hq + dm.Hkv);
     double l2t = log2(dm.theta);
     if (shm > 160 * 1024) return hipErrorInvalidValue;
+    // few rows: several workgroups per row, each with four heads or more
+    int parts = 1;
+    while (parts < 8 && R * 2 * parts <= 512 && dm.Hq / (2 * parts) >= 4) parts *= 2;
     DISPATCH_TK(dm.bf16, dm.kv8, {
         if (shm > 64 * 1024) {
             static bool attr_set = false;  // per instantiation
@@ -291,7 +299,7 @@ hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, int spl
                 attr_set = true;
             }
         }
-        hipLaunchKernelGGL((k_rope_append<T, KT>), dim3(R), dim3(256), shm, st, qkv, ldq, splits, slice, rm.row_seq, rm.row_model,
+        hipLaunchKernelGGL((k_rope_append<T, KT>), dim3(R, parts), dim3(256), shm, st, qkv, ldq, splits, slice, rm.row_seq, rm.row_model,
                            rm.row_pos, bt, max_blocks, (KT *)pool, (T *)q_out, slot_out, slot_by_row, (const T *)q_norm,
                            (const T *)k_norm, dm.Hq, dm.Hkv, dm.D, dm.Bk, l2t, dm.eps, dm.qk_norm, dm.k_scale, dm.v_scale, row_map);
     });
