@@ -289,7 +289,7 @@ hipError_t launch_rope_append(const Dims &dm, const float *qkv, int ldq, int spl
     if (shm > 160 * 1024) return hipErrorInvalidValue;
     // few rows: several workgroups per row, each with four heads or more
     int parts = 1;
-    while (parts < 8 && R * 2 * parts <= 512 && dm.Hq / (2 * parts) >= 4) parts *= 2;
+    while (parts < 8 && R * 2 * parts <= 1024 && dm.Hq / (2 * parts) >= 4) parts *= 2;
     DISPATCH_TK(dm.bf16, dm.kv8, {
         if (shm > 64 * 1024) {
             static bool attr_set = false;  // per instantiation
