@@ -150,19 +150,35 @@ __device__ __forceinline__ void row_body(const RowArgs &a, int j, float *__restr
                 const int h = c / kHeadChunks, d0 = (c % kHeadChunks) * 8;
                 const size_t pj0 = ((size_t)p0 * a.Hkv + h / g) * a.g_max + jq0 + h % g;
                 const size_t pstep = (size_t)a.Hkv * a.g_max;  // between consecutive pieces
+                // four pieces' loads in flight at a time (a piece past the last repeats it with weight zero)
                 float mx = -INFINITY;
-                for (int p = 0; p < np; ++p) mx = fmaxf(mx, a.part_ml[(pj0 + p * pstep) * 2]);
+                for (int p = 0; p < np; p += 4) {
+                    float m4[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) m4[u] = a.part_ml[(pj0 + min(p + u, np - 1) * pstep) * 2];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) mx = fmaxf(mx, m4[u]);
+                }
                 float den = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) f[e] = 0.f;
-                for (int p = 0; p < np; ++p) {
-                    const size_t pj = pj0 + p * pstep;
-                    const float wgt = __builtin_amdgcn_exp2f(a.part_ml[pj * 2] - mx);
-                    den += wgt * a.part_ml[pj * 2 + 1];
-                    const float4 v0 = *(const float4 *)(a.part_o + pj * (kHeadChunks * 8) + d0);
-                    const float4 v1 = *(const float4 *)(a.part_o + pj * (kHeadChunks * 8) + d0 + 4);
-                    f[0] += wgt * v0.x; f[1] += wgt * v0.y; f[2] += wgt * v0.z; f[3] += wgt * v0.w;
-                    f[4] += wgt * v1.x; f[5] += wgt * v1.y; f[6] += wgt * v1.z; f[7] += wgt * v1.w;
+                for (int p = 0; p < np; p += 4) {
+                    float2 ml[4];
+                    float4 v0[4], v1[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const size_t pj = pj0 + min(p + u, np - 1) * pstep;
+                        ml[u] = *(const float2 *)(a.part_ml + pj * 2);
+                        v0[u] = *(const float4 *)(a.part_o + pj * (kHeadChunks * 8) + d0);
+                        v1[u] = *(const float4 *)(a.part_o + pj * (kHeadChunks * 8) + d0 + 4);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {  // in piece order, as a loop over single pieces would add them
+                        const float wgt = p + u < np ? __builtin_amdgcn_exp2f(ml[u].x - mx) : 0.f;
+                        den += wgt * ml[u].y;
+                        f[0] += wgt * v0[u].x; f[1] += wgt * v0[u].y; f[2] += wgt * v0[u].z; f[3] += wgt * v0[u].w;
+                        f[4] += wgt * v1[u].x; f[5] += wgt * v1[u].y; f[6] += wgt * v1[u].z; f[7] += wgt * v1[u].w;
+                    }
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) f[e] = f[e] / den;
