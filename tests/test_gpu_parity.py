@@ -107,11 +107,12 @@ def test_decode_ragged_batch(shape, mode):
     _check_decode(shape, ctx, n_active, seed=11, mode=mode)
 
 
-@pytest.mark.parametrize("rows", [100, 230, 300])
+@pytest.mark.parametrize("rows", [100, 129, 230, 300, 385])
 def test_decode_row_counts_of_every_gemm_tile(rows):
     # The GEMM launcher picks its tile from the stacked row count: up to 64, up to 128, 193-256 (fused gate/up),
-    # up to 384.  The other cases of this file stay below 64 rows; these reach the other tiles, each with a
-    # ragged last row tile.
+    # up to 384, more.  The other cases of this file stay below 64 rows; these reach the other tiles, each with a
+    # ragged last row tile, and the first row count past a boundary (129, 385).  More than 256 rows also take the
+    # row and RoPE kernels with one workgroup per row instead of several.
     _say("case: decode with", rows, "stacked rows")
     shape = synth.LLAMA_SMALL
     S = rows // 5
