@@ -40,6 +40,17 @@ def filled_batch(shape, batch, seed=0):
     return pool
 
 
+def mark_unwritten(shape, batch, pool, value) -> None:
+    """Set every slot of the pool that no sequence of the batch has written to `value` (by position, not by
+    content: a written entry that happens to be exactly 0 stays as it is)."""
+    written = np.zeros(pool.shape, dtype=bool)
+    for s in range(batch.S):
+        n = int(batch.ctx_lens[s])
+        one = np.ones((n, shape.n_kv_heads, shape.head_dim), dtype=bool)
+        fill_pool(written, batch.block_tables[s], one, one)
+    pool[~written] = value
+
+
 # Cache gate, bf16 storage: |got - want| <= one bf16 ulp of the oracle's value (the entry's own rounding) +
 # CACHE_SLACK_BF16 * rms of the written entries.  The slack is 1.5 x the worst deviation that rounding the normed
 # row to bf16 (what the matrix cores are fed) causes over 10^6 entries: 8.07e-3 rms, sigma 1.66e-3 rms

@@ -9,7 +9,7 @@ import torch
 
 import oracle
 from paper_2603_13281_amd import synth
-from helpers import assert_cache_close, assert_close, fill_pool, filled_batch, oracle_config, read_pool
+from helpers import assert_cache_close, assert_close, fill_pool, filled_batch, mark_unwritten, oracle_config, read_pool
 from gpu_util import bf16_ulp, dev, host, make_layer, pool_from_device_layout, pool_to_device_layout
 
 pytestmark = pytest.mark.gpu
@@ -316,7 +316,7 @@ def test_attn_mfma_tiles_splits_and_tails(g, rows, chunk):
     rows_per_seq = [rows if i % 3 else max(1, rows - 1) for i in range(len(lens))]
     batch = synth.make_batch(shape, lens, [0] * len(lens), seed=8, headroom=0)
     pool = filled_batch(shape, batch, seed=8)
-    pool[pool == 0] = np.nan          # unwritten slots hold NaN: masked positions must not leak
+    mark_unwritten(shape, batch, pool, np.nan)   # unwritten slots hold NaN: masked positions must not leak
     row_seq = np.repeat(np.arange(len(lens)), rows_per_seq).astype(np.int32)
     R = len(row_seq)
     rng = np.random.default_rng(9)
@@ -341,7 +341,7 @@ def test_prefill_causal_groups_and_boundaries(shape):
     base = synth.make_base(shape, seed=13, norm_ones=False)
     batch = synth.make_batch(shape, pre, [0] * len(pre), seed=13, headroom=140)
     pool = filled_batch(shape, batch, seed=13)
-    pool[pool == 0] = np.nan                      # never-written slots hold NaN: masked positions must not leak
+    mark_unwritten(shape, batch, pool, np.nan)    # never-written slots hold NaN: masked positions must not leak
     x = synth.make_hidden(shape, sum(chunk), seed=13, tag=5)
     orc = oracle.Oracle(oracle_config(shape, batch.num_blocks), base, None)
     want_pool = pool.copy()

@@ -14,12 +14,12 @@ pytestmark = pytest.mark.gpu
 def _case(shape, lens, rows_per_seq, seed, limit):
     import oracle
     from gpu_util import dev, host, make_layer, pool_to_device_layout
-    from helpers import assert_close, filled_batch, oracle_config
+    from helpers import assert_close, filled_batch, mark_unwritten, oracle_config
     from paper_2603_13281_amd import synth
     print("case: static attention", shape.name, "lens", lens, "rows", rows_per_seq, "piece limit", limit, flush=True)
     batch = synth.make_batch(shape, lens, [0] * len(lens), seed=seed, headroom=0)
     pool = filled_batch(shape, batch, seed=seed)
-    pool[pool == 0] = np.nan                                     # unwritten slots must not leak
+    mark_unwritten(shape, batch, pool, np.nan)                   # unwritten slots must not leak
     row_seq = np.repeat(np.arange(len(lens)), rows_per_seq).astype(np.int32)
     q = synth.to_storage(np.random.default_rng(seed).standard_normal((len(row_seq), shape.n_q_heads, shape.head_dim)).astype(np.float32),
                          shape.bf16)
