@@ -89,3 +89,39 @@ def test_drawn_attention_call(case):
                                lens, row_seq)
     torch.cuda.synchronize()
     assert_close(host(got), want, 2e-2, "attention out")
+
+
+@pytest.mark.parametrize("case", range(6))
+def test_drawn_fp8_attention_call(case):
+    """The same over an FP8 pool of drawn codes (g = 8): the oracle reads the values the codes stand for."""
+    import dataclasses
+    from gpu_util import fp8_pool_to_float, pool_from_device_layout
+    rng = _rng(300 + case)
+    shape = synth.QWEN_SMALL
+    ks, vs = 0.02, 0.013
+    most = (10, 7, 3)[case % 3]                     # 5, 4 and 2 query tiles
+    S = int(rng.integers(1, 7))
+    lens = np.int32([max(1, int(x)) for x in rng.choice(LENS, size=S)])
+    rows = [int(rng.integers(1, most + 1)) for _ in range(S)]
+    rows[int(rng.integers(S))] = most
+    limit = int(rng.choice([0, 128, 512]))
+    print(f"case: drawn fp8 attention {case}: lens {lens.tolist()} rows {rows} piece limit {limit}", flush=True)
+    seed = 600 + case
+    base = synth.make_base(shape, seed=seed)
+    batch = synth.make_batch(shape, lens, np.zeros(S, np.int32), seed=seed, headroom=1)
+    layer = make_layer(shape, base, None, batch.num_blocks, kv_fp8=True, k_scale=ks, v_scale=vs)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(seed)
+    codes = torch.randint(0, 256, layer.cfg.pool_shape(), generator=gen, device="cuda:0", dtype=torch.uint8)
+    codes[(codes & 0x7f) == 0x7f] = 0x38            # no NaN codes inside the contexts
+    codes[(codes & 0x78) == 0x78] &= 0xbf           # |code value| < 32: scores stay in a sane range
+    row_seq = np.repeat(np.arange(S, dtype=np.int32), rows)
+    qh = synth.to_storage((rng.standard_normal((len(row_seq), shape.n_q_heads, shape.head_dim)) * 0.3).astype(np.float32), True)
+    opool = pool_from_device_layout(fp8_pool_to_float(codes, ks, vs), shape.block_size, shape.head_dim)
+    orc = oracle.Oracle(dataclasses.replace(oracle_config(shape, batch.num_blocks), kv_fp8=True, k_scale=ks, v_scale=vs), base, None)
+    want = orc.attn_shared_kv(qh, opool, batch.block_tables, lens, row_seq)
+    layer.set_attn_piece_limit(limit)
+    got = layer.attn_shared_kv(dev(qh.reshape(len(row_seq), -1), True), codes, torch.from_numpy(batch.block_tables).cuda(), lens, row_seq)
+    torch.cuda.synchronize()
+    assert_close(host(got).reshape(want.shape), want, 2e-2, "fp8 attention out")
+    layer.close()
