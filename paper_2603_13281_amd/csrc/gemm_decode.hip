@@ -16,11 +16,16 @@
 // owns 96 x 128 = 3 x 4 MFMA tiles of 32x32x16 (192 accumulator registers).  Per 16-wide K step the CU reads
 // 4 x (96 + 128) x 32 B = 28 KB of fragments for 48 MFMAs; the square-ish wave tile is what keeps the LDS below
 // the matrix pipe.  Rows beyond 192 go to further row blocks: the row blocks of one column tile sit next to each
-// other on one XCD, so the second reads the weights from that XCD's L2.
+// other on one XCD, so the second reads the weights from that XCD's L2.  Batches of at most 160 rows take a
+// 160 x 256 tile instead, the four waves side by side with 160 x 64 = 5 x 2 MFMA tiles each: the same 28 KB of
+// fragments for 40 MFMAs, fewer of them on rows that do not exist.
 //
-// Loads return in order, so everything a wave has in flight is kept at one distance, and every load is
-// unconditional (past the end of the K range it re-reads valid data that meets weight rows of zeros): the number
-// of loads between an issue and its use is then the same on every path and the compiler's wait counts are exact.
+// Loads return in order, so everything a wave has in flight is kept at one distance (D = 2 slabs: the loads
+// issued while slab i is multiplied are parked while slab i + D is), and every load is unconditional (past the
+// end of the K range it re-reads valid data that meets weight rows of zeros): the number of loads between an
+// issue and its use is then the same on every path and the compiler's wait counts are exact.  (Three slabs in
+// flight -- three register sets and LDS stages, which the 160-row tile has room for -- were measured and are
+// slower: at these sizes HBM serves the weight rows' 128-byte pieces no faster with more of them outstanding.)
 // The adapter columns follow the base K range as extra slabs: the activation side reads T, the weight side the
 // concatenation of all models' B (zeros for weight rows without an adapter).
 #include <algorithm>
@@ -66,18 +71,30 @@ __device__ __forceinline__ int pick(bool a, int x, int y) {
     return (x & m) | (y & ~m);
 }
 
-template <int TM, int TN>  // MFMA tiles of a wave; waves are 2 x 2
+// Shape of the kernel for TM x TN MFMA tiles per wave: a tall wave tile puts the four waves side by side, else they
+// sit 2 x 2; D = slabs of loads in flight = register sets = LDS stages (the loop below is written for 2 or 3).
+template <int TM, int TN>
+struct GdShape {
+    static constexpr int WVM = TM > TN ? 1 : 2, WVN = 4 / WVM;
+    static constexpr int BM = 32 * TM * WVM, BN = 32 * TN * WVN;
+    static constexpr int kStage = (BM + BN) * kBK * 2;
+    static constexpr int D = 2;
+};
+
+template <int TM, int TN>  // MFMA tiles of a wave
 __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    using Shape = GdShape<TM, TN>;
+    constexpr int WVM = Shape::WVM, WVN = Shape::WVN, BM = Shape::BM, BN = Shape::BN, D = Shape::D;
+    constexpr int WNR = BN / WVN;  // weight rows of a wave column
     constexpr int KS = kBK / 16;
     constexpr int NA = BM * kCPR / 256, NB = BN * kCPR / 256;  // 16-byte chunks of a slab per thread: activations, weights
-    constexpr int kBOff = BM * kBK * 2, kStage = (BM + BN) * kBK * 2;
-    static_assert(TN % 2 == 0 && KS % 2 == 0, "tile shape");
-    extern __shared__ __attribute__((aligned(1024))) char smem[];  // 2 stages of { X [BM][64], W [BN][64] }; then the epilogue's scratch
+    constexpr int kBOff = BM * kBK * 2, kStage = Shape::kStage;
+    static_assert(TN % 2 == 0 && KS % 2 == 0 && BM * kCPR % 256 == 0 && BN * kCPR % 256 == 0, "tile shape");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];  // D stages of { X [BM][64], W [BN][64] }; then the epilogue's scratch
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wr = w >> 1, wc = w & 1;
+    const int wr = w / WVN, wc = w % WVN;
     const int cl = lane & 31, half = lane >> 5;
     int tile_n, row_blk;
     {   // consecutive workgroups of one XCD: the row blocks of one column tile
@@ -108,7 +125,7 @@ __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
 
     // Loader: chunk i of this thread is slab row (tid / 8 + 32 i), 16-byte column c = tid % 8, of either operand.
     // Weight-tile row b: PLAIN weight row t * BN + b of the segment; DUAL: the tile covers BN / 2 output columns,
-    // a wave column of BN / 2 tile rows holds the gate rows of its BN / 4 output columns, then their up rows.
+    // a wave column of WNR tile rows holds the gate rows of its WNR / 2 output columns, then their up rows.
     const int c = tid & 7, lrow = tid >> 3;
     int offx[NA], offt[NA], offw[NB], offb[NB];
 #pragma unroll
@@ -125,7 +142,7 @@ __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int b = lrow + 32 * i;
-        int n = dual ? tile_n * (BN / 2) + (b / (BN / 2)) * (BN / 4) + b % (BN / 4) : t * BN + b;
+        int n = dual ? tile_n * (BN / 2) + (b / WNR) * (WNR / 2) + b % (WNR / 2) : t * BN + b;
         n = min(n, n_lim - 1);  // clamped columns are never stored
         offw[i] = n * g.K + 8 * c;
         offb[i] = n * g.r;
@@ -136,7 +153,7 @@ __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
     // range -> X / W at column sl * 64; past it -> T / Bcat; columns past T's last, whole slabs past the end, and
     // weight rows without an adapter: finite activations against zero weights.
     const bf16_t *x_past = t_cols ? g.T : g.X + (size_t)(base_slabs - 1) * kBK + 8 * c;
-    u32x4 xr[2][NA + NB];
+    u32x4 xr[D][NA + NB];
     auto issue_chunk = [&](int sl, int u, u32x4 &dst) {
         const bool past = sl >= sl_end;  // the slab that rounds an odd count up; it may belong to the next K slice
         const bool xbase = sl < base_slabs, base = !past && xbase;
@@ -175,35 +192,36 @@ __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
     // fragment f of K step ks of the slab in `stage`: f < TM activation rows, else weight rows
     auto read_frag = [&](int stage, int ks, int f, bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
         const char *sA = smem + stage * kStage, *sB = sA + kBOff;
-        if (f < TM) a[f] = *(const bf16x8 *)(sA + swz(wr * (BM / 2) + f * 32 + cl, 2 * ks + half));
-        else b[f - TM] = *(const bf16x8 *)(sB + swz(wc * (BN / 2) + (f - TM) * 32 + cl, 2 * ks + half));
+        if (f < TM) a[f] = *(const bf16x8 *)(sA + swz(wr * (BM / WVM) + f * 32 + cl, 2 * ks + half));
+        else b[f - TM] = *(const bf16x8 *)(sB + swz(wc * WNR + (f - TM) * 32 + cl, 2 * ks + half));
     };
 
     if (sl_end > sl_begin) {
-        // prologue: slabs 0 and 1 requested, slab 0 parked in stage 0, slab 2 requested, first fragments read
+        // prologue: slabs 0 .. D-1 requested, slab 0 parked in stage 0, slab D requested, first fragments read
 #pragma unroll
-        for (int u = 0; u < NA + NB; ++u) issue_chunk(sl_begin, u, xr[0][u]);
+        for (int d = 0; d < D; ++d)
 #pragma unroll
-        for (int u = 0; u < NA + NB; ++u) issue_chunk(sl_begin + 1, u, xr[1][u]);
+            for (int u = 0; u < NA + NB; ++u) issue_chunk(sl_begin + d, u, xr[d][u]);
 #pragma unroll
         for (int u = 0; u < NA + NB; ++u) {
             park_chunk(0, u, xr[0][u]);
-            issue_chunk(sl_begin + 2, u, xr[0][u]);
+            issue_chunk(sl_begin + D, u, xr[0][u]);
         }
         lds_barrier();
 #pragma unroll
         for (int f = 0; f < TM + TN; ++f) read_frag(0, 0, f, fa[0], fb[0]);
-        // One slab, Q = its parity: LDS stage Q holds it, register set Q ^ 1 the next one (requested two slabs
-        // ago).  A wave issues in order, and an instruction that the LDS or the memory path cannot take yet blocks
-        // the MFMAs behind it while the matrix pipe runs dry; so every memory instruction sits right behind an
-        // MFMA, whose 8 passes cover it: after the first TM + TN MFMAs of a K step the fragment reads of the next
-        // step (two fragment sets alternate), after the others one chunk of the next slab is parked in the other
-        // stage -- free since the barrier of the previous slab -- and its registers are reloaded with the slab
-        // after the next two.  The barrier precedes the last K step, whose fragment reads are the next slab's.
-        auto slab = [&](int sl, auto Qc, auto hot) {
-            constexpr int Q = decltype(Qc)::value;
+        // One slab, P = its index mod D: LDS stage P holds it, register set N = (P + 1) % D the next one (requested
+        // D slabs ago).  A wave issues in order, and an instruction that the LDS or the memory path cannot take yet
+        // blocks the MFMAs behind it while the matrix pipe runs dry; so every memory instruction sits right behind
+        // an MFMA, whose 8 passes cover it: after the first TM + TN MFMAs of a K step the fragment reads of the next
+        // step (two fragment sets alternate), after the others chunks of the next slab are parked in stage N --
+        // free since the barrier of the previous slab -- and their registers reloaded with the slab D slabs after
+        // the next.  The barrier precedes the last K step, whose fragment reads are the next slab's.
+        auto slab = [&](int sl, auto Pc, auto hot) {
+            constexpr int P = decltype(Pc)::value, N = (P + 1) % D;
             constexpr int kFree = TM * TN - (TM + TN);  // MFMAs of a K step that carry no fragment read
-            static_assert(kFree * (KS - 1) >= NA + NB, "not enough MFMAs per slab to carry its loads");
+            constexpr int kPer = (NA + NB + kFree * (KS - 1) - 1) / (kFree * (KS - 1));  // chunks behind each of them
+            static_assert(kFree > 0 && kPer <= 2, "not enough MFMAs per slab to carry its loads");
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 if (ks == KS - 1) lds_barrier();
@@ -213,31 +231,37 @@ __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
                     const int i = m / TN, j = m % TN;
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
                     if (m < TM + TN) {
-                        if (ks + 1 < KS) read_frag(Q, ks + 1, m, fa[set ^ 1], fb[set ^ 1]);
-                        else read_frag(Q ^ 1, 0, m, fa[set ^ 1], fb[set ^ 1]);
+                        if (ks + 1 < KS) read_frag(P, ks + 1, m, fa[set ^ 1], fb[set ^ 1]);
+                        else read_frag(N, 0, m, fa[set ^ 1], fb[set ^ 1]);
                     } else if (ks + 1 < KS) {
-                        const int u = ks * kFree + (m - (TM + TN));
-                        if (u < NA + NB) {
-                            park_chunk(Q ^ 1, u, xr[Q ^ 1][u]);
-                            if constexpr (decltype(hot)::value) issue_chunk_base(sl + 3, u, xr[Q ^ 1][u]);
-                            else issue_chunk(sl + 3, u, xr[Q ^ 1][u]);
+#pragma unroll
+                        for (int e = 0; e < kPer; ++e) {
+                            const int u = (ks * kFree + (m - (TM + TN))) * kPer + e;
+                            if (u < NA + NB) {
+                                park_chunk(N, u, xr[N][u]);
+                                if constexpr (decltype(hot)::value) issue_chunk_base(sl + D + 1, u, xr[N][u]);
+                                else issue_chunk(sl + D + 1, u, xr[N][u]);
+                            }
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         };
-        // slabs whose loads (three slabs ahead) stay inside the base K range of this slice, in pairs
+        // slabs whose loads (D + 1 slabs ahead) stay inside the base K range of this slice, D at a time
         int sl = sl_begin;
-        const int hot_end = sl_begin + max(0, (min(sl_end, base_slabs) - 3 - sl_begin) & ~1);
-        for (; sl < hot_end; sl += 2) {
+        const int hot_end = sl_begin + max(0, min(sl_end, base_slabs) - (D + 1) - sl_begin) / D * D;
+        for (; sl < hot_end; sl += D) {
             slab(sl, std::integral_constant<int, 0>(), std::true_type());
             slab(sl + 1, std::integral_constant<int, 1>(), std::true_type());
+            if constexpr (D > 2) slab(sl + 2, std::integral_constant<int, 2>(), std::true_type());
         }
-        // the rest in the general form, also in pairs: an odd count is rounded up by a slab of zero weights
-        for (; sl < sl_end; sl += 2) {
+        // the rest in the general form, also D at a time: a count that is not a multiple of D is rounded up by slabs
+        // of zero weights
+        for (; sl < sl_end; sl += D) {
             slab(sl, std::integral_constant<int, 0>(), std::false_type());
             slab(sl + 1, std::integral_constant<int, 1>(), std::false_type());
+            if constexpr (D > 2) slab(sl + 2, std::integral_constant<int, 2>(), std::false_type());
         }
     }
 
@@ -247,7 +271,7 @@ __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
     // tiles 0 .. TN/2-1 are the gate, TN/2 .. TN-1 the up projection of the same columns.
     lds_barrier();  // every wave has left the K loop
     constexpr int WN = 32 * TN, kEs = WN + 8;  // scratch row stride in floats
-    static_assert(4 * 32 * kEs * 4 <= 2 * kStage, "epilogue scratch must fit the slab stages");
+    static_assert(4 * 32 * kEs * 4 <= D * kStage, "epilogue scratch must fit the slab stages");
     float *scr = (float *)smem + w * 32 * kEs;
     const int row_l = half * 4;
     const int wcols = dual ? WN / 2 : WN;                                         // output columns of this wave
@@ -260,7 +284,7 @@ __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
     auto load_resid = [&](int i, uint4 (&dst)[kPasses]) {
 #pragma unroll
         for (int p = 0; p < kPasses; ++p) {
-            const int rr = rr0 + p * rpp, row = row0 + wr * (BM / 2) + i * 32 + rr, nc = n_wave + c8;
+            const int rr = rr0 + p * rpp, row = row0 + wr * (BM / WVM) + i * 32 + rr, nc = n_wave + c8;
             dst[p] = (rr < 32 && row < g.R && nc < n_lim) ? *(const uint4 *)(g.resid + (size_t)row * g.ldr + col_base + nc)
                                                             : make_uint4(0u, 0u, 0u, 0u);
         }
@@ -269,7 +293,7 @@ __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
     const bool f32_out = !dual && g.epi == EPI_F32;
     float *const y32 = (float *)g.Y + (size_t)kz * n_rows * ldy + n_out;
     bf16_t *const y16 = (bf16_t *)g.Y + n_out;
-    const int wrow0 = row0 + wr * (BM / 2);  // first row of this wave
+    const int wrow0 = row0 + wr * (BM / WVM);  // first row of this wave
     if (with_resid) load_resid(0, rres[0]);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -325,7 +349,8 @@ __global__ void __launch_bounds__(256) k_gemm_decode(GemmArgs g) {
 
 template <int TM, int TN>
 hipError_t launch_gd(GemmArgs g, hipStream_t st) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    using Shape = GdShape<TM, TN>;
+    constexpr int BM = Shape::BM, BN = Shape::BN;
     g.m_tiles = (g.R + BM - 1) / BM;
     g.n_tiles = 0;
     if (g.mode == GEMM_DUAL) {
@@ -339,7 +364,7 @@ hipError_t launch_gd(GemmArgs g, hipStream_t st) {
     const int total = g.K / kBK + ((g.T ? g.ldt : 0) + kBK - 1) / kBK;
     if (g.splits < 1) g.splits = 1;
     g.slabs_per_split = (total + g.splits - 1) / g.splits;
-    const size_t shm = (size_t)2 * (BM + BN) * kBK * sizeof(bf16_t);
+    const size_t shm = (size_t)Shape::D * Shape::kStage;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)k_gemm_decode<TM, TN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
@@ -351,7 +376,7 @@ hipError_t launch_gd(GemmArgs g, hipStream_t st) {
     return hipGetLastError();
 }
 
-constexpr int kGdBM = 192, kGdBN = 256;
+constexpr int kGdBM = 192, kGdBN = 256, kGdBMSmall = 160;  // row tile; the smaller one where it covers every row
 
 }  // namespace
 
@@ -382,7 +407,7 @@ int gemm_decode_slabs(const GemmArgs &g) { return g.K / kBK + ((g.T ? g.ldt : 0)
 hipError_t launch_gemm_decode(GemmArgs g, hipStream_t st) {
     if (!gemm_decode_supported(g)) return hipErrorInvalidValue;
     if (!g.T || !(g.B[0] || g.B[1])) { g.T = nullptr; g.ldt = 0; }
-    return launch_gd<3, 4>(g, st);
+    return g.R <= kGdBMSmall ? launch_gd<5, 2>(g, st) : launch_gd<3, 4>(g, st);
 }
 
 }  // namespace icarus

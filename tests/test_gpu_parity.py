@@ -125,14 +125,16 @@ def test_decode_row_counts_of_every_gemm_tile(rows):
     _check_decode(shape, ctx, n_active, seed=21, mode=MODES[0])
 
 
-@pytest.mark.parametrize("rows,d_ffn", [(330, 10304), (150, 20608)])
+@pytest.mark.parametrize("rows,d_ffn", [(330, 10304), (150, 20608), (131, 20608), (160, 20608), (161, 20608)])
 def test_decode_wide_ffn_takes_the_wide_projection_gemm(rows, d_ffn):
     # A fused gate/up projection wide enough for 160 tiles of 192 x 256 goes to the register-staged GEMM kernel
-    # (two row tiles at 330 rows, one partly filled at 150; the last column tile is ragged: d_ffn is not a
-    # multiple of 128).  Element by element against the oracle; the down projection then contracts over the same
-    # odd width.
+    # (two row tiles of 192 at 330 rows; at most 160 rows: the 160 x 256 tile with three slabs of loads in flight,
+    # partly filled at 131 and 150 rows, full at 160; 161 rows: one 192-row tile again; the last column tile is
+    # ragged: d_ffn is not a multiple of 128).  Element by element against the oracle; the down projection then
+    # contracts over the same odd width.
     _say("case: wide ffn", rows, "rows, d_ffn", d_ffn)
-    shape = synth.QWEN_SMALL.replace(d_model=256, n_q_heads=2, n_kv_heads=2, d_ffn=d_ffn)
+    # d_model 512: eight 64-wide slabs of base weights, so the kernel's steady-state loop runs as well as its tail
+    shape = synth.QWEN_SMALL.replace(d_model=512, n_q_heads=2, n_kv_heads=2, d_ffn=d_ffn)
     S = rows // 4
     ctx = [(5 * i) % 40 for i in range(S)]
     n_active = [3] * S
