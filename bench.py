@@ -60,7 +60,8 @@ def phase_model(wl, step):
 
 
 PROFILE_FILES = {"c3": "attn_decode_and_layer_step__config3.md", "c5": "attn_decode_and_layer_step__config5.md",
-                 "c2": "attn_decode_and_layer_step__config2.md", "c3-fp8": "attn_decode_and_layer_step__config3_fp8kv.md"}
+                 "c2": "attn_decode_and_layer_step__config2.md", "c3-fp8": "attn_decode_and_layer_step__config3_fp8kv.md",
+                 "c5-fp8": "attn_decode_and_layer_step__config5_fp8kv.md"}
 PHASE_KERNEL = {"attn": "k_attn_decode", "gemm_qkv": "k_gemm_mfma", "gemm_o": "k_gemm_mfma", "gemm_gateup": "k_gemm_mfma",
                 "gemm_down": "k_gemm_mfma"}
 

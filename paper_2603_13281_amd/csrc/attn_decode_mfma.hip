@@ -82,6 +82,13 @@ __device__ __forceinline__ void load_group(KVFrag &f, const bf16_t *__restrict__
 // where the two paths meet, keeps the copies inside the rare branch.
 #define ICARUS_IN_ACC(x) asm volatile("" : "+a"(x))
 
+// Where the decode walks keep the wave's Q fragments: in registers when the wave has two or three query tiles (a
+// wave issues in order and is alone on its SIMD, so a fragment read in front of the MFMAs that need it stalls it for
+// the read's whole latency, up to twelve times per group); with one tile they stay in LDS, which keeps that
+// instantiation at two workgroups per CU.
+template <int NT>
+constexpr bool kQInRegs = NT > 1;
+
 // Per-wave running state for NT query tiles.
 template <int NT>
 struct State {
@@ -91,15 +98,15 @@ struct State {
 };
 
 // One 32-token group: S^T, online softmax, PV, one 16-query tile at a time so that only one
-// tile's scores are live.  Uses the first N tiles of st.  qlds: Q fragments of those tiles in LDS
-// as [qt][ks][lane] (B operands).
+// tile's scores are live.  Uses the first N tiles of st.  Q fragments of those tiles (B operands): qr, in
+// registers, or qlds, in LDS as [qt][ks][lane] (see kQInRegs).
 // tail == false: all 32 tokens are valid for every query.
 // tail == true:  `left` tokens of the chunk remain from this group's first token on (for the row
 //   with the longest context); query tile qt of this lane may attend only to the first
 //   left - stag[qt] of them (stag: how many positions the lane's query row ends before the last
 //   row -- 0 at decode, the causal stagger of a prefill chunk).
 template <int NT, int N, bool tail>
-__device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf16x8 *__restrict__ qlds, int left,
+__device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf16x8 (&qr)[NT][kKS], const bf16x8 *__restrict__ qlds, int left,
                                               const int (&stag)[NT], float scale_log2, int lane) {
     const int q = lane >> 4;
     // token index inside the group of S^T element (tile t, register i) on this lane: tbase + 4t + i
@@ -119,7 +126,7 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < kKS; ++ks) {
-            bf16x8 qv = qlds[(qt * kKS + ks) * 64 + lane];
+            const bf16x8 qv = kQInRegs<NT> ? qr[qt][ks] : qlds[(qt * kKS + ks) * 64 + lane];
             s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k[0][ks], qv, s0, 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k[1][ks], qv, s1, 0, 0, 0);
         }
@@ -182,7 +189,7 @@ __device__ __forceinline__ void compute_group(State<NT> &st, KVFrag &f, const bf
 template <int NT, int N>
 __device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
                                           int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int first, int stride,
-                                          int c, int Hkv, const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
+                                          int c, int Hkv, const bf16x8 (&qr)[NT][kKS], const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
     const int n_grp = (n_tok + kGrp - 1) / kGrp;
     auto blk_of = [&](int grp, int which) {
         return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
@@ -195,15 +202,15 @@ __device__ __forceinline__ void wave_walk(State<NT> &st, const bf16_t *__restric
 #pragma nounroll
     for (int grp = first; grp < n_clean; grp += 2 * stride) {
         load_group(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
-        compute_group<NT, N, false>(st, f0, qlds, kGrp, stag, scale_log2, lane);
+        compute_group<NT, N, false>(st, f0, qr, qlds, kGrp, stag, scale_log2, lane);
         load_group(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
-        if (grp + stride < n_clean) compute_group<NT, N, false>(st, f1, qlds, kGrp, stag, scale_log2, lane);
+        if (grp + stride < n_clean) compute_group<NT, N, false>(st, f1, qr, qlds, kGrp, stag, scale_log2, lane);
     }
 #pragma nounroll
     for (int grp = n_clean; grp < n_grp; ++grp) {
         if (grp % stride != first) continue;
         load_group(f0, pool, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
-        compute_group<NT, N, true>(st, f0, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
+        compute_group<NT, N, true>(st, f0, qr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
     }
 }
 
@@ -251,7 +258,7 @@ __device__ __forceinline__ bf16x8 cvt8(uint32_t lo, uint32_t hi) {
 // k-step at a time and die at once), then the softmax of every tile, then PV with V^T codes converted
 // one d tile at a time.  scale_log2 includes the K scale; the V scale is applied when the piece ends.
 template <int NT, int N, bool tail>
-__device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, const bf16x8 *__restrict__ qlds, int left,
+__device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, const bf16x8 (&qr)[NT][kKS], const bf16x8 *__restrict__ qlds, int left,
                                                const int (&stag)[NT], float scale_log2, int lane) {
     const int q = lane >> 4;
     const int tbase = 16 * (q >> 1) + 8 * (q & 1);
@@ -269,7 +276,7 @@ __device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, c
         const bf16x8 a1 = (ks & 1) ? cvt8(r1.z, r1.w) : cvt8(r1.x, r1.y);
 #pragma unroll
         for (int qt = 0; qt < N; ++qt) {
-            bf16x8 qv = qlds[(qt * kKS + ks) * 64 + lane];
+            const bf16x8 qv = kQInRegs<NT> ? qr[qt][ks] : qlds[(qt * kKS + ks) * 64 + lane];
             s0[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qv, s0[qt], 0, 0, 0);
             s1[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qv, s1[qt], 0, 0, 0);
         }
@@ -335,7 +342,7 @@ __device__ __forceinline__ void compute_group8(State<NT> &st, const KVRaw8 &f, c
 template <int NT, int N>
 __device__ __forceinline__ void wave_walk8(State<NT> &st, const uint8_t *__restrict__ pool, const int *__restrict__ blds,
                                            int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int first, int stride,
-                                           int c, int Hkv, const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
+                                           int c, int Hkv, const bf16x8 (&qr)[NT][kKS], const bf16x8 *__restrict__ qlds, float scale_log2, int lane) {
     const int n_grp = (n_tok + kGrp - 1) / kGrp;
     auto blk_of = [&](int grp, int which) {
         return __builtin_amdgcn_readfirstlane(blds[min(grp * 2 + which, n_blk - 1)]);
@@ -345,15 +352,15 @@ __device__ __forceinline__ void wave_walk8(State<NT> &st, const uint8_t *__restr
 #pragma nounroll
     for (int grp = first; grp < n_clean; grp += 2 * stride) {  // unconditional loads, see wave_walk
         load_group8(f1, pool, blk_of(grp + stride, 0), blk_of(grp + stride, 1), c, Hkv, lane);
-        compute_group8<NT, N, false>(st, f0, qlds, kGrp, stag, scale_log2, lane);
+        compute_group8<NT, N, false>(st, f0, qr, qlds, kGrp, stag, scale_log2, lane);
         load_group8(f0, pool, blk_of(grp + 2 * stride, 0), blk_of(grp + 2 * stride, 1), c, Hkv, lane);
-        if (grp + stride < n_clean) compute_group8<NT, N, false>(st, f1, qlds, kGrp, stag, scale_log2, lane);
+        if (grp + stride < n_clean) compute_group8<NT, N, false>(st, f1, qr, qlds, kGrp, stag, scale_log2, lane);
     }
 #pragma nounroll
     for (int grp = n_clean; grp < n_grp; ++grp) {
         if (grp % stride != first) continue;
         load_group8(f0, pool, blk_of(grp, 0), blk_of(grp, 1), c, Hkv, lane);
-        compute_group8<NT, N, true>(st, f0, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
+        compute_group8<NT, N, true>(st, f0, qr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
     }
 }
 
@@ -367,7 +374,7 @@ __device__ __forceinline__ void wave_walk8(State<NT> &st, const uint8_t *__restr
 template <int NT, int N>
 __device__ __forceinline__ void shared_walk8(State<NT> &st, const uint8_t *__restrict__ pool8, const int *__restrict__ blds,
                                              int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int half, int c,
-                                             int Hkv, bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds,
+                                             int Hkv, bf16x8 *__restrict__ ring, const bf16x8 (&qr)[NT][kKS], const bf16x8 *__restrict__ qlds,
                                              float scale_log2, int lane) {
     const int n_grp = (n_tok + kGrp - 1) / kGrp;                       // groups, the masked ones included
     const int n_round = (n_grp + 3) / 4;                               // the same for every wave
@@ -404,9 +411,9 @@ __device__ __forceinline__ void shared_walk8(State<NT> &st, const uint8_t *__res
 #pragma unroll
                 for (int dt = 0; dt < kDT; ++dt) gfr.v[dt] = src[(2 * kKS + dt) * 64];
                 if (grp >= n_clean)
-                    compute_group<NT, N, true>(st, gfr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
+                    compute_group<NT, N, true>(st, gfr, qr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
                 else
-                    compute_group<NT, N, false>(st, gfr, qlds, kGrp, stag, scale_log2, lane);
+                    compute_group<NT, N, false>(st, gfr, qr, qlds, kGrp, stag, scale_log2, lane);
             }
         }
     }
@@ -432,7 +439,7 @@ __device__ __forceinline__ void dma16(const void *g, uint32_t lds_base) {
 template <int NT, int N>
 __device__ __forceinline__ void shared_walk_dma(State<NT> &st, const bf16_t *__restrict__ pool, const int *__restrict__ blds,
                                                 int n_blk, int n_tok, int n_clean, const int (&stag)[NT], int w, int half, int c,
-                                                int Hkv, bf16x8 *__restrict__ ring, const bf16x8 *__restrict__ qlds,
+                                                int Hkv, bf16x8 *__restrict__ ring, const bf16x8 (&qr)[NT][kKS], const bf16x8 *__restrict__ qlds,
                                                 float scale_log2, int lane) {
     constexpr int kStages = 4, kStageFrags = 2 * 16;  // fragments (1 KiB each) per stage
     static_assert(kRingBytes == (size_t)kStages * kStageFrags * 1024, "ring size");
@@ -479,9 +486,9 @@ __device__ __forceinline__ void shared_walk_dma(State<NT> &st, const bf16_t *__r
 #pragma unroll
             for (int dt = 0; dt < kDT; ++dt) gfr.v[dt] = src[(2 * kKS + dt) * 64];
             if (grp >= n_clean)
-                compute_group<NT, N, true>(st, gfr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
+                compute_group<NT, N, true>(st, gfr, qr, qlds, n_tok - grp * kGrp, stag, scale_log2, lane);
             else
-                compute_group<NT, N, false>(st, gfr, qlds, kGrp, stag, scale_log2, lane);
+                compute_group<NT, N, false>(st, gfr, qr, qlds, kGrp, stag, scale_log2, lane);
         }
     }
     __syncthreads();  // the ring may be reused now
@@ -607,6 +614,17 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
     const int n_blk = (n_tok + kBk - 1) / kBk;
     for (int i = threadIdx.x; i < n_blk; i += 256) blds[i] = btr[tok_begin / kBk + i];
     __syncthreads();
+    // the wave's own Q fragments, see kQInRegs (waves 2, 3 of a launch with NB tiles hold tiles NA .. NA + NB - 1)
+    bf16x8 qr[NA][kKS];
+    if constexpr (kQInRegs<NA>) {
+        const bool second = NB && (w >> 1);
+        const bf16x8 *qsrc = qlds + (second ? NA * kKS * 64 : 0) + lane;
+        const int nq = second ? NB : NA;
+#pragma unroll
+        for (int qt = 0; qt < NA; ++qt)
+#pragma unroll
+            for (int ks = 0; ks < kKS; ++ks) qr[qt][ks] = qt < nq ? qsrc[(qt * kKS + ks) * 64] : zero8();
+    }
 
     State<NA> st;
 #pragma unroll
@@ -631,11 +649,11 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
         if constexpr (KV8) {
             const uint8_t *pool8 = (const uint8_t *)pool_v;
             if (NA >= 3 && n_act >= 3)
-                wave_walk8<NA, NA>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+                wave_walk8<NA, NA>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qr, qlds, scale_log2, lane);
             else if (NA >= 2 && n_act == 2)
-                wave_walk8<NA, (NA >= 2 ? 2 : 1)>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+                wave_walk8<NA, (NA >= 2 ? 2 : 1)>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qr, qlds, scale_log2, lane);
             else
-                wave_walk8<NA, 1>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+                wave_walk8<NA, 1>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qr, qlds, scale_log2, lane);
 #pragma unroll
             for (int qt = 0; qt < NA; ++qt)
 #pragma unroll
@@ -643,11 +661,11 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
                     st.o[dt][qt][0] *= v_scale; st.o[dt][qt][1] *= v_scale; st.o[dt][qt][2] *= v_scale; st.o[dt][qt][3] *= v_scale;
                 }
         } else if (NA >= 3 && n_act >= 3)
-            wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+            wave_walk<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qr, qlds, scale_log2, lane);
         else if (NA >= 2 && n_act == 2)
-            wave_walk<NA, (NA >= 2 ? 2 : 1)>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+            wave_walk<NA, (NA >= 2 ? 2 : 1)>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qr, qlds, scale_log2, lane);
         else
-            wave_walk<NA, 1>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qlds, scale_log2, lane);
+            wave_walk<NA, 1>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, 4, c, Hkv, qr, qlds, scale_log2, lane);
         // tree merge of the four waves through LDS: (2,3) -> (0,1), then 1 -> 0
         if (w >= 2) store_to_lds<NA>(st, lds + (w - 2) * kImg, lane);
         __syncthreads();
@@ -665,14 +683,14 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
         if constexpr (KV8) {  // codes are expanded on the way into the ring: through registers
             const uint8_t *pool8 = (const uint8_t *)pool_v;
             if (role == 0)
-                shared_walk8<NA, NA>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
+                shared_walk8<NA, NA>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qr, qlds, scale_log2, lane);
             else
-                shared_walk8<NA, NB>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
+                shared_walk8<NA, NB>(st, pool8, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qr, qlds,
                                      scale_log2, lane);
         } else if (role == 0) {
-            shared_walk_dma<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds, scale_log2, lane);
+            shared_walk_dma<NA, NA>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qr, qlds, scale_log2, lane);
         } else {
-            shared_walk_dma<NA, NB>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qlds + NA * kKS * 64,
+            shared_walk_dma<NA, NB>(st, pool, blds, n_blk, n_tok, n_clean, stag, w, half, c, Hkv, ring, qr, qlds,
                                     scale_log2, lane);
         }
         if constexpr (KV8) {
@@ -696,9 +714,11 @@ __global__ void __launch_bounds__(256) k_attn_decode(const bf16_t *__restrict__ 
 }
 
 // compute_group for a group that sits in LDS as fragments (src[i * 64]: K fragments i = 0..7, then
-// V^T fragments) with the wave's Q fragments in registers (qr[qt][ks]): all tiles' S^T first, each K
-// fragment fetched once and multiplied with every tile's Q while the next ones arrive, so that no K
-// fragment is live when the V^T fragments are fetched.
+// V^T fragments) with the wave's Q fragments in registers (qr[qt][ks]).  A wave issues in order and a
+// fragment read takes a few hundred cycles to come back, so the reads are batched ahead of the MFMAs
+// that need them instead of sitting between them: the eight K fragments at the top, the eight V^T
+// fragments as soon as the S^T MFMAs are issued (into the registers the K fragments leave), so that
+// they travel while the softmax arithmetic runs and the P V MFMAs follow each other without a wait.
 template <int NT, bool tail>
 __device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *__restrict__ src, const bf16x8 (&qr)[NT][kKS],
                                                   int left, const int (&stag)[NT], float scale_log2, int lane) {
@@ -710,13 +730,16 @@ __device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *_
         f32x4 s0[NT], s1[NT];
 #pragma unroll
         for (int qt = 0; qt < NT; ++qt) { s0[qt] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[qt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        bf16x8 kf[2 * kKS];
+#pragma unroll
+        for (int i = 0; i < 2 * kKS; ++i) kf[i] = src[i * 64];
+        __builtin_amdgcn_sched_barrier(0);  // all reads first
 #pragma unroll
         for (int ks = 0; ks < kKS; ++ks) {
-            const bf16x8 k0 = src[ks * 64], k1 = src[(kKS + ks) * 64];
 #pragma unroll
             for (int qt = 0; qt < NT; ++qt) {
-                s0[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qr[qt][ks], s0[qt], 0, 0, 0);
-                s1[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qr[qt][ks], s1[qt], 0, 0, 0);
+                s0[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qr[qt][ks], s0[qt], 0, 0, 0);
+                s1[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kKS + ks], qr[qt][ks], s1[qt], 0, 0, 0);
             }
         }
 #pragma unroll
@@ -728,6 +751,10 @@ __device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *_
             }
     }
     __builtin_amdgcn_s_setprio(0);
+    bf16x8 vf[kDT];
+#pragma unroll
+    for (int dt = 0; dt < kDT; ++dt) vf[dt] = src[(2 * kKS + dt) * 64];
+    __builtin_amdgcn_sched_barrier(0);  // the reads stay ahead of the arithmetic
     bf16x8 pb[NT];
 #pragma unroll
     for (int qt = 0; qt < NT; ++qt) {
@@ -768,14 +795,13 @@ __device__ __forceinline__ void compute_group_lds(State<NT> &st, const bf16x8 *_
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int dt = 0; dt < kDT; ++dt) {
-        bf16x8 vf = src[(2 * kKS + dt) * 64];
         if (tail) {  // stale cache bytes past the end may hold anything: zero those V columns
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                if (tbase + e >= left) vf[e] = (__bf16)0.f;
+                if (tbase + e >= left) vf[dt][e] = (__bf16)0.f;
         }
 #pragma unroll
-        for (int qt = 0; qt < NT; ++qt) st.o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[qt], st.o[dt][qt], 0, 0, 0);
+        for (int qt = 0; qt < NT; ++qt) st.o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pb[qt], st.o[dt][qt], 0, 0, 0);
     }
     __builtin_amdgcn_s_setprio(0);
 }
